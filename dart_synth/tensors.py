@@ -1,0 +1,89 @@
+"""Seeded weights and hidden states, in the storage format the path reads.
+
+Recipe: projection / LM-head weights ~ N(0, 0.02); RMSNorm gains ~ 1 + 0.1 N(0, 1)
+(non-trivial so that a mis-applied gain shows up in parity); mask embeddings
+~ N(0, 0.02); hidden states ~ N(0, 1).  For the bf16 presets every tensor is
+drawn in fp32 and rounded once (round-to-nearest-even) to bf16; the returned
+arrays hold the bf16 bit patterns as uint16, and both the oracle and the HIP
+path read exactly those bits.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .configs import DraftConfig
+
+# name -> (shape builder, kind); all matrices are [out_features][in_features] row-major.
+WEIGHT_NAMES = (
+    "w_in_norm", "wq", "wk", "wv", "q_norm", "k_norm", "wo", "w_post_norm",
+    "w_gate", "w_up", "w_down", "w_final_norm", "w_lm", "mask_emb",
+)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (round-to-nearest-even), return the bits as uint16."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) to fp32 exactly."""
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _shapes(cfg: DraftConfig, max_K: int) -> dict:
+    return {
+        "w_in_norm": (cfg.d,), "wq": (cfg.q_dim, cfg.d), "wk": (cfg.kv_dim, cfg.d),
+        "wv": (cfg.kv_dim, cfg.d), "q_norm": (cfg.head_dim,), "k_norm": (cfg.head_dim,),
+        "wo": (cfg.d, cfg.q_dim), "w_post_norm": (cfg.d,),
+        "w_gate": (cfg.ffn, cfg.d), "w_up": (cfg.ffn, cfg.d), "w_down": (cfg.d, cfg.ffn),
+        "w_final_norm": (cfg.d,), "w_lm": (cfg.vocab, cfg.d),
+        "mask_emb": (max(max_K - 1, 1), cfg.d),
+    }
+
+
+def _draw(rng: np.random.Generator, shape, kind: str, store_bf16: bool) -> np.ndarray:
+    """Draw one tensor in row chunks (bounded temporary memory for the LM head)."""
+    shape = tuple(shape)
+    rows = shape[0]
+    cols = int(np.prod(shape[1:])) if len(shape) > 1 else 1
+    out = np.empty(shape, dtype=np.uint16 if store_bf16 else np.float32)
+    flat = out.reshape(rows, cols)
+    step = max(1, (1 << 24) // cols)
+    for r0 in range(0, rows, step):
+        r1 = min(rows, r0 + step)
+        z = rng.standard_normal((r1 - r0, cols), dtype=np.float32)
+        if kind == "gain":
+            z = np.float32(1.0) + np.float32(0.1) * z
+        elif kind == "small":
+            z = np.float32(0.02) * z
+        flat[r0:r1] = f32_to_bf16_bits(z) if store_bf16 else z
+    return out
+
+
+def make_weights(cfg: DraftConfig, seed: int, max_K: int | None = None) -> dict:
+    """All draft-layer tensors for one preset; uint16 (bf16 bits) or float32 arrays."""
+    max_K = cfg.K if max_K is None else max_K
+    store_bf16 = cfg.dtype == "bf16"
+    out = {}
+    for idx, (name, shape) in enumerate(_shapes(cfg, max_K).items()):
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 101, idx])))
+        kind = "gain" if name in ("w_in_norm", "q_norm", "k_norm", "w_post_norm",
+                                  "w_final_norm") else "small"
+        out[name] = _draw(rng, shape, kind, store_bf16)
+    return out
+
+
+def make_hidden(cfg: DraftConfig, seed: int, n: int | None = None) -> np.ndarray:
+    """Target hidden states of an n-token prefix, N(0, 1), [n][d]."""
+    n = cfg.ctx if n is None else n
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 202])))
+    return _draw(rng, (n, cfg.d), "unit", cfg.dtype == "bf16")
+
+
+def make_ragged_lengths(cfg: DraftConfig, seed: int) -> np.ndarray:
+    """Batch of context lengths, uniform on [ctx_min, ctx] (ragged batched preset)."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 303])))
+    lo = cfg.ctx_min if cfg.ctx_min > 0 else cfg.ctx
+    return rng.integers(lo, cfg.ctx + 1, size=cfg.batch).astype(np.int32)

@@ -1,0 +1,47 @@
+"""Oracle: the N-gram continuity model g_n (Alg. 1 "s_ng", App. C.2, App. D).
+
+A context (the previous N-1 tokens) maps to the list of successors seen after it,
+with counts.  One context lookup serves every candidate of that context (the
+single-traversal retrieval of App. C.2).  The score of candidate t is
+
+    s_ng = log(Pr(t | context) + eps),   Pr = count(context, t) / sum of the
+                                              context's stored counts,
+
+and Pr = 0 (so s_ng = log eps) when the context or the successor is absent; there
+is no back-off to shorter contexts.  The value is computed in fp64, rounded once
+to fp32 and clamped to <= 0.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+
+class NgramModel:
+    def __init__(self, n_gram: int, keys: np.ndarray, succ_ids: np.ndarray,
+                 succ_counts: np.ndarray, eps: float):
+        self.n_gram = int(n_gram)
+        self.eps = float(np.float32(eps))
+        self.succ_ids = succ_ids
+        self.succ_counts = succ_counts
+        self.row_of = {tuple(int(t) for t in key): r for r, key in enumerate(keys)}
+        self.miss = self._score(0.0)
+
+    def _score(self, pr: float) -> np.float32:
+        return min(np.float32(0.0), np.float32(math.log(pr + self.eps)))
+
+    def lookup(self, context) -> dict | None:
+        """All successors of a context -> {token: s_ng}; None if the context is unseen."""
+        r = self.row_of.get(tuple(int(t) for t in context))
+        if r is None:
+            return None
+        counts = self.succ_counts[r]
+        total = int(counts.astype(np.int64).sum())
+        return {int(t): self._score(int(c) / total)
+                for t, c in zip(self.succ_ids[r], counts) if c > 0}
+
+    def score(self, row: dict | None, token: int) -> np.float32:
+        if row is None:
+            return self.miss
+        return row.get(int(token), self.miss)
