@@ -1,0 +1,189 @@
+/*
+ * dart.h -- C ABI of the MI355X (gfx950) implementation of DART's drafting step.
+ *
+ * The drafting step (paper Sec. 3.2, Sec. 4, Alg. 1, App. C/D) is
+ *   1. one forward pass of the single-layer draft model over
+ *      [z_1..z_n, MASK x (K-1)] -> K rows of vocabulary logits
+ *      (row 0 from the last prefix position, rows 1..K-1 from the mask positions);
+ *   2. per-position top-k of each row with s_logit = log(softmax(l) + eps);
+ *   3. continuity-aware tree pruning: K levels of beam expansion scored by
+ *      Combine(s_logit, s_ng), every expansion kept in the global tree, the
+ *      theta best nodes returned as a token tree for tree-attention verification.
+ *
+ * Conventions
+ *   - All matrices are row-major [out_features][in_features]; vectors are dense.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers
+ *     are ordinary host memory.  The library never frees caller memory.
+ *   - The three hot calls (dart_draft_forward*, dart_topk, dart_tree_prune) only
+ *     enqueue kernels on the given HIP stream (hipStream_t passed as void*, NULL =
+ *     default stream).  They do not synchronise and do not allocate: every
+ *     workspace is sized at dart_create / dart_ngram_create.
+ *   - Every call returns a status; nothing aborts or throws across the ABI.  On
+ *     DART_ERR_ARG / DART_ERR_SHAPE / DART_ERR_STATE nothing has been launched and
+ *     the outputs are untouched.
+ *   - A dart_ctx must not be used from two streams at once (calls share its
+ *     workspaces and K/V buffers).
+ */
+#ifndef DART_H
+#define DART_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dart_ctx dart_ctx;       /* device weights, draft K/V buffers, workspaces */
+typedef struct dart_ngram dart_ngram;   /* device-resident N-gram successor table */
+
+typedef enum {
+  DART_OK = 0,
+  DART_ERR_ARG = 1,    /* NULL pointer or value out of its documented range */
+  DART_ERR_SHAPE = 2,  /* sizes inconsistent with the context's configuration */
+  DART_ERR_OOM = 3,    /* host or device allocation failed (create calls only) */
+  DART_ERR_HIP = 4,    /* a HIP runtime call failed */
+  DART_ERR_STATE = 5   /* call sequence invalid (e.g. n_cached beyond what is cached) */
+} dart_status;
+
+enum { DART_F32 = 0, DART_BF16 = 1 };
+
+/* Hard limits of this build (kernels keep per-level state in LDS / registers). */
+enum {
+  DART_MAX_K = 16,          /* draft length (logit rows per sequence) */
+  DART_MAX_TOPK = 64,       /* candidates per position */
+  DART_MAX_BEAM = 64,       /* beam width w */
+  DART_MAX_BUDGET = 128,    /* tree nodes including the root */
+  DART_MAX_LEVEL_NODES = 4096  /* beam_w * k, the expansions of one level */
+};
+
+/* Shapes of the draft layer: one pre-norm decoder layer "aligned with the target
+ * model" (App. B): RMSNorm, grouped-query attention with rotary positions
+ * (half-split pairing), optional per-head RMSNorm of q and k, SwiGLU, final
+ * RMSNorm, LM head.  dtype is the storage type of weights, hidden states and the
+ * K/V buffers; accumulation is always fp32 and logits are fp32. */
+typedef struct {
+  int32_t d, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  int32_t max_ctx;     /* longest prefix n */
+  int32_t max_K;       /* <= DART_MAX_K; mask_emb has max_K-1 rows */
+  int32_t max_batch;   /* number of independent sequences (K/V buffer slots) */
+  int32_t dtype;       /* DART_F32 | DART_BF16 */
+  int32_t qk_norm;     /* 0/1 */
+  float rms_eps;
+  float rope_base;
+} dart_config;
+
+/* HOST pointers, element type per dart_config.dtype (bf16 = raw 16-bit patterns).
+ * wq [Hq*hd][d], wk/wv [Hkv*hd][d], wo [d][Hq*hd], w_gate/w_up [ffn][d],
+ * w_down [d][ffn], w_lm [vocab][d], norm gains [d] (q_norm/k_norm [hd], may be
+ * NULL when qk_norm == 0), mask_emb [max_K-1][d] (the trainable <MASK>
+ * representation, App. B; may be NULL when max_K == 1).
+ * dart_create copies (and re-tiles) everything; the caller keeps its arrays. */
+typedef struct {
+  const void *w_in_norm, *wq, *wk, *wv, *q_norm, *k_norm, *wo, *w_post_norm;
+  const void *w_gate, *w_up, *w_down, *w_final_norm, *w_lm, *mask_emb;
+} dart_weights;
+
+/* Pruning hyper-parameters (App. D): k candidates per level, beam width w,
+ * budget = theta + 1 nodes (the root, i.e. the already sampled token t_{n+1}, is
+ * node 0), w_ng (0.5), logit_decay (0.9, w_logit = decay^level) and level_pow (0.7,
+ * w_level = (level+1)^-pow), level 0-based. */
+typedef struct {
+  int32_t k, beam_w, budget;
+  float w_ng, logit_decay, level_pow;
+} dart_prune_params;
+
+const char *dart_status_str(dart_status s);
+
+/* Build a context on the current HIP device.  Errors: ARG (NULL, non-positive
+ * sizes, max_K > DART_MAX_K, head_dim not 64 or 128, n_q_heads not a multiple of
+ * n_kv_heads, bf16 with d, Hq*hd or ffn not a multiple of 32, or d > 5120; fp32 with d or ffn
+ * not a multiple of 4; more than 8 query heads per K/V head), OOM, HIP. */
+dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx **out);
+void dart_destroy(dart_ctx *ctx);
+
+/* Forget the cached draft K/V rows of sequence slot `seq`. */
+dart_status dart_reset(dart_ctx *ctx, int seq);
+
+/* Draft forward for one sequence (Sec. 3.2).
+ *   hidden      device [ctx_len][d], prefix representation z_1..z_n in cfg.dtype;
+ *               only rows [n_cached, ctx_len) are read.
+ *   n_cached    number of leading prefix rows whose draft K/V are already in slot
+ *               `seq` from earlier calls with the same rows (0 = stateless call).
+ *               The draft is a single layer, so K/V of a row depend on that row
+ *               alone and results do not depend on n_cached.
+ *   K           1..max_K logit rows.
+ *   logits_out  device [K][vocab] fp32.
+ * Row j of logits_out is the draft distribution of the (j+1)-th future token:
+ * row 0 is read at the last prefix position, rows 1..K-1 at the mask positions.
+ * Errors: ARG (NULL, K, seq out of range, ctx_len < 1), SHAPE (ctx_len > max_ctx),
+ * STATE (n_cached > ctx_len-1 or > rows cached in the slot), HIP. */
+dart_status dart_draft_forward(dart_ctx *ctx, int seq, const void *hidden, int ctx_len,
+                               int n_cached, int K, float *logits_out, void *stream);
+
+/* Same for `batch` sequences in slots 0..batch-1 (ragged lengths).
+ *   hidden      HOST array of `batch` device pointers, each [ctx_len[b]][d]
+ *   ctx_len, n_cached   HOST arrays [batch]
+ *   logits_out  device [batch][K][vocab] fp32 */
+dart_status dart_draft_forward_batched(dart_ctx *ctx, int batch, const void *const *hidden,
+                                       const int32_t *ctx_len, const int32_t *n_cached, int K,
+                                       float *logits_out, void *stream);
+
+/* Per-row top-k with log-softmax scores (Alg. 1, App. D "s_logit").
+ *   logits      device [rows][vocab] fp32 (finite values), rows <= max_batch*max_K
+ *   ids_out     device [rows][k] int32, by (logit descending, token id ascending)
+ *   scores_out  device [rows][k] fp32 = min(0, log(softmax(l)_t + eps))
+ * Errors: ARG (NULL, k < 1, k > min(vocab, DART_MAX_TOPK), rows < 1),
+ * SHAPE (vocab > cfg.vocab, rows too large), HIP. */
+dart_status dart_topk(dart_ctx *ctx, const float *logits, int rows, int vocab, int k, float eps,
+                      int32_t *ids_out, float *scores_out, void *stream);
+
+/* Build the device N-gram table from raw counts (App. C): context = previous
+ * n_gram-1 tokens -> up to succ_per_key successors.  HOST inputs:
+ *   keys        [n_keys][n_gram-1] int32, oldest token first, rows distinct
+ *   succ_ids    [n_keys][succ_per_key] int32, distinct within a row
+ *   succ_counts [n_keys][succ_per_key] int32, 0 marks an unused slot
+ * Stored score of a successor: min(0, log(count / sum(row counts) + eps)) rounded
+ * to fp32; an absent context or successor scores log(eps).  No back-off.
+ * Errors: ARG (NULL, n_gram not 2 or 3, succ_per_key not in 1..64, negative ids),
+ * OOM, HIP. */
+dart_status dart_ngram_create(int n_gram, int64_t n_keys, int succ_per_key, const int32_t *keys,
+                              const int32_t *succ_ids, const int32_t *succ_counts, float eps,
+                              dart_ngram **out);
+void dart_ngram_destroy(dart_ngram *t);
+
+/* Continuity-aware tree pruning (Alg. 1, App. D) for `batch` independent
+ * sequences, one workgroup each.
+ *   ids, scores  device [batch][K][k]: candidates per level, best first
+ *                (dart_topk output with the same k)
+ *   ctx_tail     device [batch][n_gram-1] int32: last real tokens, the root
+ *                t_{n+1} last
+ *   tokens_out   device [batch][budget] int32; node 0 = root, then level-major,
+ *                within a level by (score desc, creation order); -1 beyond n_nodes
+ *   parents_out  device [batch][budget] int32 index of the parent node (-1: root
+ *                and unused slots); parents precede children
+ *   mask_out     device [batch][budget][budget] uint8, mask[i][j] = 1 iff j == i
+ *                or j is an ancestor of i (tree-attention mask); 0 elsewhere
+ *   n_nodes_out  device [batch] int32 = 1 + min(budget-1, total expansions)
+ * Scoring arithmetic is fp32 with one rounding per operation in the order
+ * ((w_logit*s_logit) + (w_ng*s_ng)) * w_level, then parent + increment, so trees
+ * are reproducible bit for bit.  Ties: beam cut by (score desc, creation asc),
+ * global cut by (score desc, level asc, creation asc).
+ * Errors: ARG (NULL, K not in 1..DART_MAX_K, k, beam_w, budget out of range,
+ * beam_w*k > DART_MAX_LEVEL_NODES, batch < 1), HIP. */
+dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, int K,
+                            const int32_t *ctx_tail, const dart_ngram *table,
+                            const dart_prune_params *params, int32_t *tokens_out,
+                            int32_t *parents_out, uint8_t *mask_out, int32_t *n_nodes_out,
+                            void *stream);
+
+/* Diagnostic (tests only): copy a named fp32 workspace of the last forward call to host
+ * memory after synchronising the device.  Names: "xn" (normed layer input), "resid", "qkv",
+ * "att_out" (attention output), "y" (after attention residual), "yn", "hmid" (SwiGLU
+ * product), "u" (after MLP residual).  Buffers hold 16 rows.  Returns the number of floats
+ * copied (at most max_count) or -1 on error. */
+int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_t max_count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DART_H */

@@ -1,0 +1,508 @@
+// C ABI of the DART drafting step: context creation (weight upload and re-tiling),
+// orchestration of the draft forward, top-k, N-gram table build and tree pruning.
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "dart_internal.h"
+
+using namespace dart;
+
+#define HIP_TRY(expr)                    \
+  do {                                   \
+    hipError_t e_ = (expr);              \
+    if (e_ != hipSuccess) return e_;     \
+  } while (0)
+
+namespace {
+
+size_t elem_size(int dtype) { return dtype == DART_BF16 ? 2 : 4; }
+
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+hipError_t upload(const void *host, size_t bytes, void **dev) {
+  HIP_TRY(hipMalloc(dev, bytes));
+  return hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice);
+}
+
+// A logical matrix given as a list of row pointers (rows may come from several tensors).
+struct RowSource {
+  std::vector<const uint8_t *> rows;
+  int Kd;
+};
+
+// fp32: plain row-major copy.
+hipError_t upload_f32(const RowSource &src, DeviceMatrix *out) {
+  const int N = (int)src.rows.size();
+  std::vector<float> host((size_t)N * src.Kd);
+  for (int r = 0; r < N; ++r) memcpy(&host[(size_t)r * src.Kd], src.rows[r], (size_t)src.Kd * 4);
+  out->N = out->n_real = N;
+  out->Kd = src.Kd;
+  return upload(host.data(), host.size() * 4, &out->data);
+}
+
+// bf16: re-tile for v_mfma_f32_16x16x32_bf16.  Tile (strip s, k-step t) holds output rows
+// 16s..16s+15 and inputs 32t..32t+31; lane l of the consuming wavefront reads the 16 bytes
+// at tile + 16*l and must find inputs 32t + 8*(l/16) .. +7 of row 16s + l%16 there (the A
+// operand layout of the instruction).  Rows beyond N are zero.
+hipError_t upload_bf16_tiles(const RowSource &src, DeviceMatrix *out) {
+  const int N = (int)src.rows.size();
+  const int strips = (N + 15) / 16, KT = src.Kd / 32;
+  const size_t total = (size_t)strips * KT * 512;          // bf16 elements
+  uint16_t *host = (uint16_t *)malloc(total * 2);
+  if (!host) return hipErrorOutOfMemory;
+  auto work = [&](int s0, int s1) {
+    for (int s = s0; s < s1; ++s)
+      for (int t = 0; t < KT; ++t) {
+        uint16_t *tile = host + ((size_t)s * KT + t) * 512;
+        for (int l = 0; l < 64; ++l) {
+          const int row = s * 16 + (l & 15);
+          if (row < N)
+            memcpy(tile + l * 8, src.rows[row] + ((size_t)t * 32 + 8 * (l >> 4)) * 2, 16);
+          else
+            memset(tile + l * 8, 0, 16);
+        }
+      }
+  };
+  const int nthr = 8;
+  std::vector<std::thread> pool;
+  for (int i = 0; i < nthr; ++i)
+    pool.emplace_back(work, (int)((int64_t)strips * i / nthr), (int)((int64_t)strips * (i + 1) / nthr));
+  for (auto &th : pool) th.join();
+  out->N = strips * 16;
+  out->n_real = N;
+  out->Kd = src.Kd;
+  hipError_t e = upload(host, total * 2, &out->data);
+  free(host);
+  return e;
+}
+
+void add_rows(RowSource &src, const void *base, int rows, int Kd, size_t es) {
+  for (int r = 0; r < rows; ++r) src.rows.push_back((const uint8_t *)base + (size_t)r * Kd * es);
+}
+
+hipError_t upload_matrix(int dtype, const RowSource &src, DeviceMatrix *out) {
+  return dtype == DART_BF16 ? upload_bf16_tiles(src, out) : upload_f32(src, out);
+}
+
+template <typename T>
+hipError_t dev_alloc(T **p, size_t count, bool zero = false) {
+  HIP_TRY(hipMalloc((void **)p, count * sizeof(T)));
+  if (zero) HIP_TRY(hipMemset(*p, 0, count * sizeof(T)));
+  return hipSuccess;
+}
+
+hipError_t build(dart_ctx *c, const dart_weights *w) {
+  const dart_config &g = c->cfg;
+  const size_t es = elem_size(g.dtype);
+  const int d = g.d, F = g.ffn, hd = g.head_dim;
+
+  RowSource qkv{{}, d};
+  add_rows(qkv, w->wq, c->q_dim, d, es);
+  add_rows(qkv, w->wk, c->kv_dim, d, es);
+  add_rows(qkv, w->wv, c->kv_dim, d, es);
+  HIP_TRY(upload_matrix(g.dtype, qkv, &c->wqkv));
+
+  RowSource wo{{}, c->q_dim};
+  add_rows(wo, w->wo, d, c->q_dim, es);
+  HIP_TRY(upload_matrix(g.dtype, wo, &c->wo));
+
+  // gate/up: fp32 keeps [gate rows | up rows]; bf16 interleaves groups of four output rows
+  // (gate f, gate f+1, up f, up f+1) so that one MFMA lane ends up holding gate/up pairs.
+  RowSource gu{{}, d};
+  if (g.dtype == DART_BF16) {
+    for (int f = 0; f < F; f += 2) {
+      gu.rows.push_back((const uint8_t *)w->w_gate + (size_t)f * d * es);
+      gu.rows.push_back((const uint8_t *)w->w_gate + (size_t)(f + 1) * d * es);
+      gu.rows.push_back((const uint8_t *)w->w_up + (size_t)f * d * es);
+      gu.rows.push_back((const uint8_t *)w->w_up + (size_t)(f + 1) * d * es);
+    }
+  } else {
+    add_rows(gu, w->w_gate, F, d, es);
+    add_rows(gu, w->w_up, F, d, es);
+  }
+  HIP_TRY(upload_matrix(g.dtype, gu, &c->wgu));
+
+  RowSource down{{}, F};
+  add_rows(down, w->w_down, d, F, es);
+  HIP_TRY(upload_matrix(g.dtype, down, &c->wdown));
+
+  RowSource lm{{}, d};
+  add_rows(lm, w->w_lm, g.vocab, d, es);
+  HIP_TRY(upload_matrix(g.dtype, lm, &c->wlm));
+
+  HIP_TRY(upload(w->w_in_norm, d * es, &c->g_in));
+  HIP_TRY(upload(w->w_post_norm, d * es, &c->g_post));
+  HIP_TRY(upload(w->w_final_norm, d * es, &c->g_final));
+  if (g.qk_norm) {
+    HIP_TRY(upload(w->q_norm, hd * es, &c->g_q));
+    HIP_TRY(upload(w->k_norm, hd * es, &c->g_k));
+  }
+  if (g.max_K > 1) HIP_TRY(upload(w->mask_emb, (size_t)(g.max_K - 1) * d * es, &c->mask_emb));
+
+  // rotary tables: angle = position * base^(-2i/hd), evaluated in double
+  const int half = hd / 2;
+  std::vector<float> cs((size_t)c->t_cap * half), sn((size_t)c->t_cap * half);
+  for (int i = 0; i < half; ++i) {
+    const double inv = std::pow((double)g.rope_base, -2.0 * i / hd);
+    for (int p = 0; p < c->t_cap; ++p) {
+      cs[(size_t)p * half + i] = (float)std::cos(p * inv);
+      sn[(size_t)p * half + i] = (float)std::sin(p * inv);
+    }
+  }
+  HIP_TRY(upload(cs.data(), cs.size() * 4, (void **)&c->rope_cos));
+  HIP_TRY(upload(sn.data(), sn.size() * 4, (void **)&c->rope_sin));
+
+  // K/V buffers start zeroed: rows never written must stay finite because the attention
+  // kernel multiplies masked keys by probability zero
+  const size_t kv_bytes = (size_t)g.max_batch * g.n_kv_heads * c->t_cap * hd * es;
+  HIP_TRY(hipMalloc(&c->kbuf, kv_bytes));
+  HIP_TRY(hipMemset(c->kbuf, 0, kv_bytes));
+  HIP_TRY(hipMalloc(&c->vbuf, kv_bytes));
+  HIP_TRY(hipMemset(c->vbuf, 0, kv_bytes));
+
+  const int R = DART_SKINNY_ROWS;
+  c->max_chunks = 1;
+  if (g.dtype == DART_BF16) {
+    const int dims[3] = {d, c->q_dim, F};
+    for (int v : dims) c->max_chunks = std::max(c->max_chunks, gemv_bf16_chunks(v));
+  }
+  c->max_splits = (c->t_cap + 127) / 128;
+  const size_t wide = (size_t)std::max(std::max(d, 2 * F), c->qkv_dim);
+  HIP_TRY(dev_alloc(&c->xn, (size_t)R * d));
+  HIP_TRY(dev_alloc(&c->resid, (size_t)R * d));
+  HIP_TRY(dev_alloc(&c->qkv, (size_t)c->max_chunks * R * c->qkv_dim));
+  HIP_TRY(hipMalloc(&c->qrot, (size_t)R * c->q_dim * 4));
+  HIP_TRY(dev_alloc(&c->att_part, (size_t)R * g.n_q_heads * c->max_splits * hd));
+  HIP_TRY(dev_alloc(&c->att_ml, (size_t)R * g.n_q_heads * c->max_splits * 2));
+  HIP_TRY(dev_alloc(&c->att_out, (size_t)R * c->q_dim));
+  HIP_TRY(dev_alloc(&c->proj, (size_t)c->max_chunks * R * wide));
+  HIP_TRY(dev_alloc(&c->y, (size_t)R * d));
+  HIP_TRY(dev_alloc(&c->yn, (size_t)R * d));
+  HIP_TRY(dev_alloc(&c->hmid, (size_t)R * F));
+  HIP_TRY(dev_alloc(&c->u, (size_t)R * d));
+
+  c->max_rows = g.max_batch * g.max_K;
+  c->topk_chunks_max = (g.vocab + 4095) / 4096;
+  HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
+  HIP_TRY(dev_alloc(&c->topk_ms, (size_t)c->max_rows * c->topk_chunks_max * 2));
+  return hipSuccess;
+}
+
+dart_status from_hip(hipError_t e) {
+  if (e == hipSuccess) return DART_OK;
+  return e == hipErrorOutOfMemory ? DART_ERR_OOM : DART_ERR_HIP;
+}
+
+// Projection of M rows of X (fp32 [M][W.Kd]) through output rows [row0, row0+nrows) of W.
+hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows, const float *X,
+                   int M, float *out, int out_stride, size_t chunk_stride, int *chunks,
+                   hipStream_t st) {
+  if (c->cfg.dtype == DART_BF16)
+    return launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride,
+                            chunks, st);
+  *chunks = 1;
+  return launch_gemv_f32(W, row0, nrows, X, M, out, out_stride, st);
+}
+
+// One pass of rows [pos0, pos0+M) through norm + QKV projection + K/V append; the last Kq
+// rows are query rows.
+hipError_t qkv_pass(dart_ctx *c, int seq, const void *hidden, int n, int pos0, int M, int Kq,
+                    hipStream_t st) {
+  const dart_config &g = c->cfg;
+  HIP_TRY(launch_rmsnorm_gather(g.dtype, hidden, c->mask_emb, c->g_in, n, pos0, M, g.d, g.rms_eps,
+                                c->xn, c->resid, M - Kq, st));
+  const size_t cs = (size_t)DART_SKINNY_ROWS * c->qkv_dim;
+  int chunks = 1;
+  if (Kq > 0) {
+    HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, &chunks, st));
+  } else {   // K and V rows only
+    HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn, M, c->qkv + c->q_dim, c->qkv_dim,
+                    cs, &chunks, st));
+  }
+  return launch_qkv_post(c, seq, c->qkv, chunks, cs, M, Kq, pos0, st);
+}
+
+hipError_t forward_one(dart_ctx *c, int seq, const void *hidden, int n, int n_cached, int K,
+                       float *logits, hipStream_t st) {
+  const dart_config &g = c->cfg;
+  const int R = DART_SKINNY_ROWS;
+  int pos0 = n_cached;
+  if ((n - n_cached) + K - 1 > R) {
+    // bulk K/V append of the prefix rows that are not query rows
+    for (int r0 = n_cached; r0 < n - 1; r0 += R)
+      HIP_TRY(qkv_pass(c, seq, hidden, n, r0, std::min(R, n - 1 - r0), 0, st));
+    pos0 = n - 1;
+  }
+  const int M = n + K - 1 - pos0;
+  HIP_TRY(qkv_pass(c, seq, hidden, n, pos0, M, K, st));
+  HIP_TRY(launch_attention(c, seq, n, K, st));
+
+  int chunks = 1;
+  size_t cs = (size_t)R * g.d;
+  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, K, c->proj, g.d, cs, &chunks, st));
+  HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, K, g.d,
+                            g.rms_eps, c->y, c->yn, st));
+  cs = (size_t)R * 2 * g.ffn;
+  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, K, c->proj, 2 * g.ffn, cs, &chunks, st));
+  HIP_TRY(launch_swiglu(c->proj, chunks, cs, K, g.ffn, g.dtype == DART_BF16, c->hmid, st));
+  cs = (size_t)R * g.d;
+  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, K, c->proj, g.d, cs, &chunks, st));
+  HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, K, g.d, g.rms_eps,
+                            c->u, c->yn, st));
+  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, K, logits, g.vocab, 0, &chunks, st));
+  return hipSuccess;
+}
+
+dart_status check_forward_args(const dart_ctx *c, int seq, const void *hidden, int n, int n_cached,
+                               int K, const float *logits) {
+  if (!c || !hidden || !logits) return DART_ERR_ARG;
+  if (seq < 0 || seq >= c->cfg.max_batch || K < 1 || K > c->cfg.max_K || n < 1 || n_cached < 0)
+    return DART_ERR_ARG;
+  if (n > c->cfg.max_ctx) return DART_ERR_SHAPE;
+  if (n_cached > n - 1 || n_cached > c->cached_rows[seq]) return DART_ERR_STATE;
+  return DART_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dart_status_str(dart_status s) {
+  switch (s) {
+    case DART_OK: return "ok";
+    case DART_ERR_ARG: return "invalid argument";
+    case DART_ERR_SHAPE: return "shape mismatch";
+    case DART_ERR_OOM: return "out of memory";
+    case DART_ERR_HIP: return "HIP runtime error";
+    case DART_ERR_STATE: return "invalid call sequence";
+  }
+  return "unknown status";
+}
+
+dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx **out) {
+  if (!cfg || !w || !out) return DART_ERR_ARG;
+  *out = nullptr;
+  const dart_config &g = *cfg;
+  if (g.d < 1 || g.n_q_heads < 1 || g.n_kv_heads < 1 || g.ffn < 1 || g.vocab < 1 || g.max_ctx < 1 ||
+      g.max_K < 1 || g.max_K > DART_MAX_K || g.max_batch < 1)
+    return DART_ERR_ARG;
+  if (g.head_dim != 64 && g.head_dim != 128) return DART_ERR_ARG;
+  if (g.n_q_heads % g.n_kv_heads != 0 || g.n_q_heads / g.n_kv_heads > 8) return DART_ERR_ARG;
+  if (g.dtype != DART_F32 && g.dtype != DART_BF16) return DART_ERR_ARG;
+  const int q_dim = g.n_q_heads * g.head_dim;
+  if (g.dtype == DART_BF16) {
+    if (g.d % 32 || q_dim % 32 || g.ffn % 32) return DART_ERR_ARG;
+    if (gemv_bf16_chunks(g.d) != 1) return DART_ERR_ARG;   // LM head writes caller memory in one pass
+  } else if (g.d % 4 || g.ffn % 4) {
+    return DART_ERR_ARG;
+  }
+  if (!w->w_in_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_post_norm || !w->w_gate ||
+      !w->w_up || !w->w_down || !w->w_final_norm || !w->w_lm)
+    return DART_ERR_ARG;
+  if (g.qk_norm && (!w->q_norm || !w->k_norm)) return DART_ERR_ARG;
+  if (g.max_K > 1 && !w->mask_emb) return DART_ERR_ARG;
+
+  dart_ctx *c = new (std::nothrow) dart_ctx();
+  if (!c) return DART_ERR_OOM;
+  c->cfg = g;
+  c->q_dim = q_dim;
+  c->kv_dim = g.n_kv_heads * g.head_dim;
+  c->qkv_dim = c->q_dim + 2 * c->kv_dim;
+  c->t_cap = round_up(g.max_ctx + g.max_K - 1, 64);
+  c->cached_rows = (int *)calloc(g.max_batch, sizeof(int));
+  if (!c->cached_rows) {
+    delete c;
+    return DART_ERR_OOM;
+  }
+  hipError_t e = build(c, w);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    dart_destroy(c);
+    return from_hip(e);
+  }
+  *out = c;
+  return DART_OK;
+}
+
+void dart_destroy(dart_ctx *c) {
+  if (!c) return;
+  void *bufs[] = {c->wqkv.data, c->wo.data, c->wgu.data, c->wdown.data, c->wlm.data, c->g_in,
+                  c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
+                  c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
+                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms};
+  for (void *p : bufs)
+    if (p) (void)hipFree(p);
+  free(c->cached_rows);
+  delete c;
+}
+
+dart_status dart_reset(dart_ctx *c, int seq) {
+  if (!c || seq < 0 || seq >= c->cfg.max_batch) return DART_ERR_ARG;
+  c->cached_rows[seq] = 0;
+  return DART_OK;
+}
+
+dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx_len, int n_cached,
+                               int K, float *logits_out, void *stream) {
+  dart_status s = check_forward_args(c, seq, hidden, ctx_len, n_cached, K, logits_out);
+  if (s != DART_OK) return s;
+  hipError_t e = forward_one(c, seq, hidden, ctx_len, n_cached, K, logits_out, (hipStream_t)stream);
+  if (e != hipSuccess) return from_hip(e);
+  c->cached_rows[seq] = ctx_len;
+  return DART_OK;
+}
+
+dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const *hidden,
+                                       const int32_t *ctx_len, const int32_t *n_cached, int K,
+                                       float *logits_out, void *stream) {
+  if (!c || !hidden || !ctx_len || !n_cached || !logits_out) return DART_ERR_ARG;
+  if (batch < 1 || batch > c->cfg.max_batch) return DART_ERR_ARG;
+  for (int b = 0; b < batch; ++b) {
+    dart_status s = check_forward_args(c, b, hidden[b], ctx_len[b], n_cached[b], K, logits_out);
+    if (s != DART_OK) return s;
+  }
+  for (int b = 0; b < batch; ++b) {
+    hipError_t e = forward_one(c, b, hidden[b], ctx_len[b], n_cached[b], K,
+                               logits_out + (size_t)b * K * c->cfg.vocab, (hipStream_t)stream);
+    if (e != hipSuccess) return from_hip(e);
+    c->cached_rows[b] = ctx_len[b];
+  }
+  return DART_OK;
+}
+
+dart_status dart_topk(dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
+                      int32_t *ids_out, float *scores_out, void *stream) {
+  if (!c || !logits || !ids_out || !scores_out) return DART_ERR_ARG;
+  if (rows < 1 || vocab < 1 || k < 1 || k > DART_MAX_TOPK || k > vocab) return DART_ERR_ARG;
+  if (vocab > c->cfg.vocab || rows > c->max_rows) return DART_ERR_SHAPE;
+  return from_hip(launch_topk(c, logits, rows, vocab, k, eps, ids_out, scores_out,
+                              (hipStream_t)stream));
+}
+
+dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *keys,
+                              const int32_t *succ_ids, const int32_t *succ_counts, float eps,
+                              dart_ngram **out) {
+  if (!out) return DART_ERR_ARG;
+  *out = nullptr;
+  if ((n_gram != 2 && n_gram != 3) || n_keys < 0 || S < 1 || S > 64) return DART_ERR_ARG;
+  if (n_keys > 0 && (!keys || !succ_ids || !succ_counts)) return DART_ERR_ARG;
+  if (n_keys > ((int64_t)1 << 30)) return DART_ERR_ARG;
+  const int ctx_len = n_gram - 1;
+  for (int64_t i = 0; i < n_keys * ctx_len; ++i)
+    if (keys[i] < 0) return DART_ERR_ARG;
+
+  uint64_t n_slots = 16;
+  while (n_slots < (uint64_t)n_keys * 2) n_slots <<= 1;
+  std::vector<uint64_t> slot_keys(n_slots, ~(uint64_t)0);
+  std::vector<int32_t> slot_rows(n_slots, -1);
+  for (int64_t r = 0; r < n_keys; ++r) {
+    const uint64_t packed = ctx_len == 2 ? ((uint64_t)(uint32_t)keys[2 * r] << 32) |
+                                               (uint32_t)keys[2 * r + 1]
+                                         : (uint64_t)(uint32_t)keys[r];
+    uint64_t h = mix64(packed) & (n_slots - 1);
+    while (slot_keys[h] != ~(uint64_t)0) {
+      if (slot_keys[h] == packed) return DART_ERR_ARG;   // duplicate context
+      h = (h + 1) & (n_slots - 1);
+    }
+    slot_keys[h] = packed;
+    slot_rows[h] = (int32_t)r;
+  }
+  // s_ng = log(Pr + eps), Pr = count / sum of the row's counts (App. D); fp64 then one rounding
+  const double eps_d = (double)eps;
+  const float miss = std::fmin(0.0f, (float)std::log(eps_d));
+  const size_t cells = (size_t)std::max<int64_t>(n_keys, 1) * S;
+  std::vector<int32_t> ids(cells, -1);
+  std::vector<float> logp(cells, miss);
+  for (int64_t r = 0; r < n_keys; ++r) {
+    int64_t total = 0;
+    for (int j = 0; j < S; ++j) {
+      if (succ_counts[r * S + j] < 0) return DART_ERR_ARG;
+      total += succ_counts[r * S + j];
+    }
+    for (int j = 0; j < S; ++j) {
+      const int32_t cnt = succ_counts[r * S + j];
+      if (cnt <= 0) continue;
+      ids[r * S + j] = succ_ids[r * S + j];
+      logp[r * S + j] = std::fmin(0.0f, (float)std::log((double)cnt / (double)total + eps_d));
+    }
+  }
+  dart_ngram *t = new (std::nothrow) dart_ngram();
+  if (!t) return DART_ERR_OOM;
+  hipError_t e = upload(slot_keys.data(), n_slots * 8, &t->slot_keys);
+  if (e == hipSuccess) e = upload(slot_rows.data(), n_slots * 4, &t->slot_rows);
+  if (e == hipSuccess) e = upload(ids.data(), cells * 4, &t->succ_ids);
+  if (e == hipSuccess) e = upload(logp.data(), cells * 4, &t->succ_logp);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    dart_ngram_destroy(t);
+    return from_hip(e);
+  }
+  t->dev.n_gram = n_gram;
+  t->dev.S = S;
+  t->dev.slot_mask = n_slots - 1;
+  t->dev.slot_keys = (const uint64_t *)t->slot_keys;
+  t->dev.slot_rows = (const int32_t *)t->slot_rows;
+  t->dev.succ_ids = (const int32_t *)t->succ_ids;
+  t->dev.succ_logp = (const float *)t->succ_logp;
+  t->dev.logp_miss = miss;
+  *out = t;
+  return DART_OK;
+}
+
+void dart_ngram_destroy(dart_ngram *t) {
+  if (!t) return;
+  void *bufs[] = {t->slot_keys, t->slot_rows, t->succ_ids, t->succ_logp};
+  for (void *p : bufs)
+    if (p) (void)hipFree(p);
+  delete t;
+}
+
+dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, int K,
+                            const int32_t *ctx_tail, const dart_ngram *table,
+                            const dart_prune_params *p, int32_t *tokens_out, int32_t *parents_out,
+                            uint8_t *mask_out, int32_t *n_nodes_out, void *stream) {
+  if (!ids || !scores || !ctx_tail || !table || !p || !tokens_out || !parents_out || !mask_out ||
+      !n_nodes_out)
+    return DART_ERR_ARG;
+  if (batch < 1 || K < 1 || K > DART_MAX_K) return DART_ERR_ARG;
+  if (p->k < 1 || p->k > DART_MAX_TOPK || p->beam_w < 1 || p->beam_w > DART_MAX_BEAM ||
+      p->budget < 1 || p->budget > DART_MAX_BUDGET || p->beam_w * p->k > DART_MAX_LEVEL_NODES)
+    return DART_ERR_ARG;
+  PruneLevelWeights lw;
+  for (int L = 0; L < DART_MAX_K; ++L) {
+    lw.w_logit[L] = (float)std::pow((double)p->logit_decay, (double)L);
+    lw.w_level[L] = (float)std::pow((double)(L + 1), -(double)p->level_pow);
+  }
+  return from_hip(launch_prune(batch, ids, scores, K, ctx_tail, table->dev, *p, lw, tokens_out,
+                               parents_out, mask_out, n_nodes_out, (hipStream_t)stream));
+}
+
+// Diagnostic: copy a named fp32 workspace of the last forward to host memory (synchronises).
+// Names: xn, resid, qkv, att_out, y, yn, hmid, u.  Returns the number of floats copied or -1.
+int64_t dart_debug_read(dart_ctx *c, const char *name, float *host_out, int64_t max_count) {
+  if (!c || !name || !host_out) return -1;
+  const int R = DART_SKINNY_ROWS;
+  const float *src = nullptr;
+  int64_t count = 0;
+  if (!strcmp(name, "xn")) src = c->xn, count = (int64_t)R * c->cfg.d;
+  else if (!strcmp(name, "resid")) src = c->resid, count = (int64_t)R * c->cfg.d;
+  else if (!strcmp(name, "qkv")) src = c->qkv, count = (int64_t)R * c->qkv_dim;
+  else if (!strcmp(name, "att_out")) src = c->att_out, count = (int64_t)R * c->q_dim;
+  else if (!strcmp(name, "y")) src = c->y, count = (int64_t)R * c->cfg.d;
+  else if (!strcmp(name, "yn")) src = c->yn, count = (int64_t)R * c->cfg.d;
+  else if (!strcmp(name, "hmid")) src = c->hmid, count = (int64_t)R * c->cfg.ffn;
+  else if (!strcmp(name, "u")) src = c->u, count = (int64_t)R * c->cfg.d;
+  else return -1;
+  if (count > max_count) count = max_count;
+  if (hipDeviceSynchronize() != hipSuccess) return -1;
+  if (hipMemcpy(host_out, src, count * 4, hipMemcpyDeviceToHost) != hipSuccess) return -1;
+  return count;
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Host-side state and kernel launchers behind the C ABI of the DART drafting step.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dart.h"
+
+#define DART_SKINNY_ROWS 16   // rows one skinny-GEMM pass carries (one MFMA column block)
+
+// One weight matrix on the device.  fp32: row-major [N][Kd].  bf16: re-tiled for
+// v_mfma_f32_16x16x32_bf16 (see pack_bf16_tiles in dart_api.hip): tile (strip s of 16
+// output rows, k-step t of 32 inputs) is 1 KiB at ((s * Kd/32) + t) * 1024, and inside a
+// tile lane l owns the 8 consecutive inputs 8*(l/16).. of output row l%16.
+struct DeviceMatrix {
+  void *data = nullptr;
+  int N = 0;        // output features (padded to a multiple of 16 for bf16)
+  int Kd = 0;       // input features
+  int n_real = 0;   // unpadded output features
+};
+
+struct NgramTableDev {
+  int n_gram;
+  int S;                      // successors per row
+  uint64_t slot_mask;         // n_slots - 1 (power of two)
+  const uint64_t *slot_keys;  // packed context or ~0 when empty
+  const int32_t *slot_rows;   // row index of the slot's context
+  const int32_t *succ_ids;    // [n_keys][S], -1 = unused
+  const float *succ_logp;     // [n_keys][S]
+  float logp_miss;
+};
+
+struct dart_ngram {
+  NgramTableDev dev;
+  void *slot_keys = nullptr, *slot_rows = nullptr, *succ_ids = nullptr, *succ_logp = nullptr;
+};
+
+struct PruneLevelWeights {
+  float w_logit[DART_MAX_K];
+  float w_level[DART_MAX_K];
+};
+
+struct dart_ctx {
+  dart_config cfg;
+  int q_dim, kv_dim, qkv_dim;
+  int t_cap;                     // K/V rows per (sequence, head): max_ctx + max_K - 1, padded to 64
+  // weights
+  DeviceMatrix wqkv, wo, wgu, wdown, wlm;   // wgu: gate and up rows interleaved (see dart_api.hip)
+  void *g_in = nullptr, *g_post = nullptr, *g_final = nullptr, *g_q = nullptr, *g_k = nullptr;
+  void *mask_emb = nullptr;
+  float *rope_cos = nullptr, *rope_sin = nullptr;   // [t_cap][hd/2]
+  // draft K/V buffers: K [batch][Hkv][t_cap][hd]; V fp32 same, bf16 transposed [batch][Hkv][hd][t_cap]
+  void *kbuf = nullptr, *vbuf = nullptr;
+  int *cached_rows = nullptr;     // host, [max_batch]
+  // activations / workspaces (device, fp32 unless noted)
+  float *xn = nullptr;            // [16][d] normed layer input
+  float *resid = nullptr;         // [rows][d] raw input rows of the query positions
+  float *qkv = nullptr;           // [chunks][16][qkv_dim]
+  void *qrot = nullptr;           // [rows][q_dim] queries after norm + rotary (fp32 or bf16)
+  float *att_part = nullptr;      // [rows*Hq][splits][hd]
+  float *att_ml = nullptr;        // [rows*Hq][splits][2]
+  float *att_out = nullptr;       // [rows][q_dim]
+  float *proj = nullptr;          // [chunks][rows][max(d, 2*ffn)] projection partial sums
+  float *y = nullptr, *yn = nullptr, *hmid = nullptr, *u = nullptr;
+  int max_rows;                   // max_batch * max_K
+  int max_splits;
+  int max_chunks;
+  // top-k workspace
+  uint64_t *topk_cand = nullptr;  // [rows][chunks][DART_MAX_TOPK]
+  float *topk_ms = nullptr;       // [rows][chunks][2]
+  int topk_chunks_max;
+};
+
+namespace dart {
+
+// Hash of a packed N-gram context; the host-side table build and the device probe share it.
+__host__ __device__ inline uint64_t mix64(uint64_t x) {
+  x ^= x >> 33;
+  x *= 0xff51afd7ed558ccdULL;
+  x ^= x >> 33;
+  x *= 0xc4ceb9fe1a85ec53ULL;
+  x ^= x >> 33;
+  return x;
+}
+
+// All launchers only enqueue work on `st` and return the launch status.
+
+hipError_t launch_rmsnorm_gather(int dtype, const void *hidden, const void *mask_emb,
+                                 const void *gain, int n, int pos0, int M, int d, float eps,
+                                 float *xn, float *resid, int resid_row0, hipStream_t st);
+
+hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
+                             size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
+                             float eps, float *y, float *yn, hipStream_t st);
+
+hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const float *X, int M,
+                           float *out, int out_stride, hipStream_t st);
+
+// bf16 skinny GEMM on packed weights; returns the number of k-chunks written through *chunks.
+hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
+                            float *out, int out_stride, size_t chunk_stride, int *chunks,
+                            hipStream_t st);
+int gemv_bf16_chunks(int Kd);
+
+hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
+                         int interleaved, float *h, hipStream_t st);
+
+hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chunks,
+                           size_t chunk_stride, int M, int Kq, int pos0, hipStream_t st);
+
+hipError_t launch_attention(const dart_ctx *c, int seq, int n, int Kq, hipStream_t st);
+
+hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
+                       int32_t *ids, float *scores, hipStream_t st);
+
+hipError_t launch_prune(int batch, const int32_t *ids, const float *scores, int K,
+                        const int32_t *ctx_tail, const NgramTableDev &tab,
+                        const dart_prune_params &p, const PruneLevelWeights &lw, int32_t *tokens,
+                        int32_t *parents, uint8_t *mask, int32_t *n_nodes, hipStream_t st);
+
+}  // namespace dart

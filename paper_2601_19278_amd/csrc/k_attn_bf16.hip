@@ -1,0 +1,199 @@
+// Masked-position attention of the draft layer on bf16 K/V buffers, MFMA 16x16x32 bf16.
+//
+// K = up to 16 query rows times Hq/Hkv query heads share each K/V head, so the scores of
+// one K/V head are a (keys x 128 dims) x (128 dims x up-to-128 queries) contraction: small,
+// but a real dense one, and the K/V stream (read once) is what bounds it.
+//
+// The product is formed transposed so that a lane owns one query column throughout:
+//   S^T[key][q] = sum_dim K[key][dim] Q[q][dim]      A = K rows (row-major buffer), B = Q
+//   O^T[dim][q] = sum_key V^T[dim][key] P^T[key][q]   A = V^T rows (V is stored transposed)
+// The MFMA result layout (lane l: column l%16, rows 4*(l/16)+r) of S^T is, after the
+// soft-max, directly the B operand of the second product if its 32-key contraction index
+// is taken as (lane group, e) <-> key 16*(e/4) + 4*(l/16) + e%4 -- V^T is loaded with the
+// same index map, so probabilities never leave registers.
+//
+// Work split: grid (key split, K/V head, query-tile group), 4 wavefronts per workgroup.
+// Every wavefront walks all keys of the split and computes the (cheap) scores and soft-max
+// statistics redundantly; wavefront w accumulates only output dims [HD/4*w, HD/4*(w+1)).
+// No LDS, no cross-wave merge; split partials are merged by attn_merge_kernel.
+#include "common.h"
+#include "dart_internal.h"
+
+namespace dart {
+
+typedef __attribute__((ext_vector_type(4))) uint16_t u16x4_t;
+
+union Bf16x8 {
+  bf16x8_t v;
+  uint4 u;
+  uint2 h[2];
+  bf16_t e[8];
+};
+
+template <int HD, int MT>
+__global__ __launch_bounds__(256) void attn_split_bf16_kernel(
+    const bf16_t *__restrict__ q,     // [Kq][Hq][HD]
+    const bf16_t *__restrict__ kbuf,  // [Hkv][t_cap][HD]
+    const bf16_t *__restrict__ vtbuf, // [Hkv][HD][t_cap]
+    int t_cap, int n, int Kq, int Hq, int group, int chunk, float scale, int nsplit,
+    float *__restrict__ o_part, float *__restrict__ ml_part) {
+  constexpr int KS = HD / 32;        // k-steps of the score product
+  constexpr int DTW = HD / 64;       // output dim tiles per wavefront
+  const int split = blockIdx.x, g = blockIdx.y, a0 = blockIdx.z * MT;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, gq = lane >> 4;
+  const int QV = Kq * group;
+  const int T = n + Kq - 1;
+  const int j_begin = split * chunk;
+  const int j_end = min(j_begin + chunk, T);
+
+  // B operands of the score product: this lane's query column, all k-steps, MT tiles
+  Bf16x8 qop[MT][KS];
+  int qrow[MT];                      // query row i of this lane's column (-1: padding)
+  size_t qslot[MT];                  // global query-vector index
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    const int ql = 16 * (a0 + a) + col;
+    const bool ok = ql < QV;
+    const int i = ok ? ql / group : 0, hg = ok ? ql % group : 0;
+    qrow[a] = ok ? i : -1;
+    qslot[a] = (size_t)i * Hq + (size_t)g * group + hg;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ok)
+        qop[a][ks].u = *reinterpret_cast<const uint4 *>(q + qslot[a] * HD + 32 * ks + 8 * gq);
+      else
+        qop[a][ks].u = make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  f32x4_t acc[MT][DTW];
+  float m[MT], l[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    m[a] = -3.0e38f;
+    l[a] = 0.f;
+#pragma unroll
+    for (int t = 0; t < DTW; ++t) acc[a][t] = {0.f, 0.f, 0.f, 0.f};
+  }
+
+  const bf16_t *kb = kbuf + (size_t)g * t_cap * HD;
+  const bf16_t *vt = vtbuf + (size_t)g * HD * t_cap;
+
+  for (int jb = j_begin; jb < j_end; jb += 32) {
+    // A operands: two 16-key tiles of K, and this wavefront's V^T dim tiles
+    Bf16x8 kop[2][KS], vop[DTW];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        kop[tt][ks].u = *reinterpret_cast<const uint4 *>(
+            kb + (size_t)(jb + 16 * tt + col) * HD + 32 * ks + 8 * gq);
+#pragma unroll
+    for (int t = 0; t < DTW; ++t) {
+      const bf16_t *row = vt + (size_t)(16 * (DTW * wave + t) + col) * t_cap + jb + 4 * gq;
+      vop[t].h[0] = *reinterpret_cast<const uint2 *>(row);
+      vop[t].h[1] = *reinterpret_cast<const uint2 *>(row + 16);
+    }
+
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+      f32x4_t s[2];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        s[tt] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tt][ks].v, qop[a][ks].v, s[tt], 0, 0, 0);
+      }
+      // mask + running soft-max statistics of this lane's query column
+      const int last = n - 1 + qrow[a];            // qrow = -1 -> nothing visible beyond n-2; unused
+      float mloc = -3.0e38f;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int jk = jb + 16 * tt + 4 * gq + r;
+          const bool vis = (qrow[a] >= 0) && (jk <= last);
+          s[tt][r] = vis ? s[tt][r] * scale : -3.0e38f;
+          mloc = fmaxf(mloc, s[tt][r]);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 16, DART_WAVE));
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, DART_WAVE));
+      const float mn = fmaxf(m[a], mloc);
+      const float corr = expf(m[a] - mn);
+      float lsum = 0.f;
+      Bf16x8 pop;
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float p = s[tt][r] > -1.0e38f ? expf(s[tt][r] - mn) : 0.f;
+          lsum += p;
+          pop.e[4 * tt + r] = f32_to_bf16(p);
+        }
+      lsum += __shfl_xor(lsum, 16, DART_WAVE);
+      lsum += __shfl_xor(lsum, 32, DART_WAVE);
+      l[a] = l[a] * corr + lsum;
+      m[a] = mn;
+#pragma unroll
+      for (int t = 0; t < DTW; ++t) {
+        acc[a][t] *= corr;
+        acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[t].v, pop.v, acc[a][t], 0, 0, 0);
+      }
+    }
+  }
+
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    if (qrow[a] < 0) continue;
+    const size_t slot = qslot[a] * nsplit + split;
+#pragma unroll
+    for (int t = 0; t < DTW; ++t) {
+      const int dim = 16 * (DTW * wave + t) + 4 * gq;
+      *reinterpret_cast<float4 *>(o_part + slot * HD + dim) =
+          make_float4(acc[a][t][0], acc[a][t][1], acc[a][t][2], acc[a][t][3]);
+    }
+    if (wave == 0 && gq == 0) {
+      ml_part[slot * 2] = m[a];
+      ml_part[slot * 2 + 1] = l[a];
+    }
+  }
+}
+
+template <int HD, int MT>
+static hipError_t launch_one(const dart_ctx *c, int seq, int n, int Kq, int chunk, int nsplit,
+                             int zgroups, hipStream_t st) {
+  const dart_config &g = c->cfg;
+  const size_t seq_elems = (size_t)g.n_kv_heads * c->t_cap * HD;
+  const bf16_t *kb = (const bf16_t *)c->kbuf + seq * seq_elems;
+  const bf16_t *vt = (const bf16_t *)c->vbuf + seq * seq_elems;
+  hipLaunchKernelGGL((attn_split_bf16_kernel<HD, MT>), dim3(nsplit, g.n_kv_heads, zgroups),
+                     dim3(256), 0, st, (const bf16_t *)c->qrot, kb, vt, c->t_cap, n, Kq,
+                     g.n_q_heads, g.n_q_heads / g.n_kv_heads, chunk, 1.0f / sqrtf((float)HD), nsplit,
+                     c->att_part, c->att_ml);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bf16(const dart_ctx *c, int seq, int n, int Kq, int *nsplit_out,
+                                 hipStream_t st) {
+  const dart_config &g = c->cfg;
+  const int T = n + Kq - 1;
+  const int chunk = 128;                                   // keys per workgroup, multiple of 32
+  const int nsplit = (T + chunk - 1) / chunk;
+  *nsplit_out = nsplit;
+  const int QV = Kq * (g.n_q_heads / g.n_kv_heads);
+  const int tiles = (QV + 15) / 16;
+  const int MT = tiles >= 3 ? 3 : tiles;                   // query tiles per workgroup
+  const int zgroups = (tiles + MT - 1) / MT;
+  if (g.head_dim == 128) {
+    if (MT == 1) return launch_one<128, 1>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+    if (MT == 2) return launch_one<128, 2>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+    return launch_one<128, 3>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+  }
+  if (MT == 1) return launch_one<64, 1>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+  if (MT == 2) return launch_one<64, 2>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+  return launch_one<64, 3>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+}
+
+}  // namespace dart

@@ -1,0 +1,114 @@
+// Masked-position attention of the draft layer, fp32 storage (small parity configuration),
+// and the split-merge kernel shared with the bf16 path.
+//
+// Query row i (0-based among the K read-out rows) sits at position n-1+i and sees keys
+// 0..n-1+i: the whole prefix plus the mask rows up to itself -- the strictly causal mask
+// of paper Sec. 3.1 restricted to one prefix (mask listing of App. B).
+#include "common.h"
+#include "dart_internal.h"
+
+namespace dart {
+
+// One wavefront per (key split, query vector).  Lane owns dims lane, lane+64.
+// Partial result: unnormalised sum_j exp(s_j - m) v_j, with m and l = sum_j exp(s_j - m).
+template <int HD>
+__global__ __launch_bounds__(64) void attn_split_f32_kernel(
+    const float *__restrict__ q, const float *__restrict__ kbuf, const float *__restrict__ vbuf,
+    int t_cap, int n, int Hq, int group, int chunk, float scale, int nsplit,
+    float *__restrict__ o_part, float *__restrict__ ml_part) {
+  constexpr int PER = HD / 64;
+  const int split = blockIdx.x, qv = blockIdx.y, lane = threadIdx.x;
+  const int i = qv / Hq, h = qv % Hq, g = h / group;
+  const int last = n - 1 + i;                          // last visible key
+  const int j0 = split * chunk;
+  const int j1 = min(j0 + chunk, last + 1);
+  float qr[PER], acc[PER];
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    qr[p] = q[(size_t)qv * HD + lane + 64 * p];
+    acc[p] = 0.f;
+  }
+  float m = -3.0e38f, l = 0.f;
+  const float *kb = kbuf + (size_t)g * t_cap * HD, *vb = vbuf + (size_t)g * t_cap * HD;
+  for (int j = j0; j < j1; ++j) {
+    float s = 0.f;
+#pragma unroll
+    for (int p = 0; p < PER; ++p) s += qr[p] * kb[(size_t)j * HD + lane + 64 * p];
+    s = wave_sum(s) * scale;
+    const float mn = fmaxf(m, s);
+    const float corr = expf(m - mn), pj = expf(s - mn);
+    l = l * corr + pj;
+#pragma unroll
+    for (int p = 0; p < PER; ++p) acc[p] = acc[p] * corr + pj * vb[(size_t)j * HD + lane + 64 * p];
+    m = mn;
+  }
+  const size_t slot = (size_t)qv * nsplit + split;
+#pragma unroll
+  for (int p = 0; p < PER; ++p) o_part[slot * HD + lane + 64 * p] = acc[p];
+  if (lane == 0) {
+    ml_part[slot * 2] = m;
+    ml_part[slot * 2 + 1] = l;
+  }
+}
+
+// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s.  Splits with l == 0 saw no key.
+__global__ __launch_bounds__(128) void attn_merge_kernel(const float *__restrict__ o_part,
+                                                         const float *__restrict__ ml_part,
+                                                         int nsplit, int hd,
+                                                         float *__restrict__ out) {
+  const int qv = blockIdx.x, t = threadIdx.x;
+  if (t >= hd) return;
+  float M = -3.0e38f;
+  for (int s = 0; s < nsplit; ++s) {
+    const float l = ml_part[((size_t)qv * nsplit + s) * 2 + 1];
+    if (l > 0.f) M = fmaxf(M, ml_part[((size_t)qv * nsplit + s) * 2]);
+  }
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const size_t slot = (size_t)qv * nsplit + s;
+    const float l = ml_part[slot * 2 + 1];
+    if (l > 0.f) {
+      const float w = expf(ml_part[slot * 2] - M);
+      num += w * o_part[slot * hd + t];
+      den += w * l;
+    }
+  }
+  out[(size_t)qv * hd + t] = num / den;
+}
+
+hipError_t launch_attention_bf16(const dart_ctx *c, int seq, int n, int Kq, int *nsplit_out,
+                                 hipStream_t st);
+
+hipError_t launch_attention(const dart_ctx *c, int seq, int n, int Kq, hipStream_t st) {
+  const dart_config &g = c->cfg;
+  const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
+  const int T = n + Kq - 1;
+  int nsplit = 1;
+  if (g.dtype == DART_BF16) {
+    hipError_t e = launch_attention_bf16(c, seq, n, Kq, &nsplit, st);
+    if (e != hipSuccess) return e;
+  } else {
+    const int chunk = 128;
+    nsplit = (T + chunk - 1) / chunk;
+    const float scale = 1.0f / sqrtf((float)hd);
+    const size_t seq_elems = (size_t)Hkv * c->t_cap * hd;
+    const float *kb = (const float *)c->kbuf + seq * seq_elems;
+    const float *vb = (const float *)c->vbuf + seq * seq_elems;
+    dim3 grid(nsplit, Kq * Hq);
+    if (hd == 64)
+      hipLaunchKernelGGL(attn_split_f32_kernel<64>, grid, dim3(64), 0, st, (const float *)c->qrot,
+                         kb, vb, c->t_cap, n, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
+                         c->att_ml);
+    else
+      hipLaunchKernelGGL(attn_split_f32_kernel<128>, grid, dim3(64), 0, st, (const float *)c->qrot,
+                         kb, vb, c->t_cap, n, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
+                         c->att_ml);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(Kq * Hq), dim3(128), 0, st, c->att_part, c->att_ml,
+                     nsplit, hd, c->att_out);
+  return hipGetLastError();
+}
+
+}  // namespace dart

@@ -1,0 +1,117 @@
+// Row-wise kernels of the draft layer: input gather + RMSNorm, residual + RMSNorm, SwiGLU.
+// (Draft layer = one pre-norm decoder layer, paper Sec. 3.2 / App. B.)
+#include "common.h"
+#include "dart_internal.h"
+
+namespace dart {
+
+// Row i of the layer input is position pos0+i of [z_1..z_n, MASK x (K-1)] (Sec. 3.2):
+// a prefix row of `hidden` when pos < n, else mask embedding pos-n.  Writes the RMS-normed
+// row (times gain) to xn[i] and, for rows >= resid_row0, the raw row to resid.
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_gather_kernel(
+    const T *__restrict__ hidden, const T *__restrict__ mask_emb, const T *__restrict__ gain, int n,
+    int pos0, int d, float eps, float *__restrict__ xn, float *__restrict__ resid, int resid_row0) {
+  __shared__ float red[16];
+  const int i = blockIdx.x;
+  const int pos = pos0 + i;
+  const T *src = pos < n ? hidden + (size_t)pos * d : mask_emb + (size_t)(pos - n) * d;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float v = to_f32(src[c]);
+    ss += v * v;
+  }
+  ss = block_sum(ss, red);
+  const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float v = to_f32(src[c]);
+    xn[(size_t)i * d + c] = v * rstd * to_f32(gain[c]);
+    if (i >= resid_row0) resid[(size_t)(i - resid_row0) * d + c] = v;
+  }
+}
+
+// y = resid + sum_c part[c];  yn = RMSNorm(y) * gain.  part[c] row r starts at
+// part + c*chunk_stride + r*row_stride.
+template <typename T>
+__global__ __launch_bounds__(256) void resid_norm_kernel(const float *__restrict__ resid,
+                                                         const float *__restrict__ part, int chunks,
+                                                         size_t chunk_stride, int row_stride,
+                                                         const T *__restrict__ gain, int d, float eps,
+                                                         float *__restrict__ y,
+                                                         float *__restrict__ yn) {
+  __shared__ float red[16];
+  const int r = blockIdx.x;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float v = resid[(size_t)r * d + c];
+    for (int k = 0; k < chunks; ++k) v += part[k * chunk_stride + (size_t)r * row_stride + c];
+    y[(size_t)r * d + c] = v;
+    ss += v * v;
+  }
+  ss = block_sum(ss, red);
+  const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x; c < d; c += blockDim.x)
+    yn[(size_t)r * d + c] = y[(size_t)r * d + c] * rstd * to_f32(gain[c]);
+}
+
+// h[r][f] = silu(gate) * up from the fused gate/up projection (summed over k-chunks).
+// interleaved = 0: row r is [gate(ffn) | up(ffn)].
+// interleaved = 1: features come in groups of 4 outputs (g f, g f+1, u f, u f+1), the row
+// order the packed bf16 matrix uses so that one MFMA lane holds a gate/up pair.
+__global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ gu, int chunks,
+                                                     size_t chunk_stride, int ffn, int interleaved,
+                                                     float *__restrict__ h) {
+  const int r = blockIdx.y;
+  const int f = blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= ffn) return;
+  size_t gi, ui;
+  if (interleaved) {
+    gi = (size_t)(f >> 1) * 4 + (f & 1);
+    ui = gi + 2;
+  } else {
+    gi = f;
+    ui = (size_t)ffn + f;
+  }
+  const float *row = gu + (size_t)r * 2 * ffn;
+  float g = 0.f, u = 0.f;
+  for (int k = 0; k < chunks; ++k) {
+    g += row[k * chunk_stride + gi];
+    u += row[k * chunk_stride + ui];
+  }
+  h[(size_t)r * ffn + f] = g / (1.0f + expf(-g)) * u;
+}
+
+hipError_t launch_rmsnorm_gather(int dtype, const void *hidden, const void *mask_emb,
+                                 const void *gain, int n, int pos0, int M, int d, float eps,
+                                 float *xn, float *resid, int resid_row0, hipStream_t st) {
+  if (dtype == DART_BF16)
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(M), dim3(256), 0, st,
+                       (const bf16_t *)hidden, (const bf16_t *)mask_emb, (const bf16_t *)gain, n,
+                       pos0, d, eps, xn, resid, resid_row0);
+  else
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(256), 0, st,
+                       (const float *)hidden, (const float *)mask_emb, (const float *)gain, n, pos0,
+                       d, eps, xn, resid, resid_row0);
+  return hipGetLastError();
+}
+
+hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
+                             size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
+                             float eps, float *y, float *yn, hipStream_t st) {
+  if (dtype == DART_BF16)
+    hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, resid, part, chunks,
+                       chunk_stride, row_stride, (const bf16_t *)gain, d, eps, y, yn);
+  else
+    hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(rows), dim3(256), 0, st, resid, part, chunks,
+                       chunk_stride, row_stride, (const float *)gain, d, eps, y, yn);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
+                         int interleaved, float *h, hipStream_t st) {
+  hipLaunchKernelGGL(swiglu_kernel, dim3((ffn + 255) / 256, rows), dim3(256), 0, st, gu, chunks,
+                     chunk_stride, ffn, interleaved, h);
+  return hipGetLastError();
+}
+
+}  // namespace dart

@@ -1,0 +1,266 @@
+// Continuity-aware tree pruning (paper Alg. 1, constants and Combine of App. D) on the GPU:
+// one workgroup per sequence, the candidate frontier (beam), the level's expansions and
+// the running best-theta list all resident in LDS; the N-gram model is a device hash table
+// (context -> successor row), one lookup per beam entry serving all k candidates (the
+// single-traversal retrieval of App. C.2).
+//
+// Per level L: every (beam entry b, candidate c) pair is scored
+//     inc = ((w_logit[L] * s_logit) + (w_ng * s_ng)) * w_level[L],  score = parent + inc
+// with one fp32 rounding per operation (no FMA contraction), so results are bit-identical
+// to a CPU evaluation of the same formula.  Each expansion becomes one 64-bit ordering key
+//     [ order-preserving score bits : 32 | 15 - level : 4 | 0x0FFFFFFF - creation : 28 ]
+// (creation = b*k + c).  Larger key = better under both cuts of the algorithm: within one
+// level it orders by (score desc, creation asc) -- the beam cut -- and across levels by
+// (score desc, level asc, creation asc) -- the global theta cut.  A bitonic sort of the
+// level's keys gives the next beam (first w) and the level's contenders for the global
+// tree (first theta), which are merged into the running best-theta list.  Since the best
+// theta of a union is the best theta of (best theta of one part) + (the other part), the
+// running list equals Alg. 1's "top-theta of T" after the last level.
+#include "common.h"
+#include "dart_internal.h"
+
+namespace dart {
+
+constexpr int PRUNE_THREADS = 256;
+
+struct PruneShared {
+  uint64_t keys[DART_MAX_LEVEL_NODES];        // this level's expansions
+  int32_t cand_id[DART_MAX_K * DART_MAX_TOPK];
+  float cand_sc[DART_MAX_K * DART_MAX_TOPK];
+  // beam (double buffered)
+  float beam_score[2][DART_MAX_BEAM];
+  int32_t beam_tok[2][DART_MAX_BEAM];
+  int32_t beam_prev[2][DART_MAX_BEAM];
+  int32_t beam_cre[2][DART_MAX_BEAM];          // creation index of the entry at its own level
+  int32_t beam_row[DART_MAX_BEAM];             // table row of the entry's context, -1 = unseen
+  // running best list (double buffered), sorted by key descending
+  uint64_t best_key[2][DART_MAX_BUDGET];
+  int32_t best_tok[2][DART_MAX_BUDGET];
+  int32_t best_par[2][DART_MAX_BUDGET];        // creation index of the parent at level-1
+  // emission
+  int32_t out_idx[DART_MAX_BUDGET];
+  int32_t out_par[DART_MAX_BUDGET];
+};
+
+// Row of a packed context, or -1.  Linear probing; the table is at most half full, and the
+// probe count is bounded by the table size so the loop always ends.
+__device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed) {
+  uint64_t h = mix64(packed) & tab.slot_mask;
+  for (uint64_t probes = 0; probes <= tab.slot_mask; ++probes) {
+    const uint64_t kk = tab.slot_keys[h];
+    if (kk == packed) return tab.slot_rows[h];
+    if (kk == ~(uint64_t)0) return -1;
+    h = (h + 1) & tab.slot_mask;
+  }
+  return -1;
+}
+
+__device__ __forceinline__ int key_level(uint64_t key) { return 15 - (int)((key >> 28) & 0xF); }
+__device__ __forceinline__ int key_creation(uint64_t key) {
+  return 0x0FFFFFFF - (int)(key & 0x0FFFFFFF);
+}
+
+__global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
+    const int32_t *__restrict__ ids, const float *__restrict__ scores, int K,
+    const int32_t *__restrict__ ctx_tail, NgramTableDev tab, int k, int beam_w, int budget,
+    float w_ng, PruneLevelWeights lw, int32_t *__restrict__ tokens_out,
+    int32_t *__restrict__ parents_out, uint8_t *__restrict__ mask_out,
+    int32_t *__restrict__ n_nodes_out) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  PruneShared &sh = *reinterpret_cast<PruneShared *>(smem_raw);
+  const int seq = blockIdx.x, t = threadIdx.x;
+  const int theta = budget - 1;
+  const int ctx_len = tab.n_gram - 1;
+  ids += (size_t)seq * K * k;
+  scores += (size_t)seq * K * k;
+  ctx_tail += (size_t)seq * ctx_len;
+  tokens_out += (size_t)seq * budget;
+  parents_out += (size_t)seq * budget;
+  mask_out += (size_t)seq * budget * budget;
+
+  for (int e = t; e < K * k; e += PRUNE_THREADS) {
+    sh.cand_id[e] = ids[e];
+    sh.cand_sc[e] = scores[e];
+  }
+  const int root = ctx_tail[ctx_len - 1];
+  if (t == 0) {
+    sh.beam_score[0][0] = 0.f;
+    sh.beam_tok[0][0] = root;
+    sh.beam_prev[0][0] = ctx_len >= 2 ? ctx_tail[ctx_len - 2] : 0;
+    sh.beam_cre[0][0] = -1;                    // the root
+  }
+  int nb = 1, n_best = 0, cur = 0, bcur = 0;
+  __syncthreads();
+
+  for (int L = 0; L < K; ++L) {
+    const int n_new = nb * k;
+    int P = 2;
+    while (P < n_new) P <<= 1;
+    // one table lookup per beam entry: context = last N-1 tokens of (ctx_tail ++ path)
+    if (t < nb) {
+      const uint64_t packed = ctx_len >= 2
+                                  ? ((uint64_t)(uint32_t)sh.beam_prev[cur][t] << 32) |
+                                        (uint32_t)sh.beam_tok[cur][t]
+                                  : (uint64_t)(uint32_t)sh.beam_tok[cur][t];
+      sh.beam_row[t] = ngram_find(tab, packed);
+    }
+    __syncthreads();
+    const float wl = lw.w_logit[L], wv = lw.w_level[L];
+    for (int e = t; e < P; e += PRUNE_THREADS) {
+      uint64_t key = 0;
+      if (e < n_new) {
+        const int b = e / k, c = e - b * k;
+        const int tok = sh.cand_id[L * k + c];
+        float s_ng = tab.logp_miss;
+        const int row = sh.beam_row[b];
+        if (row >= 0) {
+          const int32_t *rid = tab.succ_ids + (size_t)row * tab.S;
+          for (int j = 0; j < tab.S; ++j)
+            if (rid[j] == tok) {
+              s_ng = tab.succ_logp[(size_t)row * tab.S + j];
+              break;
+            }
+        }
+        const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
+        const float g = __fmul_rn(w_ng, s_ng);
+        const float inc = __fmul_rn(__fadd_rn(a, g), wv);
+        const float sc = __fadd_rn(sh.beam_score[cur][b], inc);
+        key = ((uint64_t)f32_sortable(sc) << 32) | ((uint64_t)(15 - L) << 28) |
+              (uint64_t)(0x0FFFFFFF - e);
+      }
+      sh.keys[e] = key;
+    }
+    __syncthreads();
+    // bitonic sort, descending
+    for (int size = 2; size <= P; size <<= 1) {
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        for (int e = t; e < (P >> 1); e += PRUNE_THREADS) {
+          const int lo = ((e / stride) * stride * 2) + (e % stride);
+          const int hi = lo + stride;
+          const bool desc = ((lo & size) == 0);
+          const uint64_t a = sh.keys[lo], b = sh.keys[hi];
+          if (desc ? (a < b) : (a > b)) {
+            sh.keys[lo] = b;
+            sh.keys[hi] = a;
+          }
+        }
+        __syncthreads();
+      }
+    }
+    // next beam: the first min(w, n_new) expansions
+    const int nb_next = min(beam_w, n_new);
+    const int nxt = cur ^ 1;
+    if (t < nb_next) {
+      const uint64_t key = sh.keys[t];
+      const int e = key_creation(key);
+      const int b = e / k, c = e - b * k;
+      sh.beam_score[nxt][t] = f32_unsortable((uint32_t)(key >> 32));
+      sh.beam_tok[nxt][t] = sh.cand_id[L * k + c];
+      sh.beam_prev[nxt][t] = sh.beam_tok[cur][b];
+      sh.beam_cre[nxt][t] = e;
+    }
+    // merge the level's first min(theta, n_new) into the running best list (both sorted)
+    const int n_lvl = min(theta, n_new);
+    const int bnx = bcur ^ 1;
+    if (t < n_best + n_lvl) {
+      uint64_t key;
+      int tok, par, rank;
+      if (t < n_best) {
+        key = sh.best_key[bcur][t];
+        tok = sh.best_tok[bcur][t];
+        par = sh.best_par[bcur][t];
+        rank = t;
+        for (int j = 0; j < n_lvl; ++j) rank += (sh.keys[j] > key);
+      } else {
+        const int j0 = t - n_best;
+        key = sh.keys[j0];
+        const int e = key_creation(key);
+        const int b = e / k, c = e - b * k;
+        tok = sh.cand_id[L * k + c];
+        par = sh.beam_cre[cur][b];
+        rank = j0;
+        for (int j = 0; j < n_best; ++j) rank += (sh.best_key[bcur][j] > key);
+      }
+      if (rank < theta) {
+        sh.best_key[bnx][rank] = key;
+        sh.best_tok[bnx][rank] = tok;
+        sh.best_par[bnx][rank] = par;
+      }
+    }
+    n_best = min(theta, n_best + n_lvl);
+    bcur = bnx;
+    cur = nxt;
+    nb = nb_next;
+    __syncthreads();
+  }
+
+  // emission: root, then level-major; inside a level the best list's order already is
+  // (score desc, creation asc)
+  const int n_nodes = 1 + n_best;
+  if (t < n_best) {
+    const int lev = key_level(sh.best_key[bcur][t]);
+    int idx = 1;
+    for (int j = 0; j < n_best; ++j) {
+      const int lj = key_level(sh.best_key[bcur][j]);
+      idx += (lj < lev) || (lj == lev && j < t);
+    }
+    sh.out_idx[t] = idx;
+  }
+  __syncthreads();
+  if (t < n_best) {
+    const uint64_t key = sh.best_key[bcur][t];
+    const int lev = key_level(key);
+    int parent = 0;
+    if (lev > 0) {
+      parent = -2;                                   // stays -2 only if the set were not ancestor-closed
+      const int want = sh.best_par[bcur][t];
+      for (int j = 0; j < n_best; ++j) {
+        const uint64_t kj = sh.best_key[bcur][j];
+        if (key_level(kj) == lev - 1 && key_creation(kj) == want) parent = sh.out_idx[j];
+      }
+    }
+    const int idx = sh.out_idx[t];
+    sh.out_par[idx] = parent;
+    tokens_out[idx] = sh.best_tok[bcur][t];
+    parents_out[idx] = parent;
+  }
+  if (t == 0) {
+    sh.out_par[0] = -1;
+    tokens_out[0] = root;
+    parents_out[0] = -1;
+    n_nodes_out[seq] = n_nodes;
+  }
+  for (int i = n_nodes + t; i < budget; i += PRUNE_THREADS) {
+    tokens_out[i] = -1;
+    parents_out[i] = -1;
+  }
+  for (int i = t; i < budget * budget; i += PRUNE_THREADS) mask_out[i] = 0;
+  __syncthreads();
+  if (t < n_nodes) {
+    int j = t;
+    for (int hops = 0; j >= 0 && hops <= DART_MAX_K; ++hops) {   // depth <= K: bounded walk
+      mask_out[(size_t)t * budget + j] = 1;
+      j = sh.out_par[j];
+    }
+  }
+}
+
+hipError_t launch_prune(int batch, const int32_t *ids, const float *scores, int K,
+                        const int32_t *ctx_tail, const NgramTableDev &tab,
+                        const dart_prune_params &p, const PruneLevelWeights &lw, int32_t *tokens,
+                        int32_t *parents, uint8_t *mask, int32_t *n_nodes, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)prune_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)sizeof(PruneShared));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(prune_kernel, dim3(batch), dim3(PRUNE_THREADS), sizeof(PruneShared), st, ids,
+                     scores, K, ctx_tail, tab, p.k, p.beam_w, p.budget, p.w_ng, lw, tokens, parents,
+                     mask, n_nodes);
+  return hipGetLastError();
+}
+
+}  // namespace dart

@@ -1,0 +1,78 @@
+// After the fused Q/K/V projection: per-head RMSNorm of q and k (optional), rotary
+// positions, and the append of the new K/V rows to the draft layer's K/V buffers.
+// The draft is a single layer (paper Sec. 3.2), so K/V of a row depend on that row only and
+// can be kept across draft-verify iterations.
+#include "common.h"
+#include "dart_internal.h"
+
+namespace dart {
+
+// grid (M rows, Hq + 2*Hkv heads), block = head_dim threads.
+// Row i sits at absolute position pos0+i; the last Kq rows are the query rows.
+template <typename T, typename QT>
+__global__ __launch_bounds__(128) void qkv_post_kernel(
+    const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride, int M, int Kq,
+    int pos0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
+    const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
+    const float *__restrict__ sin_tab, QT *__restrict__ q_out, T *__restrict__ kbuf,
+    T *__restrict__ vbuf, int t_cap, int v_transposed) {
+  __shared__ float red[16];
+  __shared__ float sh[128];
+  const int i = blockIdx.x, hh = blockIdx.y, t = threadIdx.x;
+  const int pos = pos0 + i;
+  const bool is_q = hh < Hq, is_k = !is_q && hh < Hq + Hkv;
+  if (is_q && i < M - Kq) return;                 // non-query rows need no q (uniform per block)
+  const int col = hh * hd + t;                    // q heads, then k heads, then v heads
+  float x = 0.f;
+  for (int c = 0; c < chunks; ++c) x += qkv[c * chunk_stride + (size_t)i * row_stride + col];
+
+  if (!is_q && !is_k) {                           // value head: store as is
+    const int g = hh - Hq - Hkv;
+    if (v_transposed)
+      vbuf[((size_t)g * hd + t) * t_cap + pos] = from_f32<T>(x);
+    else
+      vbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<T>(x);
+    return;
+  }
+  if (qk_norm) {
+    const float ss = block_sum(x * x, red);
+    x = x * (1.0f / sqrtf(ss / (float)hd + eps)) * to_f32((is_q ? q_gain : k_gain)[t]);
+  }
+  sh[t] = x;
+  __syncthreads();
+  const int half = hd >> 1;
+  const int fi = t < half ? t : t - half;
+  const float c = cos_tab[(size_t)pos * half + fi], s = sin_tab[(size_t)pos * half + fi];
+  const float y = t < half ? x * c - sh[t + half] * s : x * c + sh[t - half] * s;
+  if (is_q) {
+    const int qi = i - (M - Kq);
+    q_out[((size_t)qi * Hq + hh) * hd + t] = from_f32<QT>(y);
+  } else {
+    const int g = hh - Hq;
+    kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<T>(y);
+  }
+}
+
+hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chunks,
+                           size_t chunk_stride, int M, int Kq, int pos0, hipStream_t st) {
+  const dart_config &g = c->cfg;
+  const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
+  const size_t seq_elems = (size_t)Hkv * c->t_cap * hd;
+  dim3 grid(M, Hq + 2 * Hkv), block(hd);
+  if (g.dtype == DART_BF16) {
+    bf16_t *kb = (bf16_t *)c->kbuf + seq * seq_elems, *vb = (bf16_t *)c->vbuf + seq * seq_elems;
+    hipLaunchKernelGGL((qkv_post_kernel<bf16_t, bf16_t>), grid, block, 0, st, qkv, chunks,
+                       chunk_stride, c->qkv_dim, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
+                       (const bf16_t *)c->g_q, (const bf16_t *)c->g_k, c->rope_cos, c->rope_sin,
+                       (bf16_t *)c->qrot, kb, vb, c->t_cap, 1);
+  } else {
+    float *kb = (float *)c->kbuf + seq * seq_elems, *vb = (float *)c->vbuf + seq * seq_elems;
+    hipLaunchKernelGGL((qkv_post_kernel<float, float>), grid, block, 0, st, qkv, chunks,
+                       chunk_stride, c->qkv_dim, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
+                       (const float *)c->g_q, (const float *)c->g_k, c->rope_cos, c->rope_sin,
+                       (float *)c->qrot, kb, vb, c->t_cap, 0);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace dart

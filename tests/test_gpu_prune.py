@@ -1,0 +1,140 @@
+"""GPU parity: dart_tree_prune against the oracle's Alg. 1 -- tokens, parents, mask and node
+count bit for bit, on planted hit / partial-hit / miss workloads."""
+import numpy as np
+import pytest
+
+import dart_synth as ds
+from oracle.ngram import NgramModel
+from oracle import tree_prune as otp
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_prune(cases, params):
+    """cases share one table (the first one's) unless a single case is given."""
+    import torch
+    import paper_2601_19278_amd as dart
+    pc0 = cases[0]
+    table = dart.NgramTable(pc0.table.n_gram, pc0.table.keys, pc0.table.succ_ids,
+                            pc0.table.succ_counts, 1e-9)
+    ids = torch.from_numpy(np.stack([c.ids[:, :params.k] for c in cases])).cuda()
+    scores = torch.from_numpy(np.stack([c.scores[:, :params.k] for c in cases])).cuda()
+    tails = torch.from_numpy(np.stack([c.ctx_tail for c in cases])).cuda()
+    gp = dart.PruneParams(k=params.k, beam_w=params.beam_w, budget=params.budget, w_ng=params.w_ng,
+                          logit_decay=params.logit_decay, level_pow=params.level_pow)
+    out = table.tree_prune(ids, scores, tails, gp)
+    torch.cuda.synchronize()
+    res = [t.cpu().numpy() for t in out]
+    table.close()
+    return res
+
+
+def _compare(case, model, params, tokens, parents, mask, n_nodes):
+    ref = otp.tree_prune(case.ids, case.scores, case.ctx_tail, model, params)
+    assert int(n_nodes) == ref.n_nodes
+    np.testing.assert_array_equal(tokens, ref.tokens)
+    np.testing.assert_array_equal(parents, ref.parents)
+    np.testing.assert_array_equal(mask, ref.mask)
+
+
+@pytest.mark.parametrize("n_gram,K,k,w,budget,S", [
+    (2, 4, 4, 4, 16, 16),        # small preset: bigram, budget 16
+    (3, 8, 8, 20, 60, 64),       # 1.7B-shaped preset
+    (3, 8, 10, 20, 60, 64),      # 8B / 14B presets
+    (3, 8, 25, 20, 60, 64),      # paper defaults k=25, w=20, theta=59
+    (3, 16, 64, 64, 128, 64),    # every limit at its maximum
+    (3, 1, 1, 1, 1, 8), (3, 3, 2, 1, 2, 8), (2, 5, 3, 64, 128, 1),
+])
+def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
+    params = otp.PruneParams(k=k, beam_w=w, budget=budget)
+    n_cases = 6 if k * w > 1000 else 24
+    for seed in range(n_cases):
+        case = ds.make_prune_case(7000 + seed, vocab=151936, K=K, k=k, n_gram=n_gram, S=S)
+        model = NgramModel(n_gram, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
+        tokens, parents, mask, n_nodes = _gpu_prune([case], params)
+        _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
+
+
+def test_batch_of_sequences_shares_one_table():
+    K, k = 8, 10
+    params = otp.PruneParams(k=k, beam_w=20, budget=60)
+    base = ds.make_prune_case(7100, vocab=151936, K=K, k=k, n_gram=3, S=64)
+    cases = [base]
+    for b in range(1, 16):          # other sequences: their own candidates, the shared table
+        other = ds.make_prune_case(7100 + b, vocab=151936, K=K, k=k, n_gram=3, S=64)
+        mix = ds.PruneCase(np.where(np.arange(k)[None, :] % 2 == 0, base.ids, other.ids).astype(np.int32),
+                           other.scores, base.ctx_tail if b % 2 else other.ctx_tail, base.table)
+        cases.append(mix)
+    model = NgramModel(3, base.table.keys, base.table.succ_ids, base.table.succ_counts, 1e-9)
+    tokens, parents, mask, n_nodes = _gpu_prune(cases, params)
+    for b, case in enumerate(cases):
+        _compare(case, model, params, tokens[b], parents[b], mask[b], n_nodes[b])
+
+
+def test_weights_variants_and_empty_table():
+    K, k = 6, 5
+    case = ds.make_prune_case(7200, vocab=50000, K=K, k=k, n_gram=3, S=32)
+    model = NgramModel(3, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
+    for params in (otp.PruneParams(k=k, beam_w=7, budget=33, w_ng=0.0),
+                   otp.PruneParams(k=k, beam_w=7, budget=33, w_ng=1.5, logit_decay=0.5, level_pow=0.0),
+                   otp.PruneParams(k=k, beam_w=64, budget=128)):
+        tokens, parents, mask, n_nodes = _gpu_prune([case], params)
+        _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
+    empty = ds.NgramCounts(3, np.zeros((0, 2), np.int32), np.zeros((0, 32), np.int32),
+                           np.zeros((0, 32), np.int32))
+    case2 = ds.PruneCase(case.ids, case.scores, case.ctx_tail, empty)
+    model2 = NgramModel(3, empty.keys, empty.succ_ids, empty.succ_counts, 1e-9)
+    params = otp.PruneParams(k=k, beam_w=7, budget=33)
+    tokens, parents, mask, n_nodes = _gpu_prune([case2], params)
+    _compare(case2, model2, params, tokens[0], parents[0], mask[0], n_nodes[0])
+
+
+def test_all_scores_tie():
+    """Every node ties: the cuts fall back to (level asc, creation asc)."""
+    K, k = 4, 3
+    case = ds.make_prune_case(7300, vocab=1000, K=K, k=k, n_gram=2, S=4)
+    case = ds.PruneCase(case.ids, np.zeros_like(case.scores), case.ctx_tail, case.table)
+    model = NgramModel(2, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
+    for budget in (2, 5, 14, 40):
+        params = otp.PruneParams(k=k, beam_w=2, budget=budget, w_ng=0.0)
+        tokens, parents, mask, n_nodes = _gpu_prune([case], params)
+        _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
+
+
+def test_preset_tables_dense_bigram_and_hashed_trigram():
+    """Tables drawn with the presets' recipe (C1 dense bigram; a 2^16-key trigram table)."""
+    for cfg, n_keys in ((ds.get_config("C1"), None), (ds.get_config("C2"), 1 << 16)):
+        counts = ds.make_ngram_counts(cfg, 7400, n_keys=n_keys)
+        model = NgramModel(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
+        rng = np.random.default_rng(7401)
+        params = otp.PruneParams(k=cfg.topk, beam_w=cfg.beam_w, budget=cfg.budget)
+        for rep in range(8):
+            # walk real table rows so that levels hit: level L candidates = successors of a key
+            key = counts.keys[rng.integers(len(counts.keys))]
+            ids = np.empty((cfg.K, cfg.topk), dtype=np.int32)
+            for L in range(cfg.K):
+                row = counts.succ_ids[rng.integers(len(counts.keys))]
+                pick = rng.permutation(row)[: cfg.topk // 2]
+                rest = rng.integers(0, cfg.vocab, size=cfg.topk * 2)
+                rest = [t for t in dict.fromkeys(rest.tolist()) if t not in set(pick.tolist())]
+                ids[L] = np.concatenate([pick, rest[: cfg.topk - len(pick)]])
+            scores = -np.cumsum(rng.exponential(0.5, size=(cfg.K, cfg.topk)), axis=1).astype(np.float32)
+            case = ds.PruneCase(ids, scores, key.astype(np.int32), counts)
+            tokens, parents, mask, n_nodes = _gpu_prune([case], params)
+            _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
+
+
+def test_repeat_runs_are_bit_identical_and_errors():
+    import paper_2601_19278_amd as dart
+    case = ds.make_prune_case(7500, vocab=151936, K=8, k=10, n_gram=3, S=64)
+    params = otp.PruneParams(k=10, beam_w=20, budget=60)
+    first = _gpu_prune([case], params)
+    for _ in range(10):
+        again = _gpu_prune([case], params)
+        for a, b in zip(first, again):
+            np.testing.assert_array_equal(a, b)
+    for bad in (otp.PruneParams(k=10, beam_w=65, budget=60), otp.PruneParams(k=10, beam_w=20, budget=129),
+                otp.PruneParams(k=10, beam_w=20, budget=0)):
+        with pytest.raises(dart.DartError) as ei:
+            _gpu_prune([case], bad)
+        assert ei.value.status == 1
