@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of DART's drafting step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic input at Qwen3-14B shapes
+(preset C4: d 5120, 40/8 heads x 128, FFN 17408, vocab 151936, context 4096, K = 8):
+dart_draft_forward (warm: the prefix K/V of all but the last `--n-new` rows are cached, as
+in steady-state decoding where ~4 tokens are accepted per iteration) -> dart_topk (k = 10)
+-> dart_tree_prune (w = 20, budget 60, 2^20-key trigram table).  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(cfg, n_new: int) -> dict:
+    """Bytes the step must move once: every weight (2 B) + the draft K/V rows read by attention
+    (+ the fp32 logits written by the LM head, counted with the LM head)."""
+    p = cfg.n_params()
+    T = cfg.ctx + cfg.K - 1
+    kv = 2 * cfg.n_kv_heads * T * cfg.head_dim * 2
+    lm = p["lm_head"] * 2 + cfg.K * cfg.vocab * 4
+    return {"weights": p["total"] * 2, "kv": kv, "lm_head_kernel": lm,
+            "forward": p["total"] * 2 + kv + cfg.K * cfg.vocab * 4}
+
+
+def event_time_us(fn, iters: int, torch) -> float:
+    """Average GPU time of fn() in us, HIP events on the current stream (the one the library
+    launches on)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1000.0 / iters
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--n-new", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU hot path; run with --gpus 1 "
+              "(no multi-GPU figure is produced)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import dart_synth as ds
+    import paper_2601_19278_amd as dart
+
+    cfg = ds.get_config(args.workload)
+    seed = 1000 * int(args.workload[1:])
+    t0 = time.perf_counter()
+    W = ds.make_weights(cfg, seed)
+    hidden = ds.make_hidden(cfg, seed + 1)
+    counts = ds.make_ngram_counts(cfg, seed + 2)
+    t_gen = time.perf_counter() - t0
+    ctx = dart.DraftContext(cfg, W, max_batch=1)
+    table = dart.NgramTable(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
+    h_dev = dart.bf16_bits_to_tensor(hidden) if cfg.dtype == "bf16" else torch.from_numpy(hidden).cuda()
+    tail_np = counts.keys[0].astype(np.int32)
+    tail = torch.from_numpy(tail_np).cuda()[None]
+    params = dart.PruneParams(k=cfg.topk, beam_w=cfg.beam_w, budget=cfg.budget)
+    n, K, k = cfg.ctx, cfg.K, cfg.topk
+    dev = h_dev.device
+    logits = torch.empty((K, cfg.vocab), dtype=torch.float32, device=dev)
+    tk = (torch.empty((K, k), dtype=torch.int32, device=dev),
+          torch.empty((K, k), dtype=torch.float32, device=dev))
+    tree = (torch.empty((1, cfg.budget), dtype=torch.int32, device=dev),
+            torch.empty((1, cfg.budget), dtype=torch.int32, device=dev),
+            torch.empty((1, cfg.budget, cfg.budget), dtype=torch.uint8, device=dev),
+            torch.empty((1,), dtype=torch.int32, device=dev))
+
+    def forward(n_cached):
+        ctx.draft_forward(h_dev, n, K, n_cached=n_cached, out=logits)
+
+    def topk():
+        ctx.topk(logits, k, 1e-9, out=tk)
+
+    def prune():
+        table.tree_prune(tk[0][None], tk[1][None], tail, params, out=tree)
+
+    def step():
+        forward(n - args.n_new)
+        topk()
+        prune()
+
+    # cold call (no cached K/V) first: it also fills the cache for the warm steps
+    ctx.reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    forward(0)
+    torch.cuda.synchronize()
+    cold_us = (time.perf_counter() - t0) * 1e6
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    step_us = (time.perf_counter() - t0) * 1e6 / args.steps
+
+    it = max(20, min(100, args.steps))
+    stages = {
+        "forward_warm_us": event_time_us(lambda: forward(n - args.n_new), it, torch),
+        "forward_warm_n1_us": event_time_us(lambda: forward(n - 1), it, torch),
+        "topk_us": event_time_us(topk, it, torch),
+        "prune_us": event_time_us(prune, it, torch),
+        "step_gpu_us": event_time_us(step, it, torch),
+        "cold_forward_us": cold_us,
+    }
+    lm_us = event_time_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
+    forward(n - args.n_new)          # leave the buffers consistent
+    ab = algorithmic_bytes(cfg, args.n_new)
+    achieved = ab["lm_head_kernel"] / (lm_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "gemv_bf16_kernel (LM head)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": None, "kernel_us": round(lm_us, 2),
+                "algorithmic_bytes": ab["lm_head_kernel"]}
+    stages["lm_head_us"] = lm_us
+    stages["forward_GBps"] = ab["forward"] / (stages["forward_warm_us"] * 1e-6) / 1e9
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import draft_forward as odf, topk as otk, tree_prune as otp
+        from oracle.ngram import NgramModel
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        model = NgramModel(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
+        t0 = time.perf_counter()
+        ref = odf.draft_forward(cfg, W, hidden, K)
+        ids, scores = otk.topk_rows(ref, k, 1e-9)
+        otp.tree_prune(ids, scores, tail_np, model, otp.PruneParams(k=k, beam_w=cfg.beam_w, budget=cfg.budget))
+        cpu_s = time.perf_counter() - t0
+        cpu = {"value": round(cpu_s * 1e6, 0), "unit": "us", "cores": int(cores), "kind": "oracle",
+               "sample": f"1 full {cfg.name} draft step (fp64 forward over the whole context, full-sort "
+                         "top-k, Alg. 1 pruning), one repetition, N-gram dictionary build excluded"}
+        err = float(np.abs(logits.cpu().numpy() - ref).max())
+        stages["max_abs_logit_err_vs_oracle"] = err
+
+    out = {
+        "metric": "draft-step latency (K=8) at Qwen3-14B shapes", "value": round(step_us, 2),
+        "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(step_us / 1000.0, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: d={cfg.d} heads={cfg.n_q_heads}/{cfg.n_kv_heads}x{cfg.head_dim} "
+                               f"ffn={cfg.ffn} vocab={cfg.vocab} ctx={cfg.ctx} K={cfg.K} topk={cfg.topk} "
+                               f"beam_w={cfg.beam_w} budget={cfg.budget} trigram_keys={cfg.n_keys} "
+                               f"batch=1 warm n_new={args.n_new}"},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "stages": {a: (round(b, 2) if b >= 1.0 else float(f"{b:.3e}")) if isinstance(b, float) else b
+                   for a, b in stages.items()},
+        "input_gen_s": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -9,6 +9,8 @@ path read exactly those bits.
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 from .configs import DraftConfig
@@ -43,22 +45,32 @@ def _shapes(cfg: DraftConfig, max_K: int) -> dict:
     }
 
 
-def _draw(rng: np.random.Generator, shape, kind: str, store_bf16: bool) -> np.ndarray:
-    """Draw one tensor in row chunks (bounded temporary memory for the LM head)."""
+def _draw(seed_words, shape, kind: str, store_bf16: bool) -> np.ndarray:
+    """Draw one tensor in row chunks, each chunk from its own seeded stream (so chunks can be
+    drawn in parallel and the result does not depend on the number of workers)."""
     shape = tuple(shape)
     rows = shape[0]
     cols = int(np.prod(shape[1:])) if len(shape) > 1 else 1
     out = np.empty(shape, dtype=np.uint16 if store_bf16 else np.float32)
     flat = out.reshape(rows, cols)
     step = max(1, (1 << 24) // cols)
-    for r0 in range(0, rows, step):
-        r1 = min(rows, r0 + step)
+
+    def fill(c: int) -> None:
+        r0, r1 = c * step, min(rows, (c + 1) * step)
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([*seed_words, c])))
         z = rng.standard_normal((r1 - r0, cols), dtype=np.float32)
         if kind == "gain":
             z = np.float32(1.0) + np.float32(0.1) * z
         elif kind == "small":
             z = np.float32(0.02) * z
         flat[r0:r1] = f32_to_bf16_bits(z) if store_bf16 else z
+
+    n_chunks = (rows + step - 1) // step
+    if n_chunks == 1:
+        fill(0)
+    else:
+        with ThreadPoolExecutor(max_workers=8) as pool:
+            list(pool.map(fill, range(n_chunks)))
     return out
 
 
@@ -68,18 +80,16 @@ def make_weights(cfg: DraftConfig, seed: int, max_K: int | None = None) -> dict:
     store_bf16 = cfg.dtype == "bf16"
     out = {}
     for idx, (name, shape) in enumerate(_shapes(cfg, max_K).items()):
-        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 101, idx])))
         kind = "gain" if name in ("w_in_norm", "q_norm", "k_norm", "w_post_norm",
                                   "w_final_norm") else "small"
-        out[name] = _draw(rng, shape, kind, store_bf16)
+        out[name] = _draw([seed, 101, idx], shape, kind, store_bf16)
     return out
 
 
 def make_hidden(cfg: DraftConfig, seed: int, n: int | None = None) -> np.ndarray:
     """Target hidden states of an n-token prefix, N(0, 1), [n][d]."""
     n = cfg.ctx if n is None else n
-    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 202])))
-    return _draw(rng, (n, cfg.d), "unit", cfg.dtype == "bf16")
+    return _draw([seed, 202], (n, cfg.d), "unit", cfg.dtype == "bf16")
 
 
 def make_ragged_lengths(cfg: DraftConfig, seed: int) -> np.ndarray:

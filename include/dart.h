@@ -183,6 +183,11 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
  * copied (at most max_count) or -1 on error. */
 int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_t max_count);
 
+/* Diagnostic (benchmark only): enqueue only the LM-head projection (the final step of
+ * dart_draft_forward, Sec. 3.2) on the final-normed rows the last forward call left in the
+ * workspace; logits_out device [K][vocab] fp32.  Used to time that kernel in isolation. */
+dart_status dart_debug_lm_head(dart_ctx *ctx, int K, float *logits_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

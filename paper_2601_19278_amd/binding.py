@@ -13,7 +13,7 @@ _LIB = None
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
     "dart_draft_forward_batched", "dart_topk", "dart_ngram_create", "dart_ngram_destroy",
-    "dart_tree_prune", "dart_debug_read",
+    "dart_tree_prune", "dart_debug_read", "dart_debug_lm_head",
 )
 
 DART_F32, DART_BF16 = 0, 1
@@ -67,6 +67,9 @@ def load_library() -> C.CDLL:
     path = library_path()
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2601_19278_amd.build`")
+    # PyTorch ships its own HIP runtime (same SONAME as the system one).  Import it first so
+    # that libdart.so binds to that copy; two HIP runtimes in one process cannot share the GPU.
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, i32, i64, f32 = C.c_void_p, C.c_int, C.c_int64, C.c_float
     lib.dart_status_str.restype = C.c_char_p
@@ -86,6 +89,7 @@ def load_library() -> C.CDLL:
                                     vp, vp]
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
+    lib.dart_debug_lm_head.argtypes = [vp, i32, vp, vp]
     _LIB = lib
     return lib
 
@@ -185,15 +189,24 @@ class DraftContext:
                "dart_draft_forward_batched")
         return out
 
-    def topk(self, logits, k: int, eps: float = 1e-9, stream=None):
-        """dart_topk: logits CUDA fp32 [rows][vocab] -> (ids int32 [rows][k], scores fp32)."""
+    def topk(self, logits, k: int, eps: float = 1e-9, stream=None, out=None):
+        """dart_topk: logits CUDA fp32 [rows][vocab] -> (ids int32 [rows][k], scores fp32).
+        `out` may carry preallocated (ids, scores) tensors."""
         torch = _torch()
         rows, vocab = logits.shape
-        ids = torch.empty((rows, k), dtype=torch.int32, device=logits.device)
-        scores = torch.empty((rows, k), dtype=torch.float32, device=logits.device)
+        if out is None:
+            ids = torch.empty((rows, k), dtype=torch.int32, device=logits.device)
+            scores = torch.empty((rows, k), dtype=torch.float32, device=logits.device)
+        else:
+            ids, scores = out
         _check(self._lib.dart_topk(self._h, logits.data_ptr(), rows, vocab, k, eps, ids.data_ptr(),
                                    scores.data_ptr(), _stream_ptr(stream)), "dart_topk")
         return ids, scores
+
+    def debug_lm_head(self, K: int, out, stream=None):
+        _check(self._lib.dart_debug_lm_head(self._h, K, out.data_ptr(), _stream_ptr(stream)),
+               "dart_debug_lm_head")
+        return out
 
     def debug_read(self, name: str, rows: int, cols: int) -> np.ndarray:
         buf = np.empty(16 * cols, dtype=np.float32)
@@ -227,11 +240,12 @@ class NgramTable:
 
     __del__ = close
 
-    def tree_prune(self, ids, scores, ctx_tail, params: PruneParams, stream=None):
+    def tree_prune(self, ids, scores, ctx_tail, params: PruneParams, stream=None, out=None):
         """dart_tree_prune: ids/scores CUDA [batch][K][k] (or [K][k]); ctx_tail [batch][N-1].
 
         Returns tokens [batch][budget], parents [batch][budget], mask [batch][budget][budget],
-        n_nodes [batch] (CUDA tensors; the batch axis is dropped for 2-D inputs)."""
+        n_nodes [batch] (CUDA tensors; the batch axis is dropped for 2-D inputs).  `out` may
+        carry preallocated (tokens, parents, mask, n_nodes) tensors of the batched shapes."""
         torch = _torch()
         squeeze = ids.dim() == 2
         if squeeze:
@@ -243,10 +257,13 @@ class NgramTable:
         scores = scores.contiguous()
         ctx_tail = ctx_tail.contiguous()
         dev = ids.device
-        tokens = torch.empty((B, params.budget), dtype=torch.int32, device=dev)
-        parents = torch.empty((B, params.budget), dtype=torch.int32, device=dev)
-        mask = torch.empty((B, params.budget, params.budget), dtype=torch.uint8, device=dev)
-        n_nodes = torch.empty((B,), dtype=torch.int32, device=dev)
+        if out is None:
+            tokens = torch.empty((B, params.budget), dtype=torch.int32, device=dev)
+            parents = torch.empty((B, params.budget), dtype=torch.int32, device=dev)
+            mask = torch.empty((B, params.budget, params.budget), dtype=torch.uint8, device=dev)
+            n_nodes = torch.empty((B,), dtype=torch.int32, device=dev)
+        else:
+            tokens, parents, mask, n_nodes = out
         p = _PruneParams(params.k, params.beam_w, params.budget, params.w_ng, params.logit_decay,
                          params.level_pow)
         _check(self._lib.dart_tree_prune(B, ids.data_ptr(), scores.data_ptr(), K,

@@ -5,7 +5,10 @@
 
 typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
 
+typedef _Float16 f16_t;
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 #define DART_WAVE 64
@@ -23,10 +26,15 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+__device__ __forceinline__ float to_f32(f16_t v) { return (float)v; }
 
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+// fp16 (round-to-nearest-even), saturating at the largest finite value instead of overflowing
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) {
+  return (f16_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -483,6 +483,15 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
                                parents_out, mask_out, n_nodes_out, (hipStream_t)stream));
 }
 
+// Diagnostic: run only the LM-head projection again on the final-normed rows the last forward
+// call left in the workspace (used to time that kernel in isolation).
+dart_status dart_debug_lm_head(dart_ctx *c, int K, float *logits_out, void *stream) {
+  if (!c || !logits_out || K < 1 || K > c->cfg.max_K) return DART_ERR_ARG;
+  int chunks = 1;
+  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, &chunks,
+                          (hipStream_t)stream));
+}
+
 // Diagnostic: copy a named fp32 workspace of the last forward to host memory (synchronises).
 // Names: xn, resid, qkv, att_out, y, yn, hmid, u.  Returns the number of floats copied or -1.
 int64_t dart_debug_read(dart_ctx *c, const char *name, float *host_out, int64_t max_count) {

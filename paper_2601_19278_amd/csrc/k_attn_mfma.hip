@@ -1,4 +1,11 @@
-// Masked-position attention of the draft layer on bf16 K/V buffers, MFMA 16x16x32 bf16.
+// Masked-position attention of the draft layer for the bf16 configuration, MFMA 16x16x32.
+//
+// q, the K/V buffers and the soft-max probabilities are held in fp16 (fp32 accumulate): they
+// are the library's own intermediates, cost the same bytes as bf16, and their 11-bit
+// significand keeps the rounding of the attention path an order of magnitude below the
+// logit tolerance, which bf16's 8 bits do not (mask rows carry a tiny residual, so the
+// final RMSNorm amplifies relative errors of the attention output).  Values are bounded
+// (soft-max weights, normalised/rotated q and k); stores saturate at the fp16 maximum.
 //
 // K = up to 16 query rows times Hq/Hkv query heads share each K/V head, so the scores of
 // one K/V head are a (keys x 128 dims) x (128 dims x up-to-128 queries) contraction: small,
@@ -21,20 +28,18 @@
 
 namespace dart {
 
-typedef __attribute__((ext_vector_type(4))) uint16_t u16x4_t;
-
-union Bf16x8 {
-  bf16x8_t v;
+union F16x8 {
+  f16x8_t v;
   uint4 u;
   uint2 h[2];
-  bf16_t e[8];
+  f16_t e[8];
 };
 
 template <int HD, int MT>
-__global__ __launch_bounds__(256) void attn_split_bf16_kernel(
-    const bf16_t *__restrict__ q,     // [Kq][Hq][HD]
-    const bf16_t *__restrict__ kbuf,  // [Hkv][t_cap][HD]
-    const bf16_t *__restrict__ vtbuf, // [Hkv][HD][t_cap]
+__global__ __launch_bounds__(256) void attn_split_mfma_kernel(
+    const f16_t *__restrict__ q,      // [Kq][Hq][HD]
+    const f16_t *__restrict__ kbuf,   // [Hkv][t_cap][HD]
+    const f16_t *__restrict__ vtbuf,  // [Hkv][HD][t_cap]
     int t_cap, int n, int Kq, int Hq, int group, int chunk, float scale, int nsplit,
     float *__restrict__ o_part, float *__restrict__ ml_part) {
   constexpr int KS = HD / 32;        // k-steps of the score product
@@ -48,7 +53,7 @@ __global__ __launch_bounds__(256) void attn_split_bf16_kernel(
   const int j_end = min(j_begin + chunk, T);
 
   // B operands of the score product: this lane's query column, all k-steps, MT tiles
-  Bf16x8 qop[MT][KS];
+  F16x8 qop[MT][KS];
   int qrow[MT];                      // query row i of this lane's column (-1: padding)
   size_t qslot[MT];                  // global query-vector index
 #pragma unroll
@@ -77,12 +82,12 @@ __global__ __launch_bounds__(256) void attn_split_bf16_kernel(
     for (int t = 0; t < DTW; ++t) acc[a][t] = {0.f, 0.f, 0.f, 0.f};
   }
 
-  const bf16_t *kb = kbuf + (size_t)g * t_cap * HD;
-  const bf16_t *vt = vtbuf + (size_t)g * HD * t_cap;
+  const f16_t *kb = kbuf + (size_t)g * t_cap * HD;
+  const f16_t *vt = vtbuf + (size_t)g * HD * t_cap;
 
   for (int jb = j_begin; jb < j_end; jb += 32) {
     // A operands: two 16-key tiles of K, and this wavefront's V^T dim tiles
-    Bf16x8 kop[2][KS], vop[DTW];
+    F16x8 kop[2][KS], vop[DTW];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
@@ -91,7 +96,7 @@ __global__ __launch_bounds__(256) void attn_split_bf16_kernel(
             kb + (size_t)(jb + 16 * tt + col) * HD + 32 * ks + 8 * gq);
 #pragma unroll
     for (int t = 0; t < DTW; ++t) {
-      const bf16_t *row = vt + (size_t)(16 * (DTW * wave + t) + col) * t_cap + jb + 4 * gq;
+      const f16_t *row = vt + (size_t)(16 * (DTW * wave + t) + col) * t_cap + jb + 4 * gq;
       vop[t].h[0] = *reinterpret_cast<const uint2 *>(row);
       vop[t].h[1] = *reinterpret_cast<const uint2 *>(row + 16);
     }
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(256) void attn_split_bf16_kernel(
         s[tt] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[tt][ks].v, qop[a][ks].v, s[tt], 0, 0, 0);
+          s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kop[tt][ks].v, qop[a][ks].v, s[tt], 0, 0, 0);
       }
       // mask + running soft-max statistics of this lane's query column
       const int last = n - 1 + qrow[a];            // qrow = -1 -> nothing visible beyond n-2; unused
@@ -123,14 +128,14 @@ __global__ __launch_bounds__(256) void attn_split_bf16_kernel(
       const float mn = fmaxf(m[a], mloc);
       const float corr = expf(m[a] - mn);
       float lsum = 0.f;
-      Bf16x8 pop;
+      F16x8 pop;
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const float p = s[tt][r] > -1.0e38f ? expf(s[tt][r] - mn) : 0.f;
           lsum += p;
-          pop.e[4 * tt + r] = f32_to_bf16(p);
+          pop.e[4 * tt + r] = (f16_t)p;
         }
       lsum += __shfl_xor(lsum, 16, DART_WAVE);
       lsum += __shfl_xor(lsum, 32, DART_WAVE);
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(256) void attn_split_bf16_kernel(
 #pragma unroll
       for (int t = 0; t < DTW; ++t) {
         acc[a][t] *= corr;
-        acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[t].v, pop.v, acc[a][t], 0, 0, 0);
+        acc[a][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop[t].v, pop.v, acc[a][t], 0, 0, 0);
       }
     }
   }
@@ -166,10 +171,10 @@ static hipError_t launch_one(const dart_ctx *c, int seq, int n, int Kq, int chun
                              int zgroups, hipStream_t st) {
   const dart_config &g = c->cfg;
   const size_t seq_elems = (size_t)g.n_kv_heads * c->t_cap * HD;
-  const bf16_t *kb = (const bf16_t *)c->kbuf + seq * seq_elems;
-  const bf16_t *vt = (const bf16_t *)c->vbuf + seq * seq_elems;
-  hipLaunchKernelGGL((attn_split_bf16_kernel<HD, MT>), dim3(nsplit, g.n_kv_heads, zgroups),
-                     dim3(256), 0, st, (const bf16_t *)c->qrot, kb, vt, c->t_cap, n, Kq,
+  const f16_t *kb = (const f16_t *)c->kbuf + seq * seq_elems;
+  const f16_t *vt = (const f16_t *)c->vbuf + seq * seq_elems;
+  hipLaunchKernelGGL((attn_split_mfma_kernel<HD, MT>), dim3(nsplit, g.n_kv_heads, zgroups),
+                     dim3(256), 0, st, (const f16_t *)c->qrot, kb, vt, c->t_cap, n, Kq,
                      g.n_q_heads, g.n_q_heads / g.n_kv_heads, chunk, 1.0f / sqrtf((float)HD), nsplit,
                      c->att_part, c->att_ml);
   return hipGetLastError();

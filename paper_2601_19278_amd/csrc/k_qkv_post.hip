@@ -9,13 +9,14 @@ namespace dart {
 
 // grid (M rows, Hq + 2*Hkv heads), block = head_dim threads.
 // Row i sits at absolute position pos0+i; the last Kq rows are the query rows.
-template <typename T, typename QT>
+// T: storage type of the norm gains; CT: element type of q and of the K/V buffers.
+template <typename T, typename CT>
 __global__ __launch_bounds__(128) void qkv_post_kernel(
     const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride, int M, int Kq,
     int pos0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
     const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
-    const float *__restrict__ sin_tab, QT *__restrict__ q_out, T *__restrict__ kbuf,
-    T *__restrict__ vbuf, int t_cap, int v_transposed) {
+    const float *__restrict__ sin_tab, CT *__restrict__ q_out, CT *__restrict__ kbuf,
+    CT *__restrict__ vbuf, int t_cap, int v_transposed) {
   __shared__ float red[16];
   __shared__ float sh[128];
   const int i = blockIdx.x, hh = blockIdx.y, t = threadIdx.x;
@@ -29,9 +30,9 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
   if (!is_q && !is_k) {                           // value head: store as is
     const int g = hh - Hq - Hkv;
     if (v_transposed)
-      vbuf[((size_t)g * hd + t) * t_cap + pos] = from_f32<T>(x);
+      vbuf[((size_t)g * hd + t) * t_cap + pos] = from_f32<CT>(x);
     else
-      vbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<T>(x);
+      vbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(x);
     return;
   }
   if (qk_norm) {
@@ -46,10 +47,10 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
   const float y = t < half ? x * c - sh[t + half] * s : x * c + sh[t - half] * s;
   if (is_q) {
     const int qi = i - (M - Kq);
-    q_out[((size_t)qi * Hq + hh) * hd + t] = from_f32<QT>(y);
+    q_out[((size_t)qi * Hq + hh) * hd + t] = from_f32<CT>(y);
   } else {
     const int g = hh - Hq;
-    kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<T>(y);
+    kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(y);
   }
 }
 
@@ -60,11 +61,11 @@ hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chu
   const size_t seq_elems = (size_t)Hkv * c->t_cap * hd;
   dim3 grid(M, Hq + 2 * Hkv), block(hd);
   if (g.dtype == DART_BF16) {
-    bf16_t *kb = (bf16_t *)c->kbuf + seq * seq_elems, *vb = (bf16_t *)c->vbuf + seq * seq_elems;
-    hipLaunchKernelGGL((qkv_post_kernel<bf16_t, bf16_t>), grid, block, 0, st, qkv, chunks,
+    f16_t *kb = (f16_t *)c->kbuf + seq * seq_elems, *vb = (f16_t *)c->vbuf + seq * seq_elems;
+    hipLaunchKernelGGL((qkv_post_kernel<bf16_t, f16_t>), grid, block, 0, st, qkv, chunks,
                        chunk_stride, c->qkv_dim, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
                        (const bf16_t *)c->g_q, (const bf16_t *)c->g_k, c->rope_cos, c->rope_sin,
-                       (bf16_t *)c->qrot, kb, vb, c->t_cap, 1);
+                       (f16_t *)c->qrot, kb, vb, c->t_cap, 1);
   } else {
     float *kb = (float *)c->kbuf + seq * seq_elems, *vb = (float *)c->vbuf + seq * seq_elems;
     hipLaunchKernelGGL((qkv_post_kernel<float, float>), grid, block, 0, st, qkv, chunks,
