@@ -298,9 +298,10 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
   if (g.dtype == DART_BF16) {
     if (g.d % 32 || q_dim % 32 || g.ffn % 32) return DART_ERR_ARG;
     if (gemv_bf16_chunks(g.d) != 1) return DART_ERR_ARG;   // LM head writes caller memory in one pass
-  } else if (g.d % 4 || g.ffn % 4) {
+  } else if (g.d % 8 || g.ffn % 4) {
     return DART_ERR_ARG;
   }
+  if (g.d > 16384) return DART_ERR_ARG;
   if (!w->w_in_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_post_norm || !w->w_gate ||
       !w->w_up || !w->w_down || !w->w_final_norm || !w->w_lm)
     return DART_ERR_ARG;
@@ -399,19 +400,18 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
 
   uint64_t n_slots = 16;
   while (n_slots < (uint64_t)n_keys * 2) n_slots <<= 1;
-  std::vector<uint64_t> slot_keys(n_slots, ~(uint64_t)0);
-  std::vector<int32_t> slot_rows(n_slots, -1);
+  std::vector<NgramSlot> slots(n_slots, NgramSlot{~(uint64_t)0, -1, 0});
   for (int64_t r = 0; r < n_keys; ++r) {
     const uint64_t packed = ctx_len == 2 ? ((uint64_t)(uint32_t)keys[2 * r] << 32) |
                                                (uint32_t)keys[2 * r + 1]
                                          : (uint64_t)(uint32_t)keys[r];
     uint64_t h = mix64(packed) & (n_slots - 1);
-    while (slot_keys[h] != ~(uint64_t)0) {
-      if (slot_keys[h] == packed) return DART_ERR_ARG;   // duplicate context
+    while (slots[h].key != ~(uint64_t)0) {
+      if (slots[h].key == packed) return DART_ERR_ARG;   // duplicate context
       h = (h + 1) & (n_slots - 1);
     }
-    slot_keys[h] = packed;
-    slot_rows[h] = (int32_t)r;
+    slots[h].key = packed;
+    slots[h].row = (int32_t)r;
   }
   // s_ng = log(Pr + eps), Pr = count / sum of the row's counts (App. D); fp64 then one rounding
   const double eps_d = (double)eps;
@@ -434,8 +434,7 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
   }
   dart_ngram *t = new (std::nothrow) dart_ngram();
   if (!t) return DART_ERR_OOM;
-  hipError_t e = upload(slot_keys.data(), n_slots * 8, &t->slot_keys);
-  if (e == hipSuccess) e = upload(slot_rows.data(), n_slots * 4, &t->slot_rows);
+  hipError_t e = upload(slots.data(), n_slots * sizeof(NgramSlot), &t->slots);
   if (e == hipSuccess) e = upload(ids.data(), cells * 4, &t->succ_ids);
   if (e == hipSuccess) e = upload(logp.data(), cells * 4, &t->succ_logp);
   if (e != hipSuccess) {
@@ -446,8 +445,7 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
   t->dev.n_gram = n_gram;
   t->dev.S = S;
   t->dev.slot_mask = n_slots - 1;
-  t->dev.slot_keys = (const uint64_t *)t->slot_keys;
-  t->dev.slot_rows = (const int32_t *)t->slot_rows;
+  t->dev.slots = (const NgramSlot *)t->slots;
   t->dev.succ_ids = (const int32_t *)t->succ_ids;
   t->dev.succ_logp = (const float *)t->succ_logp;
   t->dev.logp_miss = miss;
@@ -457,7 +455,7 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
 
 void dart_ngram_destroy(dart_ngram *t) {
   if (!t) return;
-  void *bufs[] = {t->slot_keys, t->slot_rows, t->succ_ids, t->succ_logp};
+  void *bufs[] = {t->slots, t->succ_ids, t->succ_logp};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
   delete t;

@@ -18,12 +18,19 @@ struct DeviceMatrix {
   int n_real = 0;   // unpadded output features
 };
 
+// One open-addressing slot: packed context (~0 when empty) and the row it maps to, 16 bytes so
+// that a probe is a single memory access.
+struct NgramSlot {
+  uint64_t key;
+  int32_t row;
+  int32_t pad;
+};
+
 struct NgramTableDev {
   int n_gram;
   int S;                      // successors per row
   uint64_t slot_mask;         // n_slots - 1 (power of two)
-  const uint64_t *slot_keys;  // packed context or ~0 when empty
-  const int32_t *slot_rows;   // row index of the slot's context
+  const NgramSlot *slots;
   const int32_t *succ_ids;    // [n_keys][S], -1 = unused
   const float *succ_logp;     // [n_keys][S]
   float logp_miss;
@@ -31,7 +38,7 @@ struct NgramTableDev {
 
 struct dart_ngram {
   NgramTableDev dev;
-  void *slot_keys = nullptr, *slot_rows = nullptr, *succ_ids = nullptr, *succ_logp = nullptr;
+  void *slots = nullptr, *succ_ids = nullptr, *succ_logp = nullptr;
 };
 
 struct PruneLevelWeights {

@@ -17,7 +17,8 @@
 // keeps its slice of the activations (B operands, fp32 split once into bf16 hi + lo parts,
 // two MFMAs per weight tile) in registers for the whole kernel and walks the workgroup's
 // strips.  Weight tiles go through a small rolling register buffer whose loads are issued
-// right after the MFMAs that free each register (several KiB in flight per wavefront).  Per strip the 8 partial 16x16 tiles are summed through LDS in a fixed order
+// right after the MFMAs that free each register (several KiB in flight per wavefront).  Per
+// strip the 8 partial 16x16 tiles are summed through LDS in a fixed order
 // (deterministic), one barrier per strip.  When the k range is too long for the register
 // budget the range is cut into chunks handled by different workgroups, and the consumer
 // adds the chunk partials (also in fixed order).
@@ -35,33 +36,66 @@ int gemv_bf16_chunks(int Kd) {
   return (KT + GEMV_WAVES * GEMV_KPW_MAX - 1) / (GEMV_WAVES * GEMV_KPW_MAX);
 }
 
-template <int KPW, int D>
+// Tunables (fixed after measurement; the benchmark harness may override them).
+int g_gemv_wgs = 256;      // workgroups per k-chunk group: one per CU
+int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
+int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+template <bool NT>
+__device__ __forceinline__ u32x4_t load_tile(const u32x4_t *p) {
+  if constexpr (NT) {
+    return __builtin_nontemporal_load(p);
+  } else {
+    return *p;
+  }
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load (vmcnt(0)), which would drain the weight prefetch pipeline once
+// per strip; the partial tiles exchanged here live in LDS, so waiting for LDS is enough.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// M8 = true: at most 8 activation rows.  The 16 B-operand columns then carry the hi parts of
+// rows 0..7 in columns 0..7 and their lo parts in columns 8..15, so one MFMA per weight tile
+// yields both products; result[m] = D[.][m] + D[.][m+8].  M8 = false: up to 16 rows, separate
+// hi and lo operands, two MFMAs per tile.
+// EXACT = true: every wavefront owns exactly KPW k-steps (the k range divides evenly), and
+// the main loop is branch-free straight-line code -- the compiler can then keep D loads in
+// flight with exact wait counts.  EXACT = false handles ragged k ranges (unusual shapes) with
+// per-step guards and is not tuned.
+template <int KPW, int D, bool M8, bool NT, bool EXACT>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
-    const uint4 *__restrict__ Wp,   // packed tiles, 64 uint4 per tile
+    const u32x4_t *__restrict__ Wp, // packed tiles, 64 x 16 bytes per tile
     const float *__restrict__ X,    // [M][Kd]
     int M, int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols,
     float *__restrict__ out, int out_stride, size_t chunk_stride) {
   static_assert(KPW % D == 0, "a register of the rolling buffer must serve the same slots in every strip");
-  __shared__ float part[2][GEMV_WAVES][256];
+  __shared__ float part[2][GEMV_WAVES][M8 ? 256 : 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, gq = lane >> 4;
   const int chunk = blockIdx.x % nchunks;
   const int wg = blockIdx.x / nchunks, nwg = gridDim.x / nchunks;
   const int ks0 = (chunk * GEMV_WAVES + wave) * kpw;
-  const int nk = max(0, min(kpw, KT - ks0));           // wave-uniform
+  const int nk = EXACT ? KPW : max(0, min(kpw, KT - ks0));   // wave-uniform
   const int Kd = KT * 32;
 
-  // B operands: activations of this wavefront's k slice, column m = lane % 16, split into
-  // bf16 hi + bf16 lo (x ~= hi + lo to ~2^-17) so that activations keep fp32-like accuracy
-  // while the weights stay the exact bf16 values.
-  bf16x8_t bhi[KPW], blo[KPW];
+  // B operands: activations of this wavefront's k slice, split into bf16 hi + bf16 lo
+  // (x ~= hi + lo to ~2^-17) so that activations keep fp32-like accuracy while the weights
+  // stay the exact bf16 values.
+  constexpr int NB = M8 ? 1 : 2;
+  bf16x8_t bop[NB][KPW];
+  const int xrow = M8 ? (col & 7) : col;
 #pragma unroll
   for (int t = 0; t < KPW; ++t) {
     union { bf16x8_t v; bf16_t e[8]; } h, l;
 #pragma unroll
     for (int e = 0; e < 8; ++e) h.e[e] = l.e[e] = 0;
-    if (t < nk && col < M) {
-      const float *src = X + (size_t)col * Kd + (size_t)(ks0 + t) * 32 + 8 * gq;
+    if (t < nk && xrow < M) {
+      const float *src = X + (size_t)xrow * Kd + (size_t)(ks0 + t) * 32 + 8 * gq;
       const float4 lo4 = *reinterpret_cast<const float4 *>(src);
       const float4 hi4 = *reinterpret_cast<const float4 *>(src + 4);
       const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
@@ -71,54 +105,90 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
         l.e[e] = f32_to_bf16(x[e] - bf16_to_f32(h.e[e]));
       }
     }
-    bhi[t] = h.v;
-    blo[t] = l.v;
+    if (M8) {
+      bop[0][t] = col < 8 ? h.v : l.v;
+    } else {
+      bop[0][t] = h.v;
+      bop[NB - 1][t] = l.v;
+    }
   }
 
   // Rolling buffer of D weight tiles: register t % D serves slot t of every strip; the load
   // for its next slot is issued right after the MFMAs that free it, so about D KiB stay in
-  // flight per wavefront across strip boundaries.
-  union AOp { uint4 u; bf16x8_t v; };
-  AOp aop[D];
+  // flight per wavefront across strip boundaries.  After the last strip the refills re-read
+  // tiles of that same strip (in bounds, never used) so that the loop body has no branch.
+  u32x4_t aop[D];
   int s = wg;                                          // strip index relative to strip0
   if (s < nstrips) {
-    const uint4 *tile = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
+    const u32x4_t *tile = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
 #pragma unroll
     for (int r = 0; r < D; ++r)
-      if (r < nk) aop[r].u = tile[(size_t)r * 64];
+      if (r < nk) aop[r] = load_tile<NT>(tile + (size_t)r * 64);
   }
   int buf = 0;
   for (; s < nstrips; s += nwg) {
     const int sn = s + nwg;
-    const bool more = sn < nstrips;
-    const uint4 *cur = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
-    const uint4 *next = Wp + ((size_t)(strip0 + (more ? sn : s)) * KT + ks0) * 64 + lane;
+    const u32x4_t *cur = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
+    const u32x4_t *next = Wp + ((size_t)(strip0 + (sn < nstrips ? sn : s)) * KT + ks0) * 64 + lane;
+    // One accumulator chain for the hi products and one for the lo products, both in k
+    // order, so a row's result does not depend on which variant (or how many rows) ran.
     f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int t = 0; t < KPW; ++t) {
-      if (t < nk) {
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[t % D].v, bhi[t], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop[t % D].v, blo[t], acc1, 0, 0, 0);
-        if (t + D < nk)
-          aop[t % D].u = cur[(size_t)(t + D) * 64];
-        else if (more && (t % D) < nk)
-          aop[t % D].u = next[(size_t)(t % D) * 64];
+      if (EXACT || t < nk) {
+        const bf16x8_t a = __builtin_bit_cast(bf16x8_t, aop[t % D]);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[0][t], acc0, 0, 0, 0);
+        if (!M8) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[NB - 1][t], acc1, 0, 0, 0);
+        if (EXACT) {
+          aop[t % D] = load_tile<NT>(t + D < KPW ? cur + (size_t)(t + D) * 64
+                                                   : next + (size_t)(t + D - KPW) * 64);
+          // keep "MFMA, then the refill of its register" in program order: without this the
+          // scheduler groups all MFMAs before all loads and the load queue drains each strip
+          __builtin_amdgcn_sched_barrier(0);
+        } else if (t + D < nk) {
+          aop[t % D] = load_tile<NT>(cur + (size_t)(t + D) * 64);
+        } else if ((t % D) < nk) {
+          aop[t % D] = load_tile<NT>(next + (size_t)(t % D) * 64);
+        }
       }
     }
     *reinterpret_cast<float4 *>(&part[buf][wave][lane * 4]) =
-        make_float4(acc0[0] + acc1[0], acc0[1] + acc1[1], acc0[2] + acc1[2], acc0[3] + acc1[3]);
-    __syncthreads();
-    if (threadIdx.x < 256) {
-      const int m = threadIdx.x >> 4, row = threadIdx.x & 15;
-      const int idx = (((row >> 2) * 16) + m) * 4 + (row & 3);   // D[row][m] lives in lane (row/4)*16+m, reg row%4
-      float v = 0.f;
+        make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
+    if (!M8)
+      *reinterpret_cast<float4 *>(&part[buf][wave][256 + lane * 4]) =
+          make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
+    lds_barrier();
+    const int m = threadIdx.x >> 4, row = threadIdx.x & 15;
+    if (m < (M8 ? 8 : 16)) {
+      // D[row][c] lives in lane (row/4)*16 + c, register row%4.  M8: lo products sit in
+      // column m + 8 of the same tile; otherwise in the second tile.
+      const int idx = (((row >> 2) * 16) + m) * 4 + (row & 3);
+      const int idx_lo = M8 ? idx + 32 : idx + 256;
+      float v_hi = 0.f, v_lo = 0.f;
 #pragma unroll
-      for (int w = 0; w < GEMV_WAVES; ++w) v += part[buf][w][idx];
+      for (int w = 0; w < GEMV_WAVES; ++w) v_hi += part[buf][w][idx];
+#pragma unroll
+      for (int w = 0; w < GEMV_WAVES; ++w) v_lo += part[buf][w][idx_lo];
       const int c = s * 16 + row;
-      if (m < M && c < n_cols) out[chunk * chunk_stride + (size_t)m * out_stride + c] = v;
+      if (m < M && c < n_cols) out[chunk * chunk_stride + (size_t)m * out_stride + c] = v_hi + v_lo;
     }
     buf ^= 1;
   }
+}
+
+template <int KPW, int D, bool EXACT>
+static void gemv_launch(bool m8, dim3 grid, hipStream_t st, const u32x4_t *wp, const float *X, int M,
+                        int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols, float *out,
+                        int out_stride, size_t chunk_stride) {
+#define DART_GEMV_GO(M8_, NT_)                                                                    \
+  hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, M8_, NT_, EXACT>), grid, dim3(GEMV_THREADS), 0, st, \
+                     wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,         \
+                     chunk_stride)
+  if (m8 && g_gemv_nt) DART_GEMV_GO(true, true);
+  else if (m8) DART_GEMV_GO(true, false);
+  else if (g_gemv_nt) DART_GEMV_GO(false, true);
+  else DART_GEMV_GO(false, false);
+#undef DART_GEMV_GO
 }
 
 // Strips [strip0, strip0+nstrips) of the packed matrix; out[chunk][m][j], j < nstrips*16
@@ -129,22 +199,42 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   const int KT = W.Kd / 32;
   const int nchunks = gemv_bf16_chunks(W.Kd);
   const int kpw = (KT + GEMV_WAVES * nchunks - 1) / (GEMV_WAVES * nchunks);
+  const bool exact = kpw * GEMV_WAVES * nchunks == KT;
   if (chunks) *chunks = nchunks;
   const int n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
-  int wgs = 512 / nchunks;                             // two workgroups per CU on 256 CUs
+  int wgs = g_gemv_wgs / nchunks;
   if (wgs > nstrips) wgs = nstrips;
   if (wgs < 1) wgs = 1;
-  dim3 grid(wgs * nchunks), block(GEMV_THREADS);
-  const uint4 *wp = (const uint4 *)W.data;
-#define DART_GEMV_LAUNCH(KPW, D)                                                                \
-  hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D>), grid, block, 0, st, wp, X, M, KT, kpw, nchunks,  \
-                     strip0, nstrips, n_cols, out, out_stride, chunk_stride)
-  if (kpw <= 4) DART_GEMV_LAUNCH(4, 4);
-  else if (kpw <= 8) DART_GEMV_LAUNCH(8, 8);
-  else if (kpw <= 12) DART_GEMV_LAUNCH(12, 6);
-  else if (kpw <= 16) DART_GEMV_LAUNCH(16, 8);
-  else DART_GEMV_LAUNCH(20, 10);
-#undef DART_GEMV_LAUNCH
+  dim3 grid(wgs * nchunks);
+  const u32x4_t *wp = (const u32x4_t *)W.data;
+  const bool m8 = M <= 8;
+  const int depth = g_gemv_depth;
+#define DART_GEMV_ARGS m8, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
+  if (exact && kpw == 20) {
+    if (depth == 10 || (depth == 0 && !m8)) gemv_launch<20, 10, true>(DART_GEMV_ARGS);
+    else if (depth == 5) gemv_launch<20, 5, true>(DART_GEMV_ARGS);
+    else gemv_launch<20, 20, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 17) {
+    gemv_launch<17, 17, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 16) {
+    if (depth == 8) gemv_launch<16, 8, true>(DART_GEMV_ARGS);
+    else gemv_launch<16, 16, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 12) {
+    gemv_launch<12, 12, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 8) {
+    gemv_launch<8, 8, true>(DART_GEMV_ARGS);
+  } else if (kpw <= 4) {
+    gemv_launch<4, 4, false>(DART_GEMV_ARGS);
+  } else if (kpw <= 8) {
+    gemv_launch<8, 8, false>(DART_GEMV_ARGS);
+  } else if (kpw <= 12) {
+    gemv_launch<12, 6, false>(DART_GEMV_ARGS);
+  } else if (kpw <= 16) {
+    gemv_launch<16, 8, false>(DART_GEMV_ARGS);
+  } else {
+    gemv_launch<20, 10, false>(DART_GEMV_ARGS);
+  }
+#undef DART_GEMV_ARGS
   return hipGetLastError();
 }
 

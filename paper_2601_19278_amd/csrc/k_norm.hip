@@ -5,53 +5,118 @@
 
 namespace dart {
 
+constexpr int ROW_THREADS = 512;
+constexpr int ROW_MAXIT = 4;            // 8 * ROW_THREADS * ROW_MAXIT = 16384 features at most
+
+// Eight consecutive elements of a row as floats (one 16- or 32-byte access).
+__device__ __forceinline__ void load8(const float *p, float *v) {
+  const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, float *v) {
+  const uint4 a = *reinterpret_cast<const uint4 *>(p);
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
+__device__ __forceinline__ void store8(float *p, const float *v) {
+  *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
 // Row i of the layer input is position pos0+i of [z_1..z_n, MASK x (K-1)] (Sec. 3.2):
 // a prefix row of `hidden` when pos < n, else mask embedding pos-n.  Writes the RMS-normed
 // row (times gain) to xn[i] and, for rows >= resid_row0, the raw row to resid.
+// One workgroup per row; the row stays in registers between the two passes, and all loads
+// of a pass are issued before the first use (the kernel is pure latency otherwise).
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_gather_kernel(
+__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
     const T *__restrict__ hidden, const T *__restrict__ mask_emb, const T *__restrict__ gain, int n,
     int pos0, int d, float eps, float *__restrict__ xn, float *__restrict__ resid, int resid_row0) {
   __shared__ float red[16];
   const int i = blockIdx.x;
   const int pos = pos0 + i;
   const T *src = pos < n ? hidden + (size_t)pos * d : mask_emb + (size_t)(pos - n) * d;
-  float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = to_f32(src[c]);
-    ss += v * v;
+  float v[ROW_MAXIT][8], g[ROW_MAXIT][8];
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) {
+      load8(src + c, v[j]);
+      load8(gain + c, g[j]);
+    }
   }
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j)
+    if ((j * ROW_THREADS + threadIdx.x) * 8 < d)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += v[j][e] * v[j][e];
   ss = block_sum(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = to_f32(src[c]);
-    xn[(size_t)i * d + c] = v * rstd * to_f32(gain[c]);
-    if (i >= resid_row0) resid[(size_t)(i - resid_row0) * d + c] = v;
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) {
+      if (i >= resid_row0) store8(resid + (size_t)(i - resid_row0) * d + c, v[j]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
+      store8(xn + (size_t)i * d + c, v[j]);
+    }
   }
 }
 
 // y = resid + sum_c part[c];  yn = RMSNorm(y) * gain.  part[c] row r starts at
-// part + c*chunk_stride + r*row_stride.
+// part + c*chunk_stride + r*row_stride.  Chunk partials are added in index order.
 template <typename T>
-__global__ __launch_bounds__(256) void resid_norm_kernel(const float *__restrict__ resid,
-                                                         const float *__restrict__ part, int chunks,
-                                                         size_t chunk_stride, int row_stride,
-                                                         const T *__restrict__ gain, int d, float eps,
-                                                         float *__restrict__ y,
-                                                         float *__restrict__ yn) {
+__global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
+    const float *__restrict__ resid, const float *__restrict__ part, int chunks, size_t chunk_stride,
+    int row_stride, const T *__restrict__ gain, int d, float eps, float *__restrict__ y,
+    float *__restrict__ yn) {
   __shared__ float red[16];
   const int r = blockIdx.x;
-  float ss = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = resid[(size_t)r * d + c];
-    for (int k = 0; k < chunks; ++k) v += part[k * chunk_stride + (size_t)r * row_stride + c];
-    y[(size_t)r * d + c] = v;
-    ss += v * v;
+  float v[ROW_MAXIT][8], g[ROW_MAXIT][8];
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) {
+      load8(resid + (size_t)r * d + c, v[j]);
+      load8(gain + c, g[j]);
+    }
   }
+  for (int k = 0; k < chunks; ++k) {
+#pragma unroll
+    for (int j = 0; j < ROW_MAXIT; ++j) {
+      const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+      if (c < d) {
+        float p[8];
+        load8(part + k * chunk_stride + (size_t)r * row_stride + c, p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[j][e] += p[e];
+      }
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j)
+    if ((j * ROW_THREADS + threadIdx.x) * 8 < d)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += v[j][e] * v[j][e];
   ss = block_sum(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x)
-    yn[(size_t)r * d + c] = y[(size_t)r * d + c] * rstd * to_f32(gain[c]);
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) {
+      store8(y + (size_t)r * d + c, v[j]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
+      store8(yn + (size_t)r * d + c, v[j]);
+    }
+  }
 }
 
 // h[r][f] = silu(gate) * up from the fused gate/up projection (summed over k-chunks).
@@ -85,11 +150,11 @@ hipError_t launch_rmsnorm_gather(int dtype, const void *hidden, const void *mask
                                  const void *gain, int n, int pos0, int M, int d, float eps,
                                  float *xn, float *resid, int resid_row0, hipStream_t st) {
   if (dtype == DART_BF16)
-    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(M), dim3(256), 0, st,
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st,
                        (const bf16_t *)hidden, (const bf16_t *)mask_emb, (const bf16_t *)gain, n,
                        pos0, d, eps, xn, resid, resid_row0);
   else
-    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(256), 0, st,
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st,
                        (const float *)hidden, (const float *)mask_emb, (const float *)gain, n, pos0,
                        d, eps, xn, resid, resid_row0);
   return hipGetLastError();
@@ -99,10 +164,10 @@ hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, i
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
                              float eps, float *y, float *yn, hipStream_t st) {
   if (dtype == DART_BF16)
-    hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(rows), dim3(256), 0, st, resid, part, chunks,
+    hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(rows), dim3(ROW_THREADS), 0, st, resid, part, chunks,
                        chunk_stride, row_stride, (const bf16_t *)gain, d, eps, y, yn);
   else
-    hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(rows), dim3(256), 0, st, resid, part, chunks,
+    hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(rows), dim3(ROW_THREADS), 0, st, resid, part, chunks,
                        chunk_stride, row_stride, (const float *)gain, d, eps, y, yn);
   return hipGetLastError();
 }

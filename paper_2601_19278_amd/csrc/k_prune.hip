@@ -33,6 +33,9 @@ struct PruneShared {
   int32_t beam_prev[2][DART_MAX_BEAM];
   int32_t beam_cre[2][DART_MAX_BEAM];          // creation index of the entry at its own level
   int32_t beam_row[DART_MAX_BEAM];             // table row of the entry's context, -1 = unseen
+  // successor rows of the beam entries' contexts, staged once per level (row stride S + 1)
+  int32_t row_id[DART_MAX_BEAM * 65];
+  float row_lp[DART_MAX_BEAM * 65];
   // running best list (double buffered), sorted by key descending
   uint64_t best_key[2][DART_MAX_BUDGET];
   int32_t best_tok[2][DART_MAX_BUDGET];
@@ -47,8 +50,9 @@ struct PruneShared {
 __device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed) {
   uint64_t h = mix64(packed) & tab.slot_mask;
   for (uint64_t probes = 0; probes <= tab.slot_mask; ++probes) {
-    const uint64_t kk = tab.slot_keys[h];
-    if (kk == packed) return tab.slot_rows[h];
+    const uint4 raw = *reinterpret_cast<const uint4 *>(tab.slots + h);   // one 16-byte access
+    const uint64_t kk = ((uint64_t)raw.y << 32) | raw.x;
+    if (kk == packed) return (int32_t)raw.z;
     if (kk == ~(uint64_t)0) return -1;
     h = (h + 1) & tab.slot_mask;
   }
@@ -105,6 +109,17 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
       sh.beam_row[t] = ngram_find(tab, packed);
     }
     __syncthreads();
+    // stage the successor rows in LDS with coalesced, independent loads
+    const int S = tab.S, SP = S + 1;
+    for (int idx = t; idx < nb * S; idx += PRUNE_THREADS) {
+      const int b = idx / S, j = idx - b * S;
+      const int row = sh.beam_row[b];
+      if (row >= 0) {
+        sh.row_id[b * SP + j] = tab.succ_ids[(size_t)row * S + j];
+        sh.row_lp[b * SP + j] = tab.succ_logp[(size_t)row * S + j];
+      }
+    }
+    __syncthreads();
     const float wl = lw.w_logit[L], wv = lw.w_level[L];
     for (int e = t; e < P; e += PRUNE_THREADS) {
       uint64_t key = 0;
@@ -114,12 +129,8 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         float s_ng = tab.logp_miss;
         const int row = sh.beam_row[b];
         if (row >= 0) {
-          const int32_t *rid = tab.succ_ids + (size_t)row * tab.S;
-          for (int j = 0; j < tab.S; ++j)
-            if (rid[j] == tok) {
-              s_ng = tab.succ_logp[(size_t)row * tab.S + j];
-              break;
-            }
+          for (int j = 0; j < S; ++j)
+            if (sh.row_id[b * SP + j] == tok) s_ng = sh.row_lp[b * SP + j];   // ids are distinct
         }
         const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
         const float g = __fmul_rn(w_ng, s_ng);
