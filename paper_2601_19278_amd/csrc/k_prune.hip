@@ -11,9 +11,10 @@
 //     [ order-preserving score bits : 32 | 15 - level : 4 | 0x0FFFFFFF - creation : 28 ]
 // (creation = b*k + c).  Larger key = better under both cuts of the algorithm: within one
 // level it orders by (score desc, creation asc) -- the beam cut -- and across levels by
-// (score desc, level asc, creation asc) -- the global theta cut.  A bitonic sort of the
-// level's keys gives the next beam (first w) and the level's contenders for the global
-// tree (first theta), which are merged into the running best-theta list.  Since the best
+// (score desc, level asc, creation asc) -- the global theta cut.  Ranking the level's keys
+// (by counting for up to 512 expansions, by a bitonic sort beyond) gives the next beam
+// (first w) and the level's contenders for the global tree (first theta), which are merged
+// into the running best-theta list.  Since the best
 // theta of a union is the best theta of (best theta of one part) + (the other part), the
 // running list equals Alg. 1's "top-theta of T" after the last level.
 #include "common.h"
@@ -22,6 +23,7 @@
 namespace dart {
 
 constexpr int PRUNE_THREADS = 256;
+constexpr int PRUNE_FAST = 2;          // expansions per thread on the register-resident path
 
 struct PruneShared {
   uint64_t keys[DART_MAX_LEVEL_NODES];        // this level's expansions
@@ -36,6 +38,10 @@ struct PruneShared {
   // successor rows of the beam entries' contexts, staged once per level (row stride S + 1)
   int32_t row_id[DART_MAX_BEAM * 65];
   float row_lp[DART_MAX_BEAM * 65];
+  // the level's best min(theta, n_new) expansions, sorted by key descending
+  uint64_t lvl_key[DART_MAX_BUDGET];
+  int32_t lvl_tok[DART_MAX_BUDGET];
+  int32_t lvl_par[DART_MAX_BUDGET];
   // running best list (double buffered), sorted by key descending
   uint64_t best_key[2][DART_MAX_BUDGET];
   int32_t best_tok[2][DART_MAX_BUDGET];
@@ -45,23 +51,49 @@ struct PruneShared {
   int32_t out_par[DART_MAX_BUDGET];
 };
 
-// Row of a packed context, or -1.  Linear probing; the table is at most half full, and the
-// probe count is bounded by the table size so the loop always ends.
-__device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed) {
-  uint64_t h = mix64(packed) & tab.slot_mask;
+__device__ __forceinline__ uint64_t pack_context(int ctx_len, int prev, int tok) {
+  return ctx_len >= 2 ? ((uint64_t)(uint32_t)prev << 32) | (uint32_t)tok : (uint64_t)(uint32_t)tok;
+}
+
+__device__ __forceinline__ uint4 slot_load(const NgramTableDev &tab, uint64_t h) {
+  return *reinterpret_cast<const uint4 *>(tab.slots + h);          // one 16-byte access
+}
+
+// Finish a lookup whose first slot `raw` (at index h) has already been fetched: row of the
+// packed context, or -1.  Linear probing; the table is at most half full and the probe
+// count is bounded by the table size, so the loop always ends.
+__device__ int32_t ngram_resolve(const NgramTableDev &tab, uint64_t packed, uint64_t h, uint4 raw) {
   for (uint64_t probes = 0; probes <= tab.slot_mask; ++probes) {
-    const uint4 raw = *reinterpret_cast<const uint4 *>(tab.slots + h);   // one 16-byte access
     const uint64_t kk = ((uint64_t)raw.y << 32) | raw.x;
     if (kk == packed) return (int32_t)raw.z;
     if (kk == ~(uint64_t)0) return -1;
     h = (h + 1) & tab.slot_mask;
+    raw = slot_load(tab, h);
   }
   return -1;
+}
+
+__device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed) {
+  const uint64_t h = mix64(packed) & tab.slot_mask;
+  return ngram_resolve(tab, packed, h, slot_load(tab, h));
 }
 
 __device__ __forceinline__ int key_level(uint64_t key) { return 15 - (int)((key >> 28) & 0xF); }
 __device__ __forceinline__ int key_creation(uint64_t key) {
   return 0x0FFFFFFF - (int)(key & 0x0FFFFFFF);
+}
+
+// Successor rows of the nb current beam entries -> LDS, coalesced and independent loads.
+__device__ __forceinline__ void stage_rows(PruneShared &sh, const NgramTableDev &tab, int nb, int t) {
+  const int S = tab.S, SP = S + 1;
+  for (int idx = t; idx < nb * S; idx += PRUNE_THREADS) {
+    const int b = idx / S, j = idx - b * S;
+    const int row = sh.beam_row[b];
+    if (row >= 0) {
+      sh.row_id[b * SP + j] = tab.succ_ids[(size_t)row * S + j];
+      sh.row_lp[b * SP + j] = tab.succ_logp[(size_t)row * S + j];
+    }
+  }
 }
 
 __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
@@ -75,6 +107,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   const int seq = blockIdx.x, t = threadIdx.x;
   const int theta = budget - 1;
   const int ctx_len = tab.n_gram - 1;
+  const int S = tab.S, SP = S + 1;
   ids += (size_t)seq * K * k;
   scores += (size_t)seq * K * k;
   ctx_tail += (size_t)seq * ctx_len;
@@ -88,90 +121,152 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   }
   const int root = ctx_tail[ctx_len - 1];
   if (t == 0) {
+    const int prev = ctx_len >= 2 ? ctx_tail[ctx_len - 2] : 0;
     sh.beam_score[0][0] = 0.f;
     sh.beam_tok[0][0] = root;
-    sh.beam_prev[0][0] = ctx_len >= 2 ? ctx_tail[ctx_len - 2] : 0;
+    sh.beam_prev[0][0] = prev;
     sh.beam_cre[0][0] = -1;                    // the root
+    sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev, root));
   }
   int nb = 1, n_best = 0, cur = 0, bcur = 0;
+  __syncthreads();
+  stage_rows(sh, tab, 1, t);
   __syncthreads();
 
   for (int L = 0; L < K; ++L) {
     const int n_new = nb * k;
-    int P = 2;
-    while (P < n_new) P <<= 1;
-    // one table lookup per beam entry: context = last N-1 tokens of (ctx_tail ++ path)
-    if (t < nb) {
-      const uint64_t packed = ctx_len >= 2
-                                  ? ((uint64_t)(uint32_t)sh.beam_prev[cur][t] << 32) |
-                                        (uint32_t)sh.beam_tok[cur][t]
-                                  : (uint64_t)(uint32_t)sh.beam_tok[cur][t];
-      sh.beam_row[t] = ngram_find(tab, packed);
-    }
-    __syncthreads();
-    // stage the successor rows in LDS with coalesced, independent loads
-    const int S = tab.S, SP = S + 1;
-    for (int idx = t; idx < nb * S; idx += PRUNE_THREADS) {
-      const int b = idx / S, j = idx - b * S;
-      const int row = sh.beam_row[b];
-      if (row >= 0) {
-        sh.row_id[b * SP + j] = tab.succ_ids[(size_t)row * S + j];
-        sh.row_lp[b * SP + j] = tab.succ_logp[(size_t)row * S + j];
-      }
-    }
-    __syncthreads();
+    const int nb_next = min(beam_w, n_new);
+    const int n_lvl = min(theta, n_new);
+    const int nxt = cur ^ 1;
+    const bool last = L + 1 == K;
     const float wl = lw.w_logit[L], wv = lw.w_level[L];
-    for (int e = t; e < P; e += PRUNE_THREADS) {
-      uint64_t key = 0;
-      if (e < n_new) {
-        const int b = e / k, c = e - b * k;
-        const int tok = sh.cand_id[L * k + c];
-        float s_ng = tab.logp_miss;
-        const int row = sh.beam_row[b];
-        if (row >= 0) {
-          for (int j = 0; j < S; ++j)
-            if (sh.row_id[b * SP + j] == tok) s_ng = sh.row_lp[b * SP + j];   // ids are distinct
-        }
-        const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
-        const float g = __fmul_rn(w_ng, s_ng);
-        const float inc = __fmul_rn(__fadd_rn(a, g), wv);
-        const float sc = __fadd_rn(sh.beam_score[cur][b], inc);
-        key = ((uint64_t)f32_sortable(sc) << 32) | ((uint64_t)(15 - L) << 28) |
-              (uint64_t)(0x0FFFFFFF - e);
+
+    // score of expansion e = b*k + c of this level as its ordering key
+    auto expansion_key = [&](int e, int &tok_out, int &b_out) -> uint64_t {
+      const int b = e / k, c = e - b * k;
+      const int tok = sh.cand_id[L * k + c];
+      float s_ng = tab.logp_miss;
+      if (sh.beam_row[b] >= 0) {
+        for (int j = 0; j < S; ++j)
+          if (sh.row_id[b * SP + j] == tok) s_ng = sh.row_lp[b * SP + j];   // ids are distinct
       }
-      sh.keys[e] = key;
-    }
-    __syncthreads();
-    // bitonic sort, descending
-    for (int size = 2; size <= P; size <<= 1) {
-      for (int stride = size >> 1; stride > 0; stride >>= 1) {
-        for (int e = t; e < (P >> 1); e += PRUNE_THREADS) {
-          const int lo = ((e / stride) * stride * 2) + (e % stride);
-          const int hi = lo + stride;
-          const bool desc = ((lo & size) == 0);
-          const uint64_t a = sh.keys[lo], b = sh.keys[hi];
-          if (desc ? (a < b) : (a > b)) {
-            sh.keys[lo] = b;
-            sh.keys[hi] = a;
+      const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
+      const float g = __fmul_rn(w_ng, s_ng);
+      const float inc = __fmul_rn(__fadd_rn(a, g), wv);
+      const float sc = __fadd_rn(sh.beam_score[cur][b], inc);
+      tok_out = tok;
+      b_out = b;
+      return ((uint64_t)f32_sortable(sc) << 32) | ((uint64_t)(15 - L) << 28) |
+             (uint64_t)(0x0FFFFFFF - e);
+    };
+
+    if (n_new <= PRUNE_FAST * PRUNE_THREADS) {
+      // Register-resident path: a thread owns up to two expansions, ranks them by counting
+      // the keys that beat them (keys are unique), and -- because it knows the context its
+      // expansion would present at the next level -- fetches that context's hash slot
+      // already now, so the table probe overlaps with the ranking instead of following it.
+      uint64_t key[PRUNE_FAST], packed[PRUNE_FAST], hslot[PRUNE_FAST];
+      uint4 raw[PRUNE_FAST];
+      int tok[PRUNE_FAST], bb[PRUNE_FAST], rank[PRUNE_FAST];
+#pragma unroll
+      for (int q = 0; q < PRUNE_FAST; ++q) {
+        const int e = t + q * PRUNE_THREADS;
+        key[q] = 0;
+        if (e < n_new) {
+          key[q] = expansion_key(e, tok[q], bb[q]);
+          sh.keys[e] = key[q];
+          if (!last) {
+            packed[q] = pack_context(ctx_len, sh.beam_tok[cur][bb[q]], tok[q]);
+            hslot[q] = mix64(packed[q]) & tab.slot_mask;
+            raw[q] = slot_load(tab, hslot[q]);
           }
         }
-        __syncthreads();
+        rank[q] = 0;
       }
+      __syncthreads();
+      for (int j = 0; j < n_new; ++j) {
+        const uint64_t kj = sh.keys[j];
+#pragma unroll
+        for (int q = 0; q < PRUNE_FAST; ++q) rank[q] += kj > key[q];
+      }
+#pragma unroll
+      for (int q = 0; q < PRUNE_FAST; ++q) {
+        const int e = t + q * PRUNE_THREADS;
+        if (e < n_new) {
+          const int r = rank[q];
+          if (r < nb_next) {
+            sh.beam_score[nxt][r] = f32_unsortable((uint32_t)(key[q] >> 32));
+            sh.beam_tok[nxt][r] = tok[q];
+            sh.beam_prev[nxt][r] = sh.beam_tok[cur][bb[q]];
+            sh.beam_cre[nxt][r] = e;
+          }
+          if (r < n_lvl) {
+            sh.lvl_key[r] = key[q];
+            sh.lvl_tok[r] = tok[q];
+            sh.lvl_par[r] = sh.beam_cre[cur][bb[q]];
+          }
+        }
+      }
+      // beam_row of this level was last read before the barrier above: safe to overwrite
+#pragma unroll
+      for (int q = 0; q < PRUNE_FAST; ++q) {
+        const int e = t + q * PRUNE_THREADS;
+        if (!last && e < n_new && rank[q] < nb_next)
+          sh.beam_row[rank[q]] = ngram_resolve(tab, packed[q], hslot[q], raw[q]);
+      }
+    } else {
+      // General path (up to 4096 expansions): bitonic sort of the keys in LDS.
+      int P = 2, logP = 1;
+      while (P < n_new) {
+        P <<= 1;
+        ++logP;
+      }
+      for (int e = t; e < P; e += PRUNE_THREADS) {
+        int tok, b;
+        sh.keys[e] = e < n_new ? expansion_key(e, tok, b) : 0;
+      }
+      __syncthreads();
+      for (int ls = 1; ls <= logP; ++ls) {               // size = 1 << ls
+        for (int lst = ls - 1; lst >= 0; --lst) {        // stride = 1 << lst
+          for (int e = t; e < (P >> 1); e += PRUNE_THREADS) {
+            const int lo = ((e >> lst) << (lst + 1)) | (e & ((1 << lst) - 1));
+            const int hi = lo + (1 << lst);
+            const bool desc = ((lo >> ls) & 1) == 0;
+            const uint64_t a = sh.keys[lo], b = sh.keys[hi];
+            if (desc ? (a < b) : (a > b)) {
+              sh.keys[lo] = b;
+              sh.keys[hi] = a;
+            }
+          }
+          __syncthreads();
+        }
+      }
+      int row = -1;
+      if (t < max(nb_next, n_lvl)) {
+        const uint64_t kk = sh.keys[t];
+        const int e = key_creation(kk);
+        const int b = e / k, c = e - b * k;
+        const int tk = sh.cand_id[L * k + c];
+        if (t < nb_next) {
+          sh.beam_score[nxt][t] = f32_unsortable((uint32_t)(kk >> 32));
+          sh.beam_tok[nxt][t] = tk;
+          sh.beam_prev[nxt][t] = sh.beam_tok[cur][b];
+          sh.beam_cre[nxt][t] = e;
+          if (!last) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk));
+        }
+        if (t < n_lvl) {
+          sh.lvl_key[t] = kk;
+          sh.lvl_tok[t] = tk;
+          sh.lvl_par[t] = sh.beam_cre[cur][b];
+        }
+      }
+      __syncthreads();
+      if (t < nb_next) sh.beam_row[t] = row;
     }
-    // next beam: the first min(w, n_new) expansions
-    const int nb_next = min(beam_w, n_new);
-    const int nxt = cur ^ 1;
-    if (t < nb_next) {
-      const uint64_t key = sh.keys[t];
-      const int e = key_creation(key);
-      const int b = e / k, c = e - b * k;
-      sh.beam_score[nxt][t] = f32_unsortable((uint32_t)(key >> 32));
-      sh.beam_tok[nxt][t] = sh.cand_id[L * k + c];
-      sh.beam_prev[nxt][t] = sh.beam_tok[cur][b];
-      sh.beam_cre[nxt][t] = e;
-    }
-    // merge the level's first min(theta, n_new) into the running best list (both sorted)
-    const int n_lvl = min(theta, n_new);
+    __syncthreads();
+
+    // merge the level's best into the running best list (both sorted, keys unique), and
+    // stage the next level's successor rows
     const int bnx = bcur ^ 1;
     if (t < n_best + n_lvl) {
       uint64_t key;
@@ -181,14 +276,12 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         tok = sh.best_tok[bcur][t];
         par = sh.best_par[bcur][t];
         rank = t;
-        for (int j = 0; j < n_lvl; ++j) rank += (sh.keys[j] > key);
+        for (int j = 0; j < n_lvl; ++j) rank += (sh.lvl_key[j] > key);
       } else {
         const int j0 = t - n_best;
-        key = sh.keys[j0];
-        const int e = key_creation(key);
-        const int b = e / k, c = e - b * k;
-        tok = sh.cand_id[L * k + c];
-        par = sh.beam_cre[cur][b];
+        key = sh.lvl_key[j0];
+        tok = sh.lvl_tok[j0];
+        par = sh.lvl_par[j0];
         rank = j0;
         for (int j = 0; j < n_best; ++j) rank += (sh.best_key[bcur][j] > key);
       }
@@ -198,6 +291,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         sh.best_par[bnx][rank] = par;
       }
     }
+    if (!last) stage_rows(sh, tab, nb_next, t);
     n_best = min(theta, n_best + n_lvl);
     bcur = bnx;
     cur = nxt;
