@@ -20,6 +20,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+# a plain 1 GiB copy (profiles/lm_head_C4_hbm_counters.txt); re-measure after kernel changes.
+MEASURED_LM_HEAD_TRAFFIC = {"C4": 1601.3e6}
 
 
 def algorithmic_bytes(cfg, n_new: int) -> dict:
@@ -54,6 +57,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--n-new", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM bytes) for counter scaling")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU hot path; run with --gpus 1 "
@@ -134,10 +139,18 @@ def main() -> int:
     achieved = ab["lm_head_kernel"] / (lm_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemv_bf16_kernel (LM head)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": None, "kernel_us": round(lm_us, 2),
+                "traffic": MEASURED_LM_HEAD_TRAFFIC.get(cfg.name), "kernel_us": round(lm_us, 2),
                 "algorithmic_bytes": ab["lm_head_kernel"]}
     stages["lm_head_us"] = lm_us
     stages["forward_GBps"] = ab["forward"] / (stages["forward_warm_us"] * 1e-6) / 1e9
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:
