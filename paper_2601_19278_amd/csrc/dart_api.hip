@@ -169,7 +169,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   c->max_chunks = 1;
   if (g.dtype == DART_BF16) {
     const int dims[3] = {d, c->q_dim, F};
-    for (int v : dims) c->max_chunks = std::max(c->max_chunks, gemv_bf16_chunks(v));
+    for (int v : dims) c->max_chunks = std::max(c->max_chunks, 4 * gemv_bf16_chunks(v));
   }
   c->max_splits = (c->t_cap + 127) / 128;
   const size_t wide = (size_t)std::max(std::max(d, 2 * F), c->qkv_dim);
@@ -199,12 +199,16 @@ dart_status from_hip(hipError_t e) {
 }
 
 // Projection of M rows of X (fp32 [M][W.Kd]) through output rows [row0, row0+nrows) of W.
+// may_split: the consumer adds k-chunk partials, so the k range may be cut further.
 hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows, const float *X,
-                   int M, float *out, int out_stride, size_t chunk_stride, int *chunks,
-                   hipStream_t st) {
-  if (c->cfg.dtype == DART_BF16)
-    return launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride,
+                   int M, float *out, int out_stride, size_t chunk_stride, bool may_split,
+                   int *chunks, hipStream_t st) {
+  if (c->cfg.dtype == DART_BF16) {
+    const int nstrips = (nrows + 15) / 16;
+    const int split = may_split ? gemv_bf16_split(W.Kd, nstrips) : 1;
+    return launch_gemv_bf16(W, row0 / 16, nstrips, X, M, out, out_stride, chunk_stride, split,
                             chunks, st);
+  }
   *chunks = 1;
   return launch_gemv_f32(W, row0, nrows, X, M, out, out_stride, st);
 }
@@ -219,10 +223,10 @@ hipError_t qkv_pass(dart_ctx *c, int seq, const void *hidden, int n, int pos0, i
   const size_t cs = (size_t)DART_SKINNY_ROWS * c->qkv_dim;
   int chunks = 1;
   if (Kq > 0) {
-    HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, &chunks, st));
+    HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, true, &chunks, st));
   } else {   // K and V rows only
     HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn, M, c->qkv + c->q_dim, c->qkv_dim,
-                    cs, &chunks, st));
+                    cs, true, &chunks, st));
   }
   return launch_qkv_post(c, seq, c->qkv, chunks, cs, M, Kq, pos0, st);
 }
@@ -244,17 +248,17 @@ hipError_t forward_one(dart_ctx *c, int seq, const void *hidden, int n, int n_ca
 
   int chunks = 1;
   size_t cs = (size_t)R * g.d;
-  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, K, c->proj, g.d, cs, &chunks, st));
+  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, K, c->proj, g.d, cs, true, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, K, g.d,
                             g.rms_eps, c->y, c->yn, st));
   cs = (size_t)R * 2 * g.ffn;
-  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, K, c->proj, 2 * g.ffn, cs, &chunks, st));
+  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, K, c->proj, 2 * g.ffn, cs, true, &chunks, st));
   HIP_TRY(launch_swiglu(c->proj, chunks, cs, K, g.ffn, g.dtype == DART_BF16, c->hmid, st));
   cs = (size_t)R * g.d;
-  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, K, c->proj, g.d, cs, &chunks, st));
+  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, K, c->proj, g.d, cs, true, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, K, g.d, g.rms_eps,
                             c->u, c->yn, st));
-  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, K, logits, g.vocab, 0, &chunks, st));
+  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, K, logits, g.vocab, 0, false, &chunks, st));
   return hipSuccess;
 }
 
@@ -486,7 +490,7 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
 dart_status dart_debug_lm_head(dart_ctx *c, int K, float *logits_out, void *stream) {
   if (!c || !logits_out || K < 1 || K > c->cfg.max_K) return DART_ERR_ARG;
   int chunks = 1;
-  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, &chunks,
+  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, false, &chunks,
                           (hipStream_t)stream));
 }
 

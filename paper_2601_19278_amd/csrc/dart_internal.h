@@ -104,9 +104,10 @@ hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const flo
 
 // bf16 skinny GEMM on packed weights; returns the number of k-chunks written through *chunks.
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
-                            float *out, int out_stride, size_t chunk_stride, int *chunks,
+                            float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                             hipStream_t st);
-int gemv_bf16_chunks(int Kd);
+int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
+int gemv_bf16_split(int Kd, int nstrips);     // extra k-split that balances the workgroups
 
 hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
                          int interleaved, float *h, hipStream_t st);

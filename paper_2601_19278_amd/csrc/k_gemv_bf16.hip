@@ -83,6 +83,20 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   const int nk = EXACT ? KPW : max(0, min(kpw, KT - ks0));   // wave-uniform
   const int Kd = KT * 32;
 
+  // Rolling buffer of D weight tiles: register t % D serves slot t of every strip; the load
+  // for its next slot is issued right after the MFMAs that free it, so about D KiB stay in
+  // flight per wavefront across strip boundaries.  After the last strip the refills re-read
+  // tiles of that same strip (in bounds, never used) so that the loop body has no branch.
+  // The first D loads go out before the activations are fetched and converted, so the weight
+  // stream is already running during that set-up.
+  u32x4_t aop[D];
+  int s = wg;                                          // strip index relative to strip0
+  if (s < nstrips) {
+    const u32x4_t *tile = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
+#pragma unroll
+    for (int r = 0; r < D; ++r)
+      if (r < nk) aop[r] = load_tile<NT>(tile + (size_t)r * 64);
+  }
   // B operands: activations of this wavefront's k slice, split into bf16 hi + bf16 lo
   // (x ~= hi + lo to ~2^-17) so that activations keep fp32-like accuracy while the weights
   // stay the exact bf16 values.
@@ -113,18 +127,6 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
     }
   }
 
-  // Rolling buffer of D weight tiles: register t % D serves slot t of every strip; the load
-  // for its next slot is issued right after the MFMAs that free it, so about D KiB stay in
-  // flight per wavefront across strip boundaries.  After the last strip the refills re-read
-  // tiles of that same strip (in bounds, never used) so that the loop body has no branch.
-  u32x4_t aop[D];
-  int s = wg;                                          // strip index relative to strip0
-  if (s < nstrips) {
-    const u32x4_t *tile = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
-#pragma unroll
-    for (int r = 0; r < D; ++r)
-      if (r < nk) aop[r] = load_tile<NT>(tile + (size_t)r * 64);
-  }
   int buf = 0;
   for (; s < nstrips; s += nwg) {
     const int sn = s + nwg;
@@ -191,13 +193,43 @@ static void gemv_launch(bool m8, dim3 grid, hipStream_t st, const u32x4_t *wp, c
 #undef DART_GEMV_GO
 }
 
+// Extra k-split for matrices with few strips.  With one workgroup per CU, 320 strips of a
+// 5120-row matrix leave a quarter of the CUs with twice the work of the rest, and a short
+// kernel also pays for each wavefront's activation set-up.  Cutting k into `split` times more
+// chunks gives (strip, chunk) units that divide evenly over the CUs and shortens the set-up;
+// the consumer adds the extra partials.  Measured on MI355X at d = 5120: 7168 rows 25 -> 13 us,
+// 5120 rows 23 -> 11 us, 34816 rows 67 -> 56 us with split 4; matrices with more than ~12
+// strips per workgroup (the LM head) gain nothing.  Only splits that keep every wavefront's
+// k-slice an exact, supported length of at least 4 k-steps are used.
+int g_gemv_split = 0;      // benchmark override (0 = automatic)
+
+static bool exact_kpw_supported(int kpw) {
+  return kpw == 2 || kpw == 4 || kpw == 5 || kpw == 8 || kpw == 10 || kpw == 12 || kpw == 16 ||
+         kpw == 17 || kpw == 20;
+}
+
+int gemv_bf16_split(int Kd, int nstrips) {
+  const int KT = Kd / 32, base = gemv_bf16_chunks(Kd);
+  auto valid = [&](int split) {
+    const int nch = base * split;
+    return KT % (GEMV_WAVES * nch) == 0 && exact_kpw_supported(KT / (GEMV_WAVES * nch));
+  };
+  if (g_gemv_split > 0) return valid(g_gemv_split) ? g_gemv_split : 1;
+  const int wgs_base = max(1, min(g_gemv_wgs / base, nstrips));
+  if (nstrips / wgs_base >= 12) return 1;
+  for (int split = 4; split > 1; split /= 2)
+    if (valid(split) && KT / (GEMV_WAVES * base * split) >= 4) return split;
+  return 1;
+}
+
 // Strips [strip0, strip0+nstrips) of the packed matrix; out[chunk][m][j], j < nstrips*16
-// (columns beyond W.n_real - strip0*16 are not written).
+// (columns beyond W.n_real - strip0*16 are not written).  split: extra k-split (1 when the
+// output must be complete in a single chunk).
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
-                            float *out, int out_stride, size_t chunk_stride, int *chunks,
+                            float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                             hipStream_t st) {
   const int KT = W.Kd / 32;
-  const int nchunks = gemv_bf16_chunks(W.Kd);
+  const int nchunks = gemv_bf16_chunks(W.Kd) * split;
   const int kpw = (KT + GEMV_WAVES * nchunks - 1) / (GEMV_WAVES * nchunks);
   const bool exact = kpw * GEMV_WAVES * nchunks == KT;
   if (chunks) *chunks = nchunks;
@@ -221,8 +253,16 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
     else gemv_launch<16, 16, true>(DART_GEMV_ARGS);
   } else if (exact && kpw == 12) {
     gemv_launch<12, 12, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 10) {
+    gemv_launch<10, 10, true>(DART_GEMV_ARGS);
   } else if (exact && kpw == 8) {
     gemv_launch<8, 8, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 5) {
+    gemv_launch<5, 5, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 4) {
+    gemv_launch<4, 4, true>(DART_GEMV_ARGS);
+  } else if (exact && kpw == 2) {
+    gemv_launch<2, 2, true>(DART_GEMV_ARGS);
   } else if (kpw <= 4) {
     gemv_launch<4, 4, false>(DART_GEMV_ARGS);
   } else if (kpw <= 8) {
