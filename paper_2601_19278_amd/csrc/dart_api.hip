@@ -306,6 +306,7 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
     return DART_ERR_ARG;
   }
   if (g.d > 16384) return DART_ERR_ARG;
+  if (g.max_ctx + g.max_K > 32768) return DART_ERR_ARG;   // at most 256 key splits of 128
   if (!w->w_in_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_post_norm || !w->w_gate ||
       !w->w_up || !w->w_down || !w->w_final_norm || !w->w_lm)
     return DART_ERR_ARG;

@@ -52,27 +52,45 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
 }
 
 // out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s.  Splits with l == 0 saw no key.
+// One workgroup per query vector, one thread per output dim; the split weights are computed
+// once in parallel and kept in LDS, and the partial rows are then read with independent loads.
+constexpr int ATTN_MAX_SPLITS = 256;
+
 __global__ __launch_bounds__(128) void attn_merge_kernel(const float *__restrict__ o_part,
                                                          const float *__restrict__ ml_part,
                                                          int nsplit, int hd,
                                                          float *__restrict__ out) {
+  __shared__ float red[16];
+  __shared__ float w[ATTN_MAX_SPLITS];
   const int qv = blockIdx.x, t = threadIdx.x;
-  if (t >= hd) return;
-  float M = -3.0e38f;
-  for (int s = 0; s < nsplit; ++s) {
-    const float l = ml_part[((size_t)qv * nsplit + s) * 2 + 1];
-    if (l > 0.f) M = fmaxf(M, ml_part[((size_t)qv * nsplit + s) * 2]);
+  float mx = -3.0e38f;
+  for (int s = t; s < nsplit; s += blockDim.x) {
+    const size_t slot = (size_t)qv * nsplit + s;
+    if (ml_part[slot * 2 + 1] > 0.f) mx = fmaxf(mx, ml_part[slot * 2]);
   }
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
+  mx = block_max(mx, red);
+  float den = 0.f;
+  for (int s = t; s < nsplit; s += blockDim.x) {
     const size_t slot = (size_t)qv * nsplit + s;
     const float l = ml_part[slot * 2 + 1];
-    if (l > 0.f) {
-      const float w = expf(ml_part[slot * 2] - M);
-      num += w * o_part[slot * hd + t];
-      den += w * l;
-    }
+    const float ws = l > 0.f ? expf(ml_part[slot * 2] - mx) : 0.f;
+    w[s] = ws;
+    den += ws * l;
   }
+  den = block_sum(den, red);          // its barriers also publish w[]
+  if (t >= hd) return;
+  const float *src = o_part + (size_t)qv * nsplit * hd + t;
+  float num = 0.f;
+  int s = 0;
+  for (; s + 4 <= nsplit; s += 4) {
+    const float a0 = src[(size_t)s * hd], a1 = src[(size_t)(s + 1) * hd];
+    const float a2 = src[(size_t)(s + 2) * hd], a3 = src[(size_t)(s + 3) * hd];
+    num += w[s] * a0;                 // fixed order: deterministic
+    num += w[s + 1] * a1;
+    num += w[s + 2] * a2;
+    num += w[s + 3] * a3;
+  }
+  for (; s < nsplit; ++s) num += w[s] * src[(size_t)s * hd];
   out[(size_t)qv * hd + t] = num / den;
 }
 
@@ -106,7 +124,7 @@ hipError_t launch_attention(const dart_ctx *c, int seq, int n, int Kq, hipStream
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(Kq * Hq), dim3(128), 0, st, c->att_part, c->att_ml,
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(Kq * Hq), dim3(hd), 0, st, c->att_part, c->att_ml,
                      nsplit, hd, c->att_out);
   return hipGetLastError();
 }

@@ -85,21 +85,33 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(
   const f16_t *kb = kbuf + (size_t)g * t_cap * HD;
   const f16_t *vt = vtbuf + (size_t)g * HD * t_cap;
 
-  for (int jb = j_begin; jb < j_end; jb += 32) {
-    // A operands: two 16-key tiles of K, and this wavefront's V^T dim tiles
+  // A operands of one 32-key block: two 16-key tiles of K, and this wavefront's V^T dim tiles
+  struct Block {
     F16x8 kop[2][KS], vop[DTW];
+  };
+  auto load_block = [&](int jb, Block &blk) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        kop[tt][ks].u = *reinterpret_cast<const uint4 *>(
+        blk.kop[tt][ks].u = *reinterpret_cast<const uint4 *>(
             kb + (size_t)(jb + 16 * tt + col) * HD + 32 * ks + 8 * gq);
 #pragma unroll
     for (int t = 0; t < DTW; ++t) {
       const f16_t *row = vt + (size_t)(16 * (DTW * wave + t) + col) * t_cap + jb + 4 * gq;
-      vop[t].h[0] = *reinterpret_cast<const uint2 *>(row);
-      vop[t].h[1] = *reinterpret_cast<const uint2 *>(row + 16);
+      blk.vop[t].h[0] = *reinterpret_cast<const uint2 *>(row);
+      blk.vop[t].h[1] = *reinterpret_cast<const uint2 *>(row + 16);
     }
+  };
+
+  Block nxt;
+  if (j_begin < j_end) load_block(j_begin, nxt);
+  for (int jb = j_begin; jb < j_end; jb += 32) {
+    // software pipeline: the next block's K/V are in flight while this block is computed
+    const Block cur = nxt;
+    if (jb + 32 < j_end) load_block(jb + 32, nxt);
+    const F16x8 (&kop)[2][KS] = cur.kop;
+    const F16x8 (&vop)[DTW] = cur.vop;
 
 #pragma unroll
     for (int a = 0; a < MT; ++a) {

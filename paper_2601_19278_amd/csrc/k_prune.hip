@@ -35,9 +35,9 @@ struct PruneShared {
   int32_t beam_prev[2][DART_MAX_BEAM];
   int32_t beam_cre[2][DART_MAX_BEAM];          // creation index of the entry at its own level
   int32_t beam_row[DART_MAX_BEAM];             // table row of the entry's context, -1 = unseen
-  // successor rows of the beam entries' contexts, staged once per level (row stride S + 1)
-  int32_t row_id[DART_MAX_BEAM * 65];
-  float row_lp[DART_MAX_BEAM * 65];
+  // N-gram score of every (beam entry, candidate) pair of the level, filled while the beam
+  // entries' successor rows stream in
+  float s_ng[DART_MAX_LEVEL_NODES];
   // the level's best min(theta, n_new) expansions, sorted by key descending
   uint64_t lvl_key[DART_MAX_BUDGET];
   int32_t lvl_tok[DART_MAX_BUDGET];
@@ -83,15 +83,24 @@ __device__ __forceinline__ int key_creation(uint64_t key) {
   return 0x0FFFFFFF - (int)(key & 0x0FFFFFFF);
 }
 
-// Successor rows of the nb current beam entries -> LDS, coalesced and independent loads.
-__device__ __forceinline__ void stage_rows(PruneShared &sh, const NgramTableDev &tab, int nb, int t) {
-  const int S = tab.S, SP = S + 1;
+// N-gram scores of level L for the nb current beam entries: s_ng[b*k + c] = stored score of
+// candidate c among the successors of beam entry b's context, else the miss score.  The
+// successor rows are read once, coalesced, all loads independent; each loaded successor is
+// compared with the level's k candidates (LDS broadcast reads).  Successor ids are distinct
+// within a row and candidate ids within a level, so at most one thread writes a cell.
+__device__ __forceinline__ void score_rows(PruneShared &sh, const NgramTableDev &tab, int nb, int k,
+                                           int L, int t) {
+  const int S = tab.S;
+  for (int e = t; e < nb * k; e += PRUNE_THREADS) sh.s_ng[e] = tab.logp_miss;
+  __syncthreads();
   for (int idx = t; idx < nb * S; idx += PRUNE_THREADS) {
     const int b = idx / S, j = idx - b * S;
     const int row = sh.beam_row[b];
     if (row >= 0) {
-      sh.row_id[b * SP + j] = tab.succ_ids[(size_t)row * S + j];
-      sh.row_lp[b * SP + j] = tab.succ_logp[(size_t)row * S + j];
+      const int32_t id = tab.succ_ids[(size_t)row * S + j];
+      const float lp = tab.succ_logp[(size_t)row * S + j];
+      for (int c = 0; c < k; ++c)
+        if (sh.cand_id[L * k + c] == id) sh.s_ng[b * k + c] = lp;
     }
   }
 }
@@ -107,7 +116,6 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   const int seq = blockIdx.x, t = threadIdx.x;
   const int theta = budget - 1;
   const int ctx_len = tab.n_gram - 1;
-  const int S = tab.S, SP = S + 1;
   ids += (size_t)seq * K * k;
   scores += (size_t)seq * K * k;
   ctx_tail += (size_t)seq * ctx_len;
@@ -130,7 +138,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   }
   int nb = 1, n_best = 0, cur = 0, bcur = 0;
   __syncthreads();
-  stage_rows(sh, tab, 1, t);
+  score_rows(sh, tab, 1, k, 0, t);
   __syncthreads();
 
   for (int L = 0; L < K; ++L) {
@@ -145,11 +153,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     auto expansion_key = [&](int e, int &tok_out, int &b_out) -> uint64_t {
       const int b = e / k, c = e - b * k;
       const int tok = sh.cand_id[L * k + c];
-      float s_ng = tab.logp_miss;
-      if (sh.beam_row[b] >= 0) {
-        for (int j = 0; j < S; ++j)
-          if (sh.row_id[b * SP + j] == tok) s_ng = sh.row_lp[b * SP + j];   // ids are distinct
-      }
+      const float s_ng = sh.s_ng[e];
       const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
       const float g = __fmul_rn(w_ng, s_ng);
       const float inc = __fmul_rn(__fadd_rn(a, g), wv);
@@ -291,7 +295,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         sh.best_par[bnx][rank] = par;
       }
     }
-    if (!last) stage_rows(sh, tab, nb_next, t);
+    if (!last) score_rows(sh, tab, nb_next, k, L + 1, t);
     n_best = min(theta, n_best + n_lvl);
     bcur = bnx;
     cur = nxt;
