@@ -13,7 +13,7 @@ _LIB = None
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
     "dart_draft_forward_batched", "dart_topk", "dart_ngram_create", "dart_ngram_destroy",
-    "dart_tree_prune", "dart_debug_read", "dart_debug_lm_head",
+    "dart_tree_prune", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
 )
 
 DART_F32, DART_BF16 = 0, 1
@@ -90,6 +90,7 @@ def load_library() -> C.CDLL:
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
     lib.dart_debug_lm_head.argtypes = [vp, i32, vp, vp]
+    lib.dart_debug_set.argtypes = [C.c_char_p, i32]
     _LIB = lib
     return lib
 

@@ -55,13 +55,26 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int off) {
   return ((uint64_t)hi << 32) | lo;
 }
 
+// Wavefront-wide max of an unsigned 32-bit value on the DPP data path (row shifts, then the
+// gfx9 row broadcasts), result returned to every lane.  Lanes without a DPP source read 0,
+// which is neutral for an unsigned max, and max is idempotent, so overlapping shifts are fine.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));  // row_shr:1
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));  // row_shr:2
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));  // row_shr:4
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));  // row_shr:8
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xf, 0xf, false));  // row_bcast:15
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xf, 0xf, false));  // row_bcast:31
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// Wavefront-wide max of a 64-bit key: max of the high words, then max of the low words among
+// the lanes that hold that high word.
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    uint64_t o = shfl_xor_u64(v, off);
-    v = o > v ? o : v;
-  }
-  return v;
+  const uint32_t hi = (uint32_t)(v >> 32);
+  const uint32_t mh = wave_max_u32(hi);
+  const uint32_t ml = wave_max_u32(hi == mh ? (uint32_t)v : 0u);
+  return ((uint64_t)mh << 32) | ml;
 }
 
 // Block-wide sum / max for blocks of up to 1024 threads; `red` is >= 16 floats of LDS.

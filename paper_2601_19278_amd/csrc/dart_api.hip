@@ -171,7 +171,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     const int dims[3] = {d, c->q_dim, F};
     for (int v : dims) c->max_chunks = std::max(c->max_chunks, 4 * gemv_bf16_chunks(v));
   }
-  c->max_splits = (c->t_cap + 127) / 128;
+  c->max_splits = (c->t_cap + 31) / 32;      // room for the smallest key chunk a workgroup may take
   const size_t wide = (size_t)std::max(std::max(d, 2 * F), c->qkv_dim);
   HIP_TRY(dev_alloc(&c->xn, (size_t)R * d));
   HIP_TRY(dev_alloc(&c->resid, (size_t)R * d));
@@ -484,6 +484,19 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
   }
   return from_hip(launch_prune(batch, ids, scores, K, ctx_tail, table->dev, *p, lw, tokens_out,
                                parents_out, mask_out, n_nodes_out, (hipStream_t)stream));
+}
+
+// Diagnostic: set a kernel tunable by name (benchmark sweeps).  Returns 0 if the name is known.
+int dart_debug_set(const char *name, int value) {
+  if (!name) return -1;
+  if (!strcmp(name, "gemv_wgs")) g_gemv_wgs = value;
+  else if (!strcmp(name, "gemv_depth")) g_gemv_depth = value;
+  else if (!strcmp(name, "gemv_nt")) g_gemv_nt = value;
+  else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
+  else if (!strcmp(name, "attn_mt")) g_attn_mt = value < 1 ? 1 : (value > 3 ? 3 : value);
+  else if (!strcmp(name, "attn_chunk")) g_attn_chunk = value < 32 ? 32 : value / 32 * 32;
+  else return -1;
+  return 0;
 }
 
 // Diagnostic: run only the LM-head projection again on the final-normed rows the last forward

@@ -89,6 +89,9 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
   return x;
 }
 
+// Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
+extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_attn_mt, g_attn_chunk;
+
 // All launchers only enqueue work on `st` and return the launch status.
 
 hipError_t launch_rmsnorm_gather(int dtype, const void *hidden, const void *mask_emb,

@@ -138,14 +138,14 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(
       mloc = fmaxf(mloc, __shfl_xor(mloc, 16, DART_WAVE));
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32, DART_WAVE));
       const float mn = fmaxf(m[a], mloc);
-      const float corr = expf(m[a] - mn);
+      const float corr = __expf(m[a] - mn);
       float lsum = 0.f;
       F16x8 pop;
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float p = s[tt][r] > -1.0e38f ? expf(s[tt][r] - mn) : 0.f;
+          const float p = s[tt][r] > -1.0e38f ? __expf(s[tt][r] - mn) : 0.f;
           lsum += p;
           pop.e[4 * tt + r] = (f16_t)p;
         }
@@ -192,16 +192,19 @@ static hipError_t launch_one(const dart_ctx *c, int seq, int n, int Kq, int chun
   return hipGetLastError();
 }
 
+int g_attn_mt = 3;        // query tiles per workgroup (tunable)
+int g_attn_chunk = 128;   // keys per workgroup, multiple of 32 (tunable)
+
 hipError_t launch_attention_bf16(const dart_ctx *c, int seq, int n, int Kq, int *nsplit_out,
                                  hipStream_t st) {
   const dart_config &g = c->cfg;
   const int T = n + Kq - 1;
-  const int chunk = 128;                                   // keys per workgroup, multiple of 32
+  const int chunk = g_attn_chunk;
   const int nsplit = (T + chunk - 1) / chunk;
   *nsplit_out = nsplit;
   const int QV = Kq * (g.n_q_heads / g.n_kv_heads);
   const int tiles = (QV + 15) / 16;
-  const int MT = tiles >= 3 ? 3 : tiles;                   // query tiles per workgroup
+  const int MT = tiles >= g_attn_mt ? g_attn_mt : tiles;   // query tiles per workgroup
   const int zgroups = (tiles + MT - 1) / MT;
   if (g.head_dim == 128) {
     if (MT == 1) return launch_one<128, 1>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
