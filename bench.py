@@ -107,13 +107,16 @@ def main() -> int:
         topk()
         prune()
 
-    # cold call (no cached K/V) first: it also fills the cache for the warm steps
-    ctx.reset()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
+    # cold calls (no cached K/V): the first one also pays one-time kernel loading, so the
+    # second and third are timed; they leave the cache filled for the warm steps
     forward(0)
     torch.cuda.synchronize()
-    cold_us = (time.perf_counter() - t0) * 1e6
+    t0 = time.perf_counter()
+    for _ in range(2):
+        ctx.reset()
+        forward(0)
+    torch.cuda.synchronize()
+    cold_us = (time.perf_counter() - t0) * 1e6 / 2
 
     for _ in range(args.warmup):
         step()

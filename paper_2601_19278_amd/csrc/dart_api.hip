@@ -166,6 +166,16 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   HIP_TRY(hipMemset(c->vbuf, 0, kv_bytes));
 
   const int R = DART_SKINNY_ROWS;
+  c->split_qkv = c->split_o = c->split_gu = c->split_down = 1;
+  c->bulk_rows = 0;
+  if (g.dtype == DART_BF16) {
+    c->split_qkv = gemv_bf16_split(d, c->qkv_dim / 16);
+    c->split_o = gemv_bf16_split(c->q_dim, (d + 15) / 16);
+    c->split_gu = gemv_bf16_split(d, 2 * F / 16);
+    c->split_down = gemv_bf16_split(F, (d + 15) / 16);
+    if (g.max_ctx > R && gemv_bf16_row_tiles(d, c->split_qkv) >= 4)
+      c->bulk_rows = std::min(1024, round_up(g.max_ctx, 64));
+  }
   c->max_chunks = 1;
   if (g.dtype == DART_BF16) {
     const int dims[3] = {d, c->q_dim, F};
@@ -185,6 +195,10 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   HIP_TRY(dev_alloc(&c->yn, (size_t)R * d));
   HIP_TRY(dev_alloc(&c->hmid, (size_t)R * F));
   HIP_TRY(dev_alloc(&c->u, (size_t)R * d));
+  if (c->bulk_rows > 0) {
+    HIP_TRY(dev_alloc(&c->xn_bulk, (size_t)c->bulk_rows * d));
+    HIP_TRY(dev_alloc(&c->kv_bulk, (size_t)c->max_chunks * c->bulk_rows * 2 * c->kv_dim));
+  }
 
   c->max_rows = g.max_batch * g.max_K;
   c->topk_chunks_max = (g.vocab + 4095) / 4096;
@@ -199,16 +213,14 @@ dart_status from_hip(hipError_t e) {
 }
 
 // Projection of M rows of X (fp32 [M][W.Kd]) through output rows [row0, row0+nrows) of W.
-// may_split: the consumer adds k-chunk partials, so the k range may be cut further.
+// split: extra k-split of the matrix (fixed per matrix at create time so that every call cuts
+// k the same way; 1 where the output must be complete in one chunk).
 hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows, const float *X,
-                   int M, float *out, int out_stride, size_t chunk_stride, bool may_split,
-                   int *chunks, hipStream_t st) {
-  if (c->cfg.dtype == DART_BF16) {
-    const int nstrips = (nrows + 15) / 16;
-    const int split = may_split ? gemv_bf16_split(W.Kd, nstrips) : 1;
-    return launch_gemv_bf16(W, row0 / 16, nstrips, X, M, out, out_stride, chunk_stride, split,
-                            chunks, st);
-  }
+                   int M, float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
+                   hipStream_t st) {
+  if (c->cfg.dtype == DART_BF16)
+    return launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride,
+                            split, chunks, st);
   *chunks = 1;
   return launch_gemv_f32(W, row0, nrows, X, M, out, out_stride, st);
 }
@@ -223,12 +235,27 @@ hipError_t qkv_pass(dart_ctx *c, int seq, const void *hidden, int n, int pos0, i
   const size_t cs = (size_t)DART_SKINNY_ROWS * c->qkv_dim;
   int chunks = 1;
   if (Kq > 0) {
-    HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, true, &chunks, st));
+    HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv, &chunks,
+                    st));
   } else {   // K and V rows only
     HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn, M, c->qkv + c->q_dim, c->qkv_dim,
-                    cs, true, &chunks, st));
+                    cs, c->split_qkv, &chunks, st));
   }
-  return launch_qkv_post(c, seq, c->qkv, chunks, cs, M, Kq, pos0, st);
+  return launch_qkv_post(c, seq, c->qkv, chunks, cs, c->qkv_dim, 0, M, Kq, pos0, st);
+}
+
+// Bulk K/V append of prefix rows [r0, r0+M) that are not query rows (M up to bulk_rows): one
+// norm pass, one row-blocked projection through the K and V strips, one append pass.
+hipError_t kv_bulk_pass(dart_ctx *c, int seq, const void *hidden, int n, int r0, int M,
+                        hipStream_t st) {
+  const dart_config &g = c->cfg;
+  HIP_TRY(launch_rmsnorm_gather(g.dtype, hidden, c->mask_emb, c->g_in, n, r0, M, g.d, g.rms_eps,
+                                c->xn_bulk, nullptr, M, st));
+  const size_t cs = (size_t)c->bulk_rows * 2 * c->kv_dim;
+  int chunks = 1;
+  HIP_TRY(launch_gemv_bf16(c->wqkv, c->q_dim / 16, 2 * c->kv_dim / 16, c->xn_bulk, M, c->kv_bulk,
+                           2 * c->kv_dim, cs, c->split_qkv, &chunks, st));
+  return launch_qkv_post(c, seq, c->kv_bulk, chunks, cs, 2 * c->kv_dim, c->q_dim, M, 0, r0, st);
 }
 
 hipError_t forward_one(dart_ctx *c, int seq, const void *hidden, int n, int n_cached, int K,
@@ -238,8 +265,13 @@ hipError_t forward_one(dart_ctx *c, int seq, const void *hidden, int n, int n_ca
   int pos0 = n_cached;
   if ((n - n_cached) + K - 1 > R) {
     // bulk K/V append of the prefix rows that are not query rows
-    for (int r0 = n_cached; r0 < n - 1; r0 += R)
-      HIP_TRY(qkv_pass(c, seq, hidden, n, r0, std::min(R, n - 1 - r0), 0, st));
+    if (c->bulk_rows > 0) {
+      for (int r0 = n_cached; r0 < n - 1; r0 += c->bulk_rows)
+        HIP_TRY(kv_bulk_pass(c, seq, hidden, n, r0, std::min(c->bulk_rows, n - 1 - r0), st));
+    } else {
+      for (int r0 = n_cached; r0 < n - 1; r0 += R)
+        HIP_TRY(qkv_pass(c, seq, hidden, n, r0, std::min(R, n - 1 - r0), 0, st));
+    }
     pos0 = n - 1;
   }
   const int M = n + K - 1 - pos0;
@@ -248,17 +280,18 @@ hipError_t forward_one(dart_ctx *c, int seq, const void *hidden, int n, int n_ca
 
   int chunks = 1;
   size_t cs = (size_t)R * g.d;
-  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, K, c->proj, g.d, cs, true, &chunks, st));
+  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, K, c->proj, g.d, cs, c->split_o, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, K, g.d,
                             g.rms_eps, c->y, c->yn, st));
   cs = (size_t)R * 2 * g.ffn;
-  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, K, c->proj, 2 * g.ffn, cs, true, &chunks, st));
+  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, K, c->proj, 2 * g.ffn, cs, c->split_gu, &chunks,
+                  st));
   HIP_TRY(launch_swiglu(c->proj, chunks, cs, K, g.ffn, g.dtype == DART_BF16, c->hmid, st));
   cs = (size_t)R * g.d;
-  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, K, c->proj, g.d, cs, true, &chunks, st));
+  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, K, c->proj, g.d, cs, c->split_down, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, K, g.d, g.rms_eps,
                             c->u, c->yn, st));
-  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, K, logits, g.vocab, 0, false, &chunks, st));
+  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, K, logits, g.vocab, 0, 1, &chunks, st));
   return hipSuccess;
 }
 
@@ -341,7 +374,8 @@ void dart_destroy(dart_ctx *c) {
   void *bufs[] = {c->wqkv.data, c->wo.data, c->wgu.data, c->wdown.data, c->wlm.data, c->g_in,
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
-                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms};
+                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
+                  c->xn_bulk, c->kv_bulk};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
   free(c->cached_rows);
@@ -504,7 +538,7 @@ int dart_debug_set(const char *name, int value) {
 dart_status dart_debug_lm_head(dart_ctx *c, int K, float *logits_out, void *stream) {
   if (!c || !logits_out || K < 1 || K > c->cfg.max_K) return DART_ERR_ARG;
   int chunks = 1;
-  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, false, &chunks,
+  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, 1, &chunks,
                           (hipStream_t)stream));
 }
 

@@ -68,6 +68,11 @@ struct dart_ctx {
   float *att_out = nullptr;       // [rows][q_dim]
   float *proj = nullptr;          // [chunks][rows][max(d, 2*ffn)] projection partial sums
   float *y = nullptr, *yn = nullptr, *hmid = nullptr, *u = nullptr;
+  // bulk K/V build of a long prefix: row blocks of up to bulk_rows rows (0 = 16 rows at a time)
+  int bulk_rows = 0;
+  float *xn_bulk = nullptr;       // [bulk_rows][d]
+  float *kv_bulk = nullptr;       // [chunks][bulk_rows][2*kv_dim]
+  int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // extra k-split per matrix
   int max_rows;                   // max_batch * max_K
   int max_splits;
   int max_chunks;
@@ -111,12 +116,15 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
                             hipStream_t st);
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
 int gemv_bf16_split(int Kd, int nstrips);     // extra k-split that balances the workgroups
+int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may carry per row block
 
 hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
                          int interleaved, float *h, hipStream_t st);
 
+// qkv: [chunks][M][row_stride] projection partials whose column 0 is column col0 of [q | k | v].
 hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chunks,
-                           size_t chunk_stride, int M, int Kq, int pos0, hipStream_t st);
+                           size_t chunk_stride, int row_stride, int col0, int M, int Kq, int pos0,
+                           hipStream_t st);
 
 hipError_t launch_attention(const dart_ctx *c, int seq, int n, int Kq, hipStream_t st);
 

@@ -59,22 +59,31 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// M8 = true: at most 8 activation rows.  The 16 B-operand columns then carry the hi parts of
-// rows 0..7 in columns 0..7 and their lo parts in columns 8..15, so one MFMA per weight tile
-// yields both products; result[m] = D[.][m] + D[.][m+8].  M8 = false: up to 16 rows, separate
-// hi and lo operands, two MFMAs per tile.
+// MT = 0: at most 8 activation rows.  The 16 B-operand columns then carry the hi parts of rows
+// 0..7 in columns 0..7 and their lo parts in columns 8..15, so one MFMA per weight tile yields
+// both products; result[m] = D[.][m] + D[.][m+8].
+// MT >= 1: up to 16*MT rows as MT column tiles, separate hi and lo operands, 2*MT MFMAs per
+// weight tile (MT = 1 is the 9..16-row case of the draft step; MT = 2, 4 serve the bulk K/V
+// build of a long prefix, where each workgroup takes one block of 16*MT rows, blockIdx.y).
+// All variants accumulate a row's hi products and lo products in two chains in k order and
+// add the eight k-slice partials in the same order, so a row's result does not depend on the
+// variant, on the number of rows, or on which call computed it.
 // EXACT = true: every wavefront owns exactly KPW k-steps (the k range divides evenly), and
 // the main loop is branch-free straight-line code -- the compiler can then keep D loads in
 // flight with exact wait counts.  EXACT = false handles ragged k ranges (unusual shapes) with
 // per-step guards and is not tuned.
-template <int KPW, int D, bool M8, bool NT, bool EXACT>
+template <int KPW, int D, int MT, bool NT, bool EXACT>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
     const u32x4_t *__restrict__ Wp, // packed tiles, 64 x 16 bytes per tile
     const float *__restrict__ X,    // [M][Kd]
     int M, int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols,
     float *__restrict__ out, int out_stride, size_t chunk_stride) {
   static_assert(KPW % D == 0, "a register of the rolling buffer must serve the same slots in every strip");
-  __shared__ float part[2][GEMV_WAVES][M8 ? 256 : 512];
+  constexpr bool M8 = MT == 0;
+  constexpr int NMT = M8 ? 1 : MT;                     // column tiles
+  constexpr int NACC = M8 ? 1 : 2 * MT;                // accumulator tiles per strip
+  constexpr int NBUF = NACC <= 2 ? 2 : 1;              // LDS double buffering while it fits
+  __shared__ float part[NBUF][GEMV_WAVES][NACC * 256];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, gq = lane >> 4;
   const int chunk = blockIdx.x % nchunks;
@@ -82,6 +91,10 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   const int ks0 = (chunk * GEMV_WAVES + wave) * kpw;
   const int nk = EXACT ? KPW : max(0, min(kpw, KT - ks0));   // wave-uniform
   const int Kd = KT * 32;
+  const int row_base = blockIdx.y * 16 * NMT;          // this workgroup's block of rows
+  X += (size_t)row_base * Kd;
+  out += (size_t)row_base * out_stride;
+  M = min(M - row_base, 16 * NMT);
 
   // Rolling buffer of D weight tiles: register t % D serves slot t of every strip; the load
   // for its next slot is issued right after the MFMAs that free it, so about D KiB stay in
@@ -100,30 +113,32 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   // B operands: activations of this wavefront's k slice, split into bf16 hi + bf16 lo
   // (x ~= hi + lo to ~2^-17) so that activations keep fp32-like accuracy while the weights
   // stay the exact bf16 values.
-  constexpr int NB = M8 ? 1 : 2;
-  bf16x8_t bop[NB][KPW];
-  const int xrow = M8 ? (col & 7) : col;
+  bf16x8_t bop[NACC][KPW];
 #pragma unroll
-  for (int t = 0; t < KPW; ++t) {
-    union { bf16x8_t v; bf16_t e[8]; } h, l;
+  for (int mt = 0; mt < NMT; ++mt) {
+    const int xrow = M8 ? (col & 7) : 16 * mt + col;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) h.e[e] = l.e[e] = 0;
-    if (t < nk && xrow < M) {
-      const float *src = X + (size_t)xrow * Kd + (size_t)(ks0 + t) * 32 + 8 * gq;
-      const float4 lo4 = *reinterpret_cast<const float4 *>(src);
-      const float4 hi4 = *reinterpret_cast<const float4 *>(src + 4);
-      const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+    for (int t = 0; t < KPW; ++t) {
+      union { bf16x8_t v; bf16_t e[8]; } h, l;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        h.e[e] = f32_to_bf16(x[e]);
-        l.e[e] = f32_to_bf16(x[e] - bf16_to_f32(h.e[e]));
+      for (int e = 0; e < 8; ++e) h.e[e] = l.e[e] = 0;
+      if (t < nk && xrow < M) {
+        const float *src = X + (size_t)xrow * Kd + (size_t)(ks0 + t) * 32 + 8 * gq;
+        const float4 lo4 = *reinterpret_cast<const float4 *>(src);
+        const float4 hi4 = *reinterpret_cast<const float4 *>(src + 4);
+        const float x[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          h.e[e] = f32_to_bf16(x[e]);
+          l.e[e] = f32_to_bf16(x[e] - bf16_to_f32(h.e[e]));
+        }
       }
-    }
-    if (M8) {
-      bop[0][t] = col < 8 ? h.v : l.v;
-    } else {
-      bop[0][t] = h.v;
-      bop[NB - 1][t] = l.v;
+      if (M8) {
+        bop[0][t] = col < 8 ? h.v : l.v;
+      } else {
+        bop[2 * mt][t] = h.v;
+        bop[NACC > 1 ? 2 * mt + 1 : 0][t] = l.v;
+      }
     }
   }
 
@@ -132,15 +147,16 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
     const int sn = s + nwg;
     const u32x4_t *cur = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
     const u32x4_t *next = Wp + ((size_t)(strip0 + (sn < nstrips ? sn : s)) * KT + ks0) * 64 + lane;
-    // One accumulator chain for the hi products and one for the lo products, both in k
-    // order, so a row's result does not depend on which variant (or how many rows) ran.
-    f32x4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t acc[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int t = 0; t < KPW; ++t) {
       if (EXACT || t < nk) {
         const bf16x8_t a = __builtin_bit_cast(bf16x8_t, aop[t % D]);
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[0][t], acc0, 0, 0, 0);
-        if (!M8) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[NB - 1][t], acc1, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NACC; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[i][t], acc[i], 0, 0, 0);
         if (EXACT) {
           aop[t % D] = load_tile<NT>(t + D < KPW ? cur + (size_t)(t + D) * 64
                                                    : next + (size_t)(t + D - KPW) * 64);
@@ -154,42 +170,47 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
         }
       }
     }
-    *reinterpret_cast<float4 *>(&part[buf][wave][lane * 4]) =
-        make_float4(acc0[0], acc0[1], acc0[2], acc0[3]);
-    if (!M8)
-      *reinterpret_cast<float4 *>(&part[buf][wave][256 + lane * 4]) =
-          make_float4(acc1[0], acc1[1], acc1[2], acc1[3]);
+    if (NBUF == 1) lds_barrier();                      // the previous strip's readers are done
+#pragma unroll
+    for (int i = 0; i < NACC; ++i)
+      *reinterpret_cast<float4 *>(&part[buf][wave][i * 256 + lane * 4]) =
+          make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
     lds_barrier();
-    const int m = threadIdx.x >> 4, row = threadIdx.x & 15;
-    if (m < (M8 ? 8 : 16)) {
-      // D[row][c] lives in lane (row/4)*16 + c, register row%4.  M8: lo products sit in
-      // column m + 8 of the same tile; otherwise in the second tile.
-      const int idx = (((row >> 2) * 16) + m) * 4 + (row & 3);
+    // D[row][c] of a tile lives in lane (row/4)*16 + c, register row%4.  MT = 0: lo products
+    // sit in column m + 8 of the same tile; otherwise in the tile after the hi tile.
+    for (int o = threadIdx.x; o < (M8 ? 128 : 256 * NMT); o += GEMV_THREADS) {
+      const int mt = o >> 8, m = (o >> 4) & 15, row = o & 15;
+      const int idx = (M8 ? 0 : 2 * mt * 256) + (((row >> 2) * 16) + m) * 4 + (row & 3);
       const int idx_lo = M8 ? idx + 32 : idx + 256;
       float v_hi = 0.f, v_lo = 0.f;
 #pragma unroll
       for (int w = 0; w < GEMV_WAVES; ++w) v_hi += part[buf][w][idx];
 #pragma unroll
       for (int w = 0; w < GEMV_WAVES; ++w) v_lo += part[buf][w][idx_lo];
-      const int c = s * 16 + row;
-      if (m < M && c < n_cols) out[chunk * chunk_stride + (size_t)m * out_stride + c] = v_hi + v_lo;
+      const int c = s * 16 + row, mm = 16 * mt + m;
+      if (mm < M && c < n_cols)
+        out[chunk * chunk_stride + (size_t)mm * out_stride + c] = v_hi + v_lo;
     }
-    buf ^= 1;
+    if (NBUF == 2) buf ^= 1;
   }
 }
 
 template <int KPW, int D, bool EXACT>
-static void gemv_launch(bool m8, dim3 grid, hipStream_t st, const u32x4_t *wp, const float *X, int M,
+static void gemv_launch(int mt, dim3 grid, hipStream_t st, const u32x4_t *wp, const float *X, int M,
                         int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols, float *out,
                         int out_stride, size_t chunk_stride) {
-#define DART_GEMV_GO(M8_, NT_)                                                                    \
-  hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, M8_, NT_, EXACT>), grid, dim3(GEMV_THREADS), 0, st, \
+#define DART_GEMV_GO(MT_, NT_)                                                                    \
+  hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, MT_, NT_, EXACT>), grid, dim3(GEMV_THREADS), 0, st, \
                      wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,         \
                      chunk_stride)
-  if (m8 && g_gemv_nt) DART_GEMV_GO(true, true);
-  else if (m8) DART_GEMV_GO(true, false);
-  else if (g_gemv_nt) DART_GEMV_GO(false, true);
-  else DART_GEMV_GO(false, false);
+  if constexpr (KPW <= 5) {                            // the row-block variants need short k-slices
+    if (mt == 4) { if (g_gemv_nt) DART_GEMV_GO(4, true); else DART_GEMV_GO(4, false); return; }
+    if (mt == 2) { if (g_gemv_nt) DART_GEMV_GO(2, true); else DART_GEMV_GO(2, false); return; }
+  }
+  if (mt == 0 && g_gemv_nt) DART_GEMV_GO(0, true);
+  else if (mt == 0) DART_GEMV_GO(0, false);
+  else if (g_gemv_nt) DART_GEMV_GO(1, true);
+  else DART_GEMV_GO(1, false);
 #undef DART_GEMV_GO
 }
 
@@ -222,9 +243,19 @@ int gemv_bf16_split(int Kd, int nstrips) {
   return 1;
 }
 
+// Largest row block (in 16-row tiles) the kernel can take for this matrix and split: the
+// activations of a block must fit the register budget next to the weight buffer.
+int gemv_bf16_row_tiles(int Kd, int split) {
+  const int KT = Kd / 32, nch = gemv_bf16_chunks(Kd) * split;
+  if (KT % (GEMV_WAVES * nch) != 0) return 1;
+  const int kpw = KT / (GEMV_WAVES * nch);
+  return kpw <= 5 && exact_kpw_supported(kpw) ? 4 : 1;
+}
+
 // Strips [strip0, strip0+nstrips) of the packed matrix; out[chunk][m][j], j < nstrips*16
 // (columns beyond W.n_real - strip0*16 are not written).  split: extra k-split (1 when the
-// output must be complete in a single chunk).
+// output must be complete in a single chunk).  M may exceed 16 only up to
+// 16 * gemv_bf16_row_tiles(Kd, split) * any number of row blocks (grid.y).
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                             hipStream_t st) {
@@ -234,14 +265,21 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   const bool exact = kpw * GEMV_WAVES * nchunks == KT;
   if (chunks) *chunks = nchunks;
   const int n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
-  int wgs = g_gemv_wgs / nchunks;
+  int mt = M <= 8 ? 0 : 1, row_blocks = 1;
+  if (M > 16) {
+    const int cap = gemv_bf16_row_tiles(W.Kd, split);
+    if (cap < 2) return hipErrorInvalidValue;          // caller must pass <= 16 rows per launch
+    mt = M > 32 ? 4 : 2;
+    row_blocks = (M + 16 * mt - 1) / (16 * mt);
+  }
+  int wgs = g_gemv_wgs / (nchunks * row_blocks);
   if (wgs > nstrips) wgs = nstrips;
   if (wgs < 1) wgs = 1;
-  dim3 grid(wgs * nchunks);
+  dim3 grid(wgs * nchunks, row_blocks);
   const u32x4_t *wp = (const u32x4_t *)W.data;
-  const bool m8 = M <= 8;
   const int depth = g_gemv_depth;
-#define DART_GEMV_ARGS m8, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
+  const bool m8 = mt == 0;
+#define DART_GEMV_ARGS mt, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
   if (exact && kpw == 20) {
     if (depth == 10 || (depth == 0 && !m8)) gemv_launch<20, 10, true>(DART_GEMV_ARGS);
     else if (depth == 5) gemv_launch<20, 5, true>(DART_GEMV_ARGS);

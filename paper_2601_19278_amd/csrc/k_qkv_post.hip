@@ -12,7 +12,8 @@ namespace dart {
 // T: storage type of the norm gains; CT: element type of q and of the K/V buffers.
 template <typename T, typename CT>
 __global__ __launch_bounds__(128) void qkv_post_kernel(
-    const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride, int M, int Kq,
+    const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride, int col0, int M,
+    int Kq,
     int pos0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
     const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
     const float *__restrict__ sin_tab, CT *__restrict__ q_out, CT *__restrict__ kbuf,
@@ -23,7 +24,7 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
   const int pos = pos0 + i;
   const bool is_q = hh < Hq, is_k = !is_q && hh < Hq + Hkv;
   if (is_q && i < M - Kq) return;                 // non-query rows need no q (uniform per block)
-  const int col = hh * hd + t;                    // q heads, then k heads, then v heads
+  const int col = hh * hd + t - col0;             // q heads, then k heads, then v heads
   float x = 0.f;
   for (int c = 0; c < chunks; ++c) x += qkv[c * chunk_stride + (size_t)i * row_stride + col];
 
@@ -55,7 +56,8 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
 }
 
 hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chunks,
-                           size_t chunk_stride, int M, int Kq, int pos0, hipStream_t st) {
+                           size_t chunk_stride, int row_stride, int col0, int M, int Kq, int pos0,
+                           hipStream_t st) {
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
   const size_t seq_elems = (size_t)Hkv * c->t_cap * hd;
@@ -63,13 +65,13 @@ hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chu
   if (g.dtype == DART_BF16) {
     f16_t *kb = (f16_t *)c->kbuf + seq * seq_elems, *vb = (f16_t *)c->vbuf + seq * seq_elems;
     hipLaunchKernelGGL((qkv_post_kernel<bf16_t, f16_t>), grid, block, 0, st, qkv, chunks,
-                       chunk_stride, c->qkv_dim, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
+                       chunk_stride, row_stride, col0, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
                        (const bf16_t *)c->g_q, (const bf16_t *)c->g_k, c->rope_cos, c->rope_sin,
                        (f16_t *)c->qrot, kb, vb, c->t_cap, 1);
   } else {
     float *kb = (float *)c->kbuf + seq * seq_elems, *vb = (float *)c->vbuf + seq * seq_elems;
     hipLaunchKernelGGL((qkv_post_kernel<float, float>), grid, block, 0, st, qkv, chunks,
-                       chunk_stride, c->qkv_dim, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
+                       chunk_stride, row_stride, col0, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
                        (const float *)c->g_q, (const float *)c->g_k, c->rope_cos, c->rope_sin,
                        (float *)c->qrot, kb, vb, c->t_cap, 0);
   }
