@@ -160,3 +160,37 @@ def test_c2_full_size_matches_oracle():
 def test_c4_headline_full_size_matches_oracle():
     cfg = ds.get_config("C4")
     _run(cfg, 1000 * 4, n_cached_list=(0, cfg.ctx - 1, cfg.ctx - 4))
+
+
+def test_c3_full_size_matches_oracle():
+    cfg = ds.get_config("C3")
+    _run(cfg, 1000 * 3, n_cached_list=(0, cfg.ctx - 1, cfg.ctx - 4))
+
+
+def test_c5_batched_ragged_full_size_sampled_sequences_match_oracle():
+    """Preset C5: 16 ragged sequences through dart_draft_forward_batched; the oracle checks the
+    shortest, the median and the longest sequence (all K x vocab logits of each)."""
+    from dart_synth.tensors import make_ragged_lengths
+    cfg = ds.get_config("C5")
+    ctx, W = make_context(cfg, 5000)
+    lens = make_ragged_lengths(cfg, 5001).tolist()
+    hiddens = [ds.make_hidden(cfg, 5002 + b, n=lens[b]) for b in range(cfg.batch)]
+    devs = [hidden_to_device(cfg, h) for h in hiddens]
+    out = ctx.draft_forward_batched(devs, lens, [0] * cfg.batch, cfg.K).cpu().numpy()
+    order = np.argsort(lens)
+    for b in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):
+        ref = odf.draft_forward(cfg, W, hiddens[b], cfg.K)
+        ok, msg = logits_close(out[b], ref, **BF16_TOL)
+        assert ok, f"sequence {b} (n={lens[b]}): {msg}"
+    # a second, warm batched call (one new token per sequence) reproduces a cold call bit for bit
+    lens2 = [min(n + 1, cfg.ctx) for n in lens]
+    hid2 = [ds.make_hidden(cfg, 5002 + b, n=lens2[b]) for b in range(cfg.batch)]
+    for b in range(cfg.batch):
+        assert np.array_equal(hid2[b][: lens[b]], hiddens[b])
+    dev2 = [hidden_to_device(cfg, h) for h in hid2]
+    warm = ctx.draft_forward_batched(dev2, lens2, lens, cfg.K).cpu().numpy()
+    for b in range(cfg.batch):
+        ctx.reset(b)
+    cold = ctx.draft_forward_batched(dev2, lens2, [0] * cfg.batch, cfg.K).cpu().numpy()
+    np.testing.assert_array_equal(warm, cold)
+    ctx.close()
