@@ -189,7 +189,7 @@ int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_
 dart_status dart_debug_lm_head(dart_ctx *ctx, int K, float *logits_out, void *stream);
 
 /* Diagnostic (benchmark sweeps only): override a launch tunable of the kernels by name
- * ("gemv_wgs", "gemv_depth", "gemv_nt", "gemv_split", "attn_mt", "attn_chunk").  Process-wide,
+ * ("gemv_wgs", "gemv_depth", "gemv_nt", "gemv_split", "attn_mt").  Process-wide,
  * not thread-safe.  Returns 0, or -1 for an unknown name. */
 int dart_debug_set(const char *name, int value);
 

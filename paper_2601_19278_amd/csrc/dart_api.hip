@@ -167,38 +167,40 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
 
   const int R = DART_SKINNY_ROWS;
   c->split_qkv = c->split_o = c->split_gu = c->split_down = 1;
-  c->bulk_rows = 0;
+  int ch_qkv = 1, ch_o = 1, ch_gu = 1, ch_down = 1;      // k-chunks each projection writes
+  c->kv_rows = R;
   if (g.dtype == DART_BF16) {
     c->split_qkv = gemv_bf16_split(d, c->qkv_dim / 16);
     c->split_o = gemv_bf16_split(c->q_dim, (d + 15) / 16);
     c->split_gu = gemv_bf16_split(d, 2 * F / 16);
     c->split_down = gemv_bf16_split(F, (d + 15) / 16);
+    ch_qkv = gemv_bf16_chunks(d) * c->split_qkv;
+    ch_o = gemv_bf16_chunks(c->q_dim) * c->split_o;
+    ch_gu = gemv_bf16_chunks(d) * c->split_gu;
+    ch_down = gemv_bf16_chunks(F) * c->split_down;
     if (g.max_ctx > R && gemv_bf16_row_tiles(d, c->split_qkv) >= 4)
-      c->bulk_rows = std::min(1024, round_up(g.max_ctx, 64));
+      c->kv_rows = std::min(1024, round_up(g.max_ctx, 64));
   }
-  c->max_chunks = 1;
-  if (g.dtype == DART_BF16) {
-    const int dims[3] = {d, c->q_dim, F};
-    for (int v : dims) c->max_chunks = std::max(c->max_chunks, 4 * gemv_bf16_chunks(v));
-  }
-  c->max_splits = (c->t_cap + 31) / 32;      // room for the smallest key chunk a workgroup may take
-  const size_t wide = (size_t)std::max(std::max(d, 2 * F), c->qkv_dim);
-  HIP_TRY(dev_alloc(&c->xn, (size_t)R * d));
-  HIP_TRY(dev_alloc(&c->resid, (size_t)R * d));
-  HIP_TRY(dev_alloc(&c->qkv, (size_t)c->max_chunks * R * c->qkv_dim));
-  HIP_TRY(hipMalloc(&c->qrot, (size_t)R * c->q_dim * 4));
-  HIP_TRY(dev_alloc(&c->att_part, (size_t)R * g.n_q_heads * c->max_splits * hd));
-  HIP_TRY(dev_alloc(&c->att_ml, (size_t)R * g.n_q_heads * c->max_splits * 2));
-  HIP_TRY(dev_alloc(&c->att_out, (size_t)R * c->q_dim));
-  HIP_TRY(dev_alloc(&c->proj, (size_t)c->max_chunks * R * wide));
-  HIP_TRY(dev_alloc(&c->y, (size_t)R * d));
-  HIP_TRY(dev_alloc(&c->yn, (size_t)R * d));
-  HIP_TRY(dev_alloc(&c->hmid, (size_t)R * F));
-  HIP_TRY(dev_alloc(&c->u, (size_t)R * d));
-  if (c->bulk_rows > 0) {
-    HIP_TRY(dev_alloc(&c->xn_bulk, (size_t)c->bulk_rows * d));
-    HIP_TRY(dev_alloc(&c->kv_bulk, (size_t)c->max_chunks * c->bulk_rows * 2 * c->kv_dim));
-  }
+  // one pass carries the query rows of up to DART_SEQ_GROUP sequences
+  c->ws_rows = std::max(R, std::min(g.max_batch, DART_SEQ_GROUP) * g.max_K);
+  const size_t W = c->ws_rows;
+  c->max_splits = (c->t_cap + ATTN_KEY_CHUNK - 1) / ATTN_KEY_CHUNK;
+  const size_t proj_elems = std::max(std::max((size_t)ch_o * d, (size_t)ch_down * d),
+                                     (size_t)ch_gu * 2 * F);
+  HIP_TRY(dev_alloc(&c->xn, W * d));
+  HIP_TRY(dev_alloc(&c->resid, W * d));
+  HIP_TRY(dev_alloc(&c->qkv, (size_t)ch_qkv * W * c->qkv_dim));
+  HIP_TRY(hipMalloc(&c->qrot, W * c->q_dim * 4));
+  HIP_TRY(dev_alloc(&c->att_part, W * g.n_q_heads * c->max_splits * hd));
+  HIP_TRY(dev_alloc(&c->att_ml, W * g.n_q_heads * c->max_splits * 2));
+  HIP_TRY(dev_alloc(&c->att_out, W * c->q_dim));
+  HIP_TRY(dev_alloc(&c->proj, W * proj_elems));
+  HIP_TRY(dev_alloc(&c->y, W * d));
+  HIP_TRY(dev_alloc(&c->yn, W * d));
+  HIP_TRY(dev_alloc(&c->hmid, W * F));
+  HIP_TRY(dev_alloc(&c->u, W * d));
+  HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * d));
+  HIP_TRY(dev_alloc(&c->kv_part, (size_t)ch_qkv * c->kv_rows * 2 * c->kv_dim));
 
   c->max_rows = g.max_batch * g.max_K;
   c->topk_chunks_max = (g.vocab + 4095) / 4096;
@@ -212,86 +214,120 @@ dart_status from_hip(hipError_t e) {
   return e == hipErrorOutOfMemory ? DART_ERR_OOM : DART_ERR_HIP;
 }
 
-// Projection of M rows of X (fp32 [M][W.Kd]) through output rows [row0, row0+nrows) of W.
+// Projection of M rows of X (fp32 [M][W.Kd]) through output rows [row0, row0+nrows) of W;
+// out[chunk][m][j] with row stride out_stride and chunk stride chunk_stride.
 // split: extra k-split of the matrix (fixed per matrix at create time so that every call cuts
 // k the same way; 1 where the output must be complete in one chunk).
 hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows, const float *X,
                    int M, float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                    hipStream_t st) {
-  if (c->cfg.dtype == DART_BF16)
-    return launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride,
-                            split, chunks, st);
-  *chunks = 1;
-  return launch_gemv_f32(W, row0, nrows, X, M, out, out_stride, st);
-}
-
-// One pass of rows [pos0, pos0+M) through norm + QKV projection + K/V append; the last Kq
-// rows are query rows.
-hipError_t qkv_pass(dart_ctx *c, int seq, const void *hidden, int n, int pos0, int M, int Kq,
-                    hipStream_t st) {
-  const dart_config &g = c->cfg;
-  HIP_TRY(launch_rmsnorm_gather(g.dtype, hidden, c->mask_emb, c->g_in, n, pos0, M, g.d, g.rms_eps,
-                                c->xn, c->resid, M - Kq, st));
-  const size_t cs = (size_t)DART_SKINNY_ROWS * c->qkv_dim;
-  int chunks = 1;
-  if (Kq > 0) {
-    HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv, &chunks,
-                    st));
-  } else {   // K and V rows only
-    HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn, M, c->qkv + c->q_dim, c->qkv_dim,
-                    cs, c->split_qkv, &chunks, st));
+  const int R = DART_SKINNY_ROWS;
+  if (c->cfg.dtype == DART_BF16) {
+    if (M <= R || gemv_bf16_row_tiles(W.Kd, split) >= 2)
+      return launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride,
+                              split, chunks, st);
+    for (int m0 = 0; m0 < M; m0 += R)
+      HIP_TRY(launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X + (size_t)m0 * W.Kd,
+                               std::min(R, M - m0), out + (size_t)m0 * out_stride, out_stride,
+                               chunk_stride, split, chunks, st));
+    return hipSuccess;
   }
-  return launch_qkv_post(c, seq, c->qkv, chunks, cs, c->qkv_dim, 0, M, Kq, pos0, st);
+  *chunks = 1;
+  for (int m0 = 0; m0 < M; m0 += R)
+    HIP_TRY(launch_gemv_f32(W, row0, nrows, X + (size_t)m0 * W.Kd, std::min(R, M - m0),
+                            out + (size_t)m0 * out_stride, out_stride, st));
+  return hipSuccess;
 }
 
-// Bulk K/V append of prefix rows [r0, r0+M) that are not query rows (M up to bulk_rows): one
-// norm pass, one row-blocked projection through the K and V strips, one append pass.
-hipError_t kv_bulk_pass(dart_ctx *c, int seq, const void *hidden, int n, int r0, int M,
-                        hipStream_t st) {
+// One sequence of a forward call.
+struct SeqJob {
+  int slot;
+  const void *hidden;
+  int n, n_cached;
+};
+
+// K/V-only pass: norm + K and V projection + append for the rows described by sb (sb.K = 0,
+// at most kv_rows rows).
+hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
   const dart_config &g = c->cfg;
-  HIP_TRY(launch_rmsnorm_gather(g.dtype, hidden, c->mask_emb, c->g_in, n, r0, M, g.d, g.rms_eps,
-                                c->xn_bulk, nullptr, M, st));
-  const size_t cs = (size_t)c->bulk_rows * 2 * c->kv_dim;
+  const int M = sb.row_off[sb.B];
+  HIP_TRY(launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, c->xn_kv,
+                                nullptr, st));
+  const size_t cs = (size_t)c->kv_rows * 2 * c->kv_dim;
   int chunks = 1;
-  HIP_TRY(launch_gemv_bf16(c->wqkv, c->q_dim / 16, 2 * c->kv_dim / 16, c->xn_bulk, M, c->kv_bulk,
-                           2 * c->kv_dim, cs, c->split_qkv, &chunks, st));
-  return launch_qkv_post(c, seq, c->kv_bulk, chunks, cs, 2 * c->kv_dim, c->q_dim, M, 0, r0, st);
+  HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn_kv, M, c->kv_part, 2 * c->kv_dim, cs,
+                  c->split_qkv, &chunks, st));
+  return launch_qkv_post(c, sb, c->kv_part, chunks, cs, 2 * c->kv_dim, c->q_dim, st);
 }
 
-hipError_t forward_one(dart_ctx *c, int seq, const void *hidden, int n, int n_cached, int K,
-                       float *logits, hipStream_t st) {
+// Draft forward of up to DART_SEQ_GROUP sequences; logits [B][K][vocab].
+hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, float *logits,
+                         hipStream_t st) {
   const dart_config &g = c->cfg;
   const int R = DART_SKINNY_ROWS;
-  int pos0 = n_cached;
-  if ((n - n_cached) + K - 1 > R) {
-    // bulk K/V append of the prefix rows that are not query rows
-    if (c->bulk_rows > 0) {
-      for (int r0 = n_cached; r0 < n - 1; r0 += c->bulk_rows)
-        HIP_TRY(kv_bulk_pass(c, seq, hidden, n, r0, std::min(c->bulk_rows, n - 1 - r0), st));
-    } else {
-      for (int r0 = n_cached; r0 < n - 1; r0 += R)
-        HIP_TRY(qkv_pass(c, seq, hidden, n, r0, std::min(R, n - 1 - r0), 0, st));
+  // A single sequence with few new rows takes one pass for all of them; otherwise the prefix
+  // rows that are not query rows go through K/V-only passes first.
+  const bool combined = B == 1 && (jobs[0].n - jobs[0].n_cached) + K - 1 <= R;
+  if (!combined) {
+    SeqBatch sb{};
+    auto flush = [&]() -> hipError_t {
+      if (sb.B == 0) return hipSuccess;
+      hipError_t e = kv_pass(c, sb, st);
+      sb = SeqBatch{};
+      return e;
+    };
+    for (int b = 0; b < B; ++b) {
+      int r0 = jobs[b].n_cached;
+      while (r0 < jobs[b].n - 1) {
+        const int room = c->kv_rows - sb.row_off[sb.B];
+        const int take = std::min(room, jobs[b].n - 1 - r0);
+        const int i = sb.B++;
+        sb.hidden[i] = jobs[b].hidden;
+        sb.n[i] = jobs[b].n;
+        sb.pos0[i] = r0;
+        sb.slot[i] = jobs[b].slot;
+        sb.row_off[i + 1] = sb.row_off[i] + take;
+        r0 += take;
+        if (sb.row_off[sb.B] == c->kv_rows || sb.B == DART_SEQ_GROUP) HIP_TRY(flush());
+      }
     }
-    pos0 = n - 1;
+    HIP_TRY(flush());
   }
-  const int M = n + K - 1 - pos0;
-  HIP_TRY(qkv_pass(c, seq, hidden, n, pos0, M, K, st));
-  HIP_TRY(launch_attention(c, seq, n, K, st));
 
+  SeqBatch sb{};
+  sb.B = B;
+  sb.K = K;
+  for (int b = 0; b < B; ++b) {
+    sb.hidden[b] = jobs[b].hidden;
+    sb.n[b] = jobs[b].n;
+    sb.pos0[b] = combined ? jobs[b].n_cached : jobs[b].n - 1;
+    sb.slot[b] = jobs[b].slot;
+    sb.row_off[b + 1] = sb.row_off[b] + (jobs[b].n - sb.pos0[b]) + K - 1;
+  }
+  const int M = sb.row_off[B], QR = B * K;       // pass rows, query rows
+  const size_t W = c->ws_rows;
+  HIP_TRY(launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, c->xn, c->resid,
+                                st));
   int chunks = 1;
-  size_t cs = (size_t)R * g.d;
-  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, K, c->proj, g.d, cs, c->split_o, &chunks, st));
-  HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, K, g.d,
-                            g.rms_eps, c->y, c->yn, st));
-  cs = (size_t)R * 2 * g.ffn;
-  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, K, c->proj, 2 * g.ffn, cs, c->split_gu, &chunks,
+  size_t cs = W * c->qkv_dim;
+  HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv, &chunks,
                   st));
-  HIP_TRY(launch_swiglu(c->proj, chunks, cs, K, g.ffn, g.dtype == DART_BF16, c->hmid, st));
-  cs = (size_t)R * g.d;
-  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, K, c->proj, g.d, cs, c->split_down, &chunks, st));
-  HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, K, g.d, g.rms_eps,
+  HIP_TRY(launch_qkv_post(c, sb, c->qkv, chunks, cs, c->qkv_dim, 0, st));
+  HIP_TRY(launch_attention(c, sb, st));
+
+  cs = W * g.d;
+  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, QR, c->proj, g.d, cs, c->split_o, &chunks, st));
+  HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, QR, g.d,
+                            g.rms_eps, c->y, c->yn, st));
+  cs = W * 2 * g.ffn;
+  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, QR, c->proj, 2 * g.ffn, cs, c->split_gu, &chunks,
+                  st));
+  HIP_TRY(launch_swiglu(c->proj, chunks, cs, QR, g.ffn, g.dtype == DART_BF16, c->hmid, st));
+  cs = W * g.d;
+  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down, &chunks, st));
+  HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
                             c->u, c->yn, st));
-  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, K, logits, g.vocab, 0, 1, &chunks, st));
+  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, QR, logits, g.vocab, 0, 1, &chunks, st));
   return hipSuccess;
 }
 
@@ -375,7 +411,7 @@ void dart_destroy(dart_ctx *c) {
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
-                  c->xn_bulk, c->kv_bulk};
+                  c->xn_kv, c->kv_part};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
   free(c->cached_rows);
@@ -392,7 +428,9 @@ dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx
                                int K, float *logits_out, void *stream) {
   dart_status s = check_forward_args(c, seq, hidden, ctx_len, n_cached, K, logits_out);
   if (s != DART_OK) return s;
-  hipError_t e = forward_one(c, seq, hidden, ctx_len, n_cached, K, logits_out, (hipStream_t)stream);
+  const SeqJob job{seq, hidden, ctx_len, n_cached};
+  c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
+  hipError_t e = forward_group(c, 1, &job, K, logits_out, (hipStream_t)stream);
   if (e != hipSuccess) return from_hip(e);
   c->cached_rows[seq] = ctx_len;
   return DART_OK;
@@ -407,11 +445,17 @@ dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const
     dart_status s = check_forward_args(c, b, hidden[b], ctx_len[b], n_cached[b], K, logits_out);
     if (s != DART_OK) return s;
   }
-  for (int b = 0; b < batch; ++b) {
-    hipError_t e = forward_one(c, b, hidden[b], ctx_len[b], n_cached[b], K,
-                               logits_out + (size_t)b * K * c->cfg.vocab, (hipStream_t)stream);
+  for (int b0 = 0; b0 < batch; b0 += DART_SEQ_GROUP) {
+    const int nb = std::min(DART_SEQ_GROUP, batch - b0);
+    SeqJob jobs[DART_SEQ_GROUP];
+    for (int i = 0; i < nb; ++i) {
+      jobs[i] = SeqJob{b0 + i, hidden[b0 + i], ctx_len[b0 + i], n_cached[b0 + i]};
+      c->cached_rows[b0 + i] = 0;
+    }
+    hipError_t e = forward_group(c, nb, jobs, K, logits_out + (size_t)b0 * K * c->cfg.vocab,
+                                 (hipStream_t)stream);
     if (e != hipSuccess) return from_hip(e);
-    c->cached_rows[b] = ctx_len[b];
+    for (int i = 0; i < nb; ++i) c->cached_rows[b0 + i] = ctx_len[b0 + i];
   }
   return DART_OK;
 }
@@ -528,7 +572,6 @@ int dart_debug_set(const char *name, int value) {
   else if (!strcmp(name, "gemv_nt")) g_gemv_nt = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
   else if (!strcmp(name, "attn_mt")) g_attn_mt = value < 1 ? 1 : (value > 3 ? 3 : value);
-  else if (!strcmp(name, "attn_chunk")) g_attn_chunk = value < 32 ? 32 : value / 32 * 32;
   else return -1;
   return 0;
 }

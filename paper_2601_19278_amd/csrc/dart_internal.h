@@ -6,6 +6,7 @@
 #include "../../include/dart.h"
 
 #define DART_SKINNY_ROWS 16   // rows one skinny-GEMM pass carries (one MFMA column block)
+#define ATTN_KEY_CHUNK 128    // keys one attention workgroup walks (split-KV granularity)
 
 // One weight matrix on the device.  fp32: row-major [N][Kd].  bf16: re-tiled for
 // v_mfma_f32_16x16x32_bf16 (see pack_bf16_tiles in dart_api.hip): tile (strip s of 16
@@ -46,6 +47,30 @@ struct PruneLevelWeights {
   float w_level[DART_MAX_K];
 };
 
+// One pass of the layer over rows of up to DART_SEQ_GROUP sequences, passed to kernels by
+// value.  The pass's rows are the concatenation, sequence after sequence, of positions
+// [pos0[b], pos0[b] + rows_b); row_off[b] is the first row of sequence b (row_off[B] = total).
+// The last K rows of every sequence are its query rows (K = 0: a K/V-only pass); query row j
+// of sequence b has the compact index b*K + j in the q / residual / output buffers.
+#define DART_SEQ_GROUP 16
+struct SeqBatch {
+  int B, K;
+  const void *hidden[DART_SEQ_GROUP];   // [n][d] prefix representation of the sequence
+  int n[DART_SEQ_GROUP];                // prefix length
+  int pos0[DART_SEQ_GROUP];             // first position of the sequence's rows in this pass
+  int row_off[DART_SEQ_GROUP + 1];
+  int slot[DART_SEQ_GROUP];             // K/V buffer slot
+};
+
+// Sequence b, position pos and query index qi (< 0 for a non-query row) of pass row r.
+__host__ __device__ inline void seq_of_row(const SeqBatch &sb, int r, int &b, int &pos, int &qi) {
+  b = 0;
+  while (b + 1 < sb.B && r >= sb.row_off[b + 1]) ++b;
+  const int local = r - sb.row_off[b];
+  pos = sb.pos0[b] + local;
+  qi = local - (sb.row_off[b + 1] - sb.row_off[b] - sb.K);
+}
+
 struct dart_ctx {
   dart_config cfg;
   int q_dim, kv_dim, qkv_dim;
@@ -58,24 +83,24 @@ struct dart_ctx {
   // draft K/V buffers: K [batch][Hkv][t_cap][hd]; V fp32 same, bf16 transposed [batch][Hkv][hd][t_cap]
   void *kbuf = nullptr, *vbuf = nullptr;
   int *cached_rows = nullptr;     // host, [max_batch]
-  // activations / workspaces (device, fp32 unless noted)
-  float *xn = nullptr;            // [16][d] normed layer input
-  float *resid = nullptr;         // [rows][d] raw input rows of the query positions
-  float *qkv = nullptr;           // [chunks][16][qkv_dim]
-  void *qrot = nullptr;           // [rows][q_dim] queries after norm + rotary (fp32 or bf16)
-  float *att_part = nullptr;      // [rows*Hq][splits][hd]
-  float *att_ml = nullptr;        // [rows*Hq][splits][2]
-  float *att_out = nullptr;       // [rows][q_dim]
-  float *proj = nullptr;          // [chunks][rows][max(d, 2*ffn)] projection partial sums
+  // activations / workspaces (device, fp32 unless noted); ws_rows = rows one pass may carry
+  int ws_rows = 16;
+  float *xn = nullptr;            // [ws_rows][d] normed layer input
+  float *resid = nullptr;         // [ws_rows][d] raw input rows of the query positions
+  float *qkv = nullptr;           // [chunks][ws_rows][qkv_dim]
+  void *qrot = nullptr;           // [ws_rows][q_dim] queries after norm + rotary (fp32 or fp16)
+  float *att_part = nullptr;      // [ws_rows*Hq][splits][hd]
+  float *att_ml = nullptr;        // [ws_rows*Hq][splits][2]
+  float *att_out = nullptr;       // [ws_rows][q_dim]
+  float *proj = nullptr;          // projection partial sums, [chunks][ws_rows][N] of the largest
   float *y = nullptr, *yn = nullptr, *hmid = nullptr, *u = nullptr;
-  // bulk K/V build of a long prefix: row blocks of up to bulk_rows rows (0 = 16 rows at a time)
-  int bulk_rows = 0;
-  float *xn_bulk = nullptr;       // [bulk_rows][d]
-  float *kv_bulk = nullptr;       // [chunks][bulk_rows][2*kv_dim]
+  // K/V-only passes (prefix rows that are not query rows): up to kv_rows rows per pass
+  int kv_rows = 16;
+  float *xn_kv = nullptr;         // [kv_rows][d]
+  float *kv_part = nullptr;       // [chunks][kv_rows][2*kv_dim]
   int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // extra k-split per matrix
   int max_rows;                   // max_batch * max_K
-  int max_splits;
-  int max_chunks;
+  int max_splits;                 // key splits the attention workspaces hold per query vector
   // top-k workspace
   uint64_t *topk_cand = nullptr;  // [rows][chunks][DART_MAX_TOPK]
   float *topk_ms = nullptr;       // [rows][chunks][2]
@@ -95,13 +120,13 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 }
 
 // Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_attn_mt, g_attn_chunk;
+extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_attn_mt;
 
 // All launchers only enqueue work on `st` and return the launch status.
 
-hipError_t launch_rmsnorm_gather(int dtype, const void *hidden, const void *mask_emb,
-                                 const void *gain, int n, int pos0, int M, int d, float eps,
-                                 float *xn, float *resid, int resid_row0, hipStream_t st);
+hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
+                                 const void *gain, int d, float eps, float *xn, float *resid,
+                                 hipStream_t st);
 
 hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
@@ -121,12 +146,12 @@ int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may car
 hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
                          int interleaved, float *h, hipStream_t st);
 
-// qkv: [chunks][M][row_stride] projection partials whose column 0 is column col0 of [q | k | v].
-hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chunks,
-                           size_t chunk_stride, int row_stride, int col0, int M, int Kq, int pos0,
-                           hipStream_t st);
+// qkv: [chunks][rows][row_stride] projection partials whose column 0 is column col0 of [q | k | v].
+hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *qkv, int chunks,
+                           size_t chunk_stride, int row_stride, int col0, hipStream_t st);
 
-hipError_t launch_attention(const dart_ctx *c, int seq, int n, int Kq, hipStream_t st);
+// Attention of the B*K query rows of the pass (compact order) over their sequences' K/V.
+hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t st);
 
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st);

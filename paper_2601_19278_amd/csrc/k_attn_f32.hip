@@ -10,17 +10,20 @@
 namespace dart {
 
 // One wavefront per (key split, query vector).  Lane owns dims lane, lane+64.
+// Query vector qv = (b*K + i)*Hq + h: query row i of sequence b (SeqBatch), head h.
 // Partial result: unnormalised sum_j exp(s_j - m) v_j, with m and l = sum_j exp(s_j - m).
 template <int HD>
 __global__ __launch_bounds__(64) void attn_split_f32_kernel(
-    const float *__restrict__ q, const float *__restrict__ kbuf, const float *__restrict__ vbuf,
-    int t_cap, int n, int Hq, int group, int chunk, float scale, int nsplit,
-    float *__restrict__ o_part, float *__restrict__ ml_part) {
+    SeqBatch sb, const float *__restrict__ q, const float *__restrict__ kbuf,
+    const float *__restrict__ vbuf, size_t slot_elems, int t_cap, int Hq, int group, int chunk,
+    float scale, int nsplit, float *__restrict__ o_part, float *__restrict__ ml_part) {
   constexpr int PER = HD / 64;
   const int split = blockIdx.x, qv = blockIdx.y, lane = threadIdx.x;
-  const int i = qv / Hq, h = qv % Hq, g = h / group;
-  const int last = n - 1 + i;                          // last visible key
+  const int row = qv / Hq, h = qv % Hq, g = h / group;
+  const int b = row / sb.K, i = row % sb.K;
+  const int last = sb.n[b] - 1 + i;                    // last visible key
   const int j0 = split * chunk;
+  if (j0 >= sb.n[b] + sb.K - 1) return;                // beyond the sequence: the merge never reads it
   const int j1 = min(j0 + chunk, last + 1);
   float qr[PER], acc[PER];
 #pragma unroll
@@ -29,7 +32,8 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
     acc[p] = 0.f;
   }
   float m = -3.0e38f, l = 0.f;
-  const float *kb = kbuf + (size_t)g * t_cap * HD, *vb = vbuf + (size_t)g * t_cap * HD;
+  const float *kb = kbuf + sb.slot[b] * slot_elems + (size_t)g * t_cap * HD;
+  const float *vb = vbuf + sb.slot[b] * slot_elems + (size_t)g * t_cap * HD;
   for (int j = j0; j < j1; ++j) {
     float s = 0.f;
 #pragma unroll
@@ -51,26 +55,31 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
   }
 }
 
-// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s.  Splits with l == 0 saw no key.
-// One workgroup per query vector, one thread per output dim; the split weights are computed
-// once in parallel and kept in LDS, and the partial rows are then read with independent loads.
+// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s over the splits that hold keys of
+// the query's sequence (ceil((n + K - 1) / chunk) of the nsplit slots).  A split with l == 0
+// saw no visible key.  One workgroup per query vector, one thread per output dim; the split
+// weights are computed once in parallel and kept in LDS, and the partial rows are then read
+// with independent loads.
 constexpr int ATTN_MAX_SPLITS = 256;
 
-__global__ __launch_bounds__(128) void attn_merge_kernel(const float *__restrict__ o_part,
+__global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, int chunk,
+                                                         const float *__restrict__ o_part,
                                                          const float *__restrict__ ml_part,
                                                          int nsplit, int hd,
                                                          float *__restrict__ out) {
   __shared__ float red[16];
   __shared__ float w[ATTN_MAX_SPLITS];
   const int qv = blockIdx.x, t = threadIdx.x;
+  const int b = qv / (Hq * sb.K);
+  const int used = (sb.n[b] + sb.K - 1 + chunk - 1) / chunk;    // splits of this sequence
   float mx = -3.0e38f;
-  for (int s = t; s < nsplit; s += blockDim.x) {
+  for (int s = t; s < used; s += blockDim.x) {
     const size_t slot = (size_t)qv * nsplit + s;
     if (ml_part[slot * 2 + 1] > 0.f) mx = fmaxf(mx, ml_part[slot * 2]);
   }
   mx = block_max(mx, red);
   float den = 0.f;
-  for (int s = t; s < nsplit; s += blockDim.x) {
+  for (int s = t; s < used; s += blockDim.x) {
     const size_t slot = (size_t)qv * nsplit + s;
     const float l = ml_part[slot * 2 + 1];
     const float ws = l > 0.f ? expf(ml_part[slot * 2] - mx) : 0.f;
@@ -82,7 +91,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float *__restrict
   const float *src = o_part + (size_t)qv * nsplit * hd + t;
   float num = 0.f;
   int s = 0;
-  for (; s + 4 <= nsplit; s += 4) {
+  for (; s + 4 <= used; s += 4) {
     const float a0 = src[(size_t)s * hd], a1 = src[(size_t)(s + 1) * hd];
     const float a2 = src[(size_t)(s + 2) * hd], a3 = src[(size_t)(s + 3) * hd];
     num += w[s] * a0;                 // fixed order: deterministic
@@ -90,42 +99,43 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float *__restrict
     num += w[s + 2] * a2;
     num += w[s + 3] * a3;
   }
-  for (; s < nsplit; ++s) num += w[s] * src[(size_t)s * hd];
+  for (; s < used; ++s) num += w[s] * src[(size_t)s * hd];
   out[(size_t)qv * hd + t] = num / den;
 }
 
-hipError_t launch_attention_bf16(const dart_ctx *c, int seq, int n, int Kq, int *nsplit_out,
+hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, int chunk, int nsplit,
                                  hipStream_t st);
 
-hipError_t launch_attention(const dart_ctx *c, int seq, int n, int Kq, hipStream_t st) {
+hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
-  const int T = n + Kq - 1;
-  int nsplit = 1;
+  int n_max = 0;
+  for (int b = 0; b < sb.B; ++b) n_max = max(n_max, sb.n[b]);
+  const int chunk = ATTN_KEY_CHUNK;                      // keys per workgroup
+  const int nsplit = (n_max + sb.K - 1 + chunk - 1) / chunk;
+  const size_t slot_elems = (size_t)Hkv * c->t_cap * hd;
+  const int QVT = sb.B * sb.K * Hq;                      // query vectors of the pass
   if (g.dtype == DART_BF16) {
-    hipError_t e = launch_attention_bf16(c, seq, n, Kq, &nsplit, st);
+    hipError_t e = launch_attention_bf16(c, sb, chunk, nsplit, st);
     if (e != hipSuccess) return e;
   } else {
-    const int chunk = 128;
-    nsplit = (T + chunk - 1) / chunk;
     const float scale = 1.0f / sqrtf((float)hd);
-    const size_t seq_elems = (size_t)Hkv * c->t_cap * hd;
-    const float *kb = (const float *)c->kbuf + seq * seq_elems;
-    const float *vb = (const float *)c->vbuf + seq * seq_elems;
-    dim3 grid(nsplit, Kq * Hq);
+    dim3 grid(nsplit, QVT);
     if (hd == 64)
-      hipLaunchKernelGGL(attn_split_f32_kernel<64>, grid, dim3(64), 0, st, (const float *)c->qrot,
-                         kb, vb, c->t_cap, n, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
+      hipLaunchKernelGGL(attn_split_f32_kernel<64>, grid, dim3(64), 0, st, sb,
+                         (const float *)c->qrot, (const float *)c->kbuf, (const float *)c->vbuf,
+                         slot_elems, c->t_cap, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
                          c->att_ml);
     else
-      hipLaunchKernelGGL(attn_split_f32_kernel<128>, grid, dim3(64), 0, st, (const float *)c->qrot,
-                         kb, vb, c->t_cap, n, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
+      hipLaunchKernelGGL(attn_split_f32_kernel<128>, grid, dim3(64), 0, st, sb,
+                         (const float *)c->qrot, (const float *)c->kbuf, (const float *)c->vbuf,
+                         slot_elems, c->t_cap, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
                          c->att_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(Kq * Hq), dim3(hd), 0, st, c->att_part, c->att_ml,
-                     nsplit, hd, c->att_out);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, Hq, chunk, c->att_part,
+                     c->att_ml, nsplit, hd, c->att_out);
   return hipGetLastError();
 }
 

@@ -19,7 +19,7 @@
 // is taken as (lane group, e) <-> key 16*(e/4) + 4*(l/16) + e%4 -- V^T is loaded with the
 // same index map, so probabilities never leave registers.
 //
-// Work split: grid (key split, K/V head, query-tile group), 4 wavefronts per workgroup.
+// Work split: grid (key split, K/V head, sequence x query-tile group), 4 wavefronts per workgroup.
 // Every wavefront walks all keys of the split and computes the (cheap) scores and soft-max
 // statistics redundantly; wavefront w accumulates only output dims [HD/4*w, HD/4*(w+1)).
 // No LDS, no cross-wave merge; split partials are merged by attn_merge_kernel.
@@ -37,19 +37,23 @@ union F16x8 {
 
 template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_split_mfma_kernel(
-    const f16_t *__restrict__ q,      // [Kq][Hq][HD]
-    const f16_t *__restrict__ kbuf,   // [Hkv][t_cap][HD]
-    const f16_t *__restrict__ vtbuf,  // [Hkv][HD][t_cap]
-    int t_cap, int n, int Kq, int Hq, int group, int chunk, float scale, int nsplit,
-    float *__restrict__ o_part, float *__restrict__ ml_part) {
+    SeqBatch sb,
+    const f16_t *__restrict__ q,      // [B*K][Hq][HD], query rows in compact order
+    const f16_t *__restrict__ kbuf,   // [slot][Hkv][t_cap][HD]
+    const f16_t *__restrict__ vtbuf,  // [slot][Hkv][HD][t_cap]
+    size_t slot_elems, int t_cap, int zgroups, int Hq, int group, int chunk, float scale,
+    int nsplit, float *__restrict__ o_part, float *__restrict__ ml_part) {
   constexpr int KS = HD / 32;        // k-steps of the score product
   constexpr int DTW = HD / 64;       // output dim tiles per wavefront
-  const int split = blockIdx.x, g = blockIdx.y, a0 = blockIdx.z * MT;
+  const int split = blockIdx.x, g = blockIdx.y;
+  const int b = blockIdx.z / zgroups, a0 = (blockIdx.z % zgroups) * MT;
+  const int Kq = sb.K, n = sb.n[b];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, gq = lane >> 4;
   const int QV = Kq * group;
   const int T = n + Kq - 1;
   const int j_begin = split * chunk;
+  if (j_begin >= T) return;                              // the merge never reads this split
   const int j_end = min(j_begin + chunk, T);
 
   // B operands of the score product: this lane's query column, all k-steps, MT tiles
@@ -62,7 +66,7 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(
     const bool ok = ql < QV;
     const int i = ok ? ql / group : 0, hg = ok ? ql % group : 0;
     qrow[a] = ok ? i : -1;
-    qslot[a] = (size_t)i * Hq + (size_t)g * group + hg;
+    qslot[a] = (size_t)(b * Kq + i) * Hq + (size_t)g * group + hg;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (ok)
@@ -82,8 +86,8 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(
     for (int t = 0; t < DTW; ++t) acc[a][t] = {0.f, 0.f, 0.f, 0.f};
   }
 
-  const f16_t *kb = kbuf + (size_t)g * t_cap * HD;
-  const f16_t *vt = vtbuf + (size_t)g * HD * t_cap;
+  const f16_t *kb = kbuf + sb.slot[b] * slot_elems + (size_t)g * t_cap * HD;
+  const f16_t *vt = vtbuf + sb.slot[b] * slot_elems + (size_t)g * HD * t_cap;
 
   // A operands of one 32-key block: two 16-key tiles of K, and this wavefront's V^T dim tiles
   struct Block {
@@ -179,41 +183,35 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(
 }
 
 template <int HD, int MT>
-static hipError_t launch_one(const dart_ctx *c, int seq, int n, int Kq, int chunk, int nsplit,
+static hipError_t launch_one(const dart_ctx *c, const SeqBatch &sb, int chunk, int nsplit,
                              int zgroups, hipStream_t st) {
   const dart_config &g = c->cfg;
-  const size_t seq_elems = (size_t)g.n_kv_heads * c->t_cap * HD;
-  const f16_t *kb = (const f16_t *)c->kbuf + seq * seq_elems;
-  const f16_t *vt = (const f16_t *)c->vbuf + seq * seq_elems;
-  hipLaunchKernelGGL((attn_split_mfma_kernel<HD, MT>), dim3(nsplit, g.n_kv_heads, zgroups),
-                     dim3(256), 0, st, (const f16_t *)c->qrot, kb, vt, c->t_cap, n, Kq,
-                     g.n_q_heads, g.n_q_heads / g.n_kv_heads, chunk, 1.0f / sqrtf((float)HD), nsplit,
-                     c->att_part, c->att_ml);
+  const size_t slot_elems = (size_t)g.n_kv_heads * c->t_cap * HD;
+  hipLaunchKernelGGL((attn_split_mfma_kernel<HD, MT>),
+                     dim3(nsplit, g.n_kv_heads, zgroups * sb.B), dim3(256), 0, st, sb,
+                     (const f16_t *)c->qrot, (const f16_t *)c->kbuf, (const f16_t *)c->vbuf,
+                     slot_elems, c->t_cap, zgroups, g.n_q_heads, g.n_q_heads / g.n_kv_heads, chunk,
+                     1.0f / sqrtf((float)HD), nsplit, c->att_part, c->att_ml);
   return hipGetLastError();
 }
 
 int g_attn_mt = 3;        // query tiles per workgroup (tunable)
-int g_attn_chunk = 128;   // keys per workgroup, multiple of 32 (tunable)
 
-hipError_t launch_attention_bf16(const dart_ctx *c, int seq, int n, int Kq, int *nsplit_out,
+hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, int chunk, int nsplit,
                                  hipStream_t st) {
   const dart_config &g = c->cfg;
-  const int T = n + Kq - 1;
-  const int chunk = g_attn_chunk;
-  const int nsplit = (T + chunk - 1) / chunk;
-  *nsplit_out = nsplit;
-  const int QV = Kq * (g.n_q_heads / g.n_kv_heads);
+  const int QV = sb.K * (g.n_q_heads / g.n_kv_heads);
   const int tiles = (QV + 15) / 16;
   const int MT = tiles >= g_attn_mt ? g_attn_mt : tiles;   // query tiles per workgroup
   const int zgroups = (tiles + MT - 1) / MT;
   if (g.head_dim == 128) {
-    if (MT == 1) return launch_one<128, 1>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
-    if (MT == 2) return launch_one<128, 2>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
-    return launch_one<128, 3>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+    if (MT == 1) return launch_one<128, 1>(c, sb, chunk, nsplit, zgroups, st);
+    if (MT == 2) return launch_one<128, 2>(c, sb, chunk, nsplit, zgroups, st);
+    return launch_one<128, 3>(c, sb, chunk, nsplit, zgroups, st);
   }
-  if (MT == 1) return launch_one<64, 1>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
-  if (MT == 2) return launch_one<64, 2>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
-  return launch_one<64, 3>(c, seq, n, Kq, chunk, nsplit, zgroups, st);
+  if (MT == 1) return launch_one<64, 1>(c, sb, chunk, nsplit, zgroups, st);
+  if (MT == 2) return launch_one<64, 2>(c, sb, chunk, nsplit, zgroups, st);
+  return launch_one<64, 3>(c, sb, chunk, nsplit, zgroups, st);
 }
 
 }  // namespace dart

@@ -27,19 +27,22 @@ __device__ __forceinline__ void store8(float *p, const float *v) {
   *reinterpret_cast<float4 *>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
 }
 
-// Row i of the layer input is position pos0+i of [z_1..z_n, MASK x (K-1)] (Sec. 3.2):
-// a prefix row of `hidden` when pos < n, else mask embedding pos-n.  Writes the RMS-normed
-// row (times gain) to xn[i] and, for rows >= resid_row0, the raw row to resid.
+// Row r of the pass is position pos of sequence b of [z_1..z_n, MASK x (K-1)] (Sec. 3.2): a
+// prefix row of that sequence's `hidden` when pos < n, else mask embedding pos-n.  Writes the
+// RMS-normed row (times gain) to xn[r] and, for query rows, the raw row to resid[b*K + j].
 // One workgroup per row; the row stays in registers between the two passes, and all loads
 // of a pass are issued before the first use (the kernel is pure latency otherwise).
 template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
-    const T *__restrict__ hidden, const T *__restrict__ mask_emb, const T *__restrict__ gain, int n,
-    int pos0, int d, float eps, float *__restrict__ xn, float *__restrict__ resid, int resid_row0) {
+    SeqBatch sb, const T *__restrict__ mask_emb, const T *__restrict__ gain, int d, float eps,
+    float *__restrict__ xn, float *__restrict__ resid) {
   __shared__ float red[16];
   const int i = blockIdx.x;
-  const int pos = pos0 + i;
-  const T *src = pos < n ? hidden + (size_t)pos * d : mask_emb + (size_t)(pos - n) * d;
+  int b, pos, qi;
+  seq_of_row(sb, i, b, pos, qi);
+  const int n = sb.n[b];
+  const T *src = pos < n ? (const T *)sb.hidden[b] + (size_t)pos * d
+                         : mask_emb + (size_t)(pos - n) * d;
   float v[ROW_MAXIT][8], g[ROW_MAXIT][8];
 #pragma unroll
   for (int j = 0; j < ROW_MAXIT; ++j) {
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
   for (int j = 0; j < ROW_MAXIT; ++j) {
     const int c = (j * ROW_THREADS + threadIdx.x) * 8;
     if (c < d) {
-      if (i >= resid_row0) store8(resid + (size_t)(i - resid_row0) * d + c, v[j]);
+      if (qi >= 0) store8(resid + (size_t)(b * sb.K + qi) * d + c, v[j]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
       store8(xn + (size_t)i * d + c, v[j]);
@@ -146,17 +149,16 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ g
   h[(size_t)r * ffn + f] = g / (1.0f + expf(-g)) * u;
 }
 
-hipError_t launch_rmsnorm_gather(int dtype, const void *hidden, const void *mask_emb,
-                                 const void *gain, int n, int pos0, int M, int d, float eps,
-                                 float *xn, float *resid, int resid_row0, hipStream_t st) {
+hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
+                                 const void *gain, int d, float eps, float *xn, float *resid,
+                                 hipStream_t st) {
+  const int M = sb.row_off[sb.B];
   if (dtype == DART_BF16)
-    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st,
-                       (const bf16_t *)hidden, (const bf16_t *)mask_emb, (const bf16_t *)gain, n,
-                       pos0, d, eps, xn, resid, resid_row0);
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, sb,
+                       (const bf16_t *)mask_emb, (const bf16_t *)gain, d, eps, xn, resid);
   else
-    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st,
-                       (const float *)hidden, (const float *)mask_emb, (const float *)gain, n, pos0,
-                       d, eps, xn, resid, resid_row0);
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st, sb,
+                       (const float *)mask_emb, (const float *)gain, d, eps, xn, resid);
   return hipGetLastError();
 }
 

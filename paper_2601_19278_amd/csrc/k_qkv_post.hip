@@ -7,23 +7,26 @@
 
 namespace dart {
 
-// grid (M rows, Hq + 2*Hkv heads), block = head_dim threads.
-// Row i sits at absolute position pos0+i; the last Kq rows are the query rows.
+// grid (pass rows, Hq + 2*Hkv heads), block = head_dim threads.
+// Pass row i is position pos of sequence b (SeqBatch); q is produced for query rows only and
+// stored at the compact index b*K + j; k and v of every row go to the sequence's K/V slot.
 // T: storage type of the norm gains; CT: element type of q and of the K/V buffers.
 template <typename T, typename CT>
 __global__ __launch_bounds__(128) void qkv_post_kernel(
-    const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride, int col0, int M,
-    int Kq,
-    int pos0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
+    SeqBatch sb, const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride,
+    int col0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
     const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
     const float *__restrict__ sin_tab, CT *__restrict__ q_out, CT *__restrict__ kbuf,
-    CT *__restrict__ vbuf, int t_cap, int v_transposed) {
+    CT *__restrict__ vbuf, size_t slot_elems, int t_cap, int v_transposed) {
   __shared__ float red[16];
   __shared__ float sh[128];
   const int i = blockIdx.x, hh = blockIdx.y, t = threadIdx.x;
-  const int pos = pos0 + i;
+  int b, pos, qi;
+  seq_of_row(sb, i, b, pos, qi);
   const bool is_q = hh < Hq, is_k = !is_q && hh < Hq + Hkv;
-  if (is_q && i < M - Kq) return;                 // non-query rows need no q (uniform per block)
+  if (is_q && qi < 0) return;                     // non-query rows need no q (uniform per block)
+  kbuf += (size_t)sb.slot[b] * slot_elems;
+  vbuf += (size_t)sb.slot[b] * slot_elems;
   const int col = hh * hd + t - col0;             // q heads, then k heads, then v heads
   float x = 0.f;
   for (int c = 0; c < chunks; ++c) x += qkv[c * chunk_stride + (size_t)i * row_stride + col];
@@ -47,33 +50,29 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
   const float c = cos_tab[(size_t)pos * half + fi], s = sin_tab[(size_t)pos * half + fi];
   const float y = t < half ? x * c - sh[t + half] * s : x * c + sh[t - half] * s;
   if (is_q) {
-    const int qi = i - (M - Kq);
-    q_out[((size_t)qi * Hq + hh) * hd + t] = from_f32<CT>(y);
+    q_out[((size_t)(b * sb.K + qi) * Hq + hh) * hd + t] = from_f32<CT>(y);
   } else {
     const int g = hh - Hq;
     kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(y);
   }
 }
 
-hipError_t launch_qkv_post(const dart_ctx *c, int seq, const float *qkv, int chunks,
-                           size_t chunk_stride, int row_stride, int col0, int M, int Kq, int pos0,
-                           hipStream_t st) {
+hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *qkv, int chunks,
+                           size_t chunk_stride, int row_stride, int col0, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
-  const size_t seq_elems = (size_t)Hkv * c->t_cap * hd;
-  dim3 grid(M, Hq + 2 * Hkv), block(hd);
+  const size_t slot_elems = (size_t)Hkv * c->t_cap * hd;
+  dim3 grid(sb.row_off[sb.B], Hq + 2 * Hkv), block(hd);
   if (g.dtype == DART_BF16) {
-    f16_t *kb = (f16_t *)c->kbuf + seq * seq_elems, *vb = (f16_t *)c->vbuf + seq * seq_elems;
-    hipLaunchKernelGGL((qkv_post_kernel<bf16_t, f16_t>), grid, block, 0, st, qkv, chunks,
-                       chunk_stride, row_stride, col0, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
+    hipLaunchKernelGGL((qkv_post_kernel<bf16_t, f16_t>), grid, block, 0, st, sb, qkv, chunks,
+                       chunk_stride, row_stride, col0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
                        (const bf16_t *)c->g_q, (const bf16_t *)c->g_k, c->rope_cos, c->rope_sin,
-                       (f16_t *)c->qrot, kb, vb, c->t_cap, 1);
+                       (f16_t *)c->qrot, (f16_t *)c->kbuf, (f16_t *)c->vbuf, slot_elems, c->t_cap, 1);
   } else {
-    float *kb = (float *)c->kbuf + seq * seq_elems, *vb = (float *)c->vbuf + seq * seq_elems;
-    hipLaunchKernelGGL((qkv_post_kernel<float, float>), grid, block, 0, st, qkv, chunks,
-                       chunk_stride, row_stride, col0, M, Kq, pos0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
+    hipLaunchKernelGGL((qkv_post_kernel<float, float>), grid, block, 0, st, sb, qkv, chunks,
+                       chunk_stride, row_stride, col0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
                        (const float *)c->g_q, (const float *)c->g_k, c->rope_cos, c->rope_sin,
-                       (float *)c->qrot, kb, vb, c->t_cap, 0);
+                       (float *)c->qrot, (float *)c->kbuf, (float *)c->vbuf, slot_elems, c->t_cap, 0);
   }
   return hipGetLastError();
 }
