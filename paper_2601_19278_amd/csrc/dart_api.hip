@@ -180,6 +180,17 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     ch_down = gemv_bf16_chunks(F) * c->split_down;
     if (g.max_ctx > R && gemv_bf16_row_tiles(d, c->split_qkv) >= 4)
       c->kv_rows = std::min(1024, round_up(g.max_ctx, 64));
+    if (g.max_batch > 1) {     // the batched entry point runs on the multi-row kernel
+      c->gch_qkv = gemm_bf16_chunks(d, c->qkv_dim / 16);
+      c->gch_o = gemm_bf16_chunks(c->q_dim, (d + 15) / 16);
+      c->gch_gu = gemm_bf16_chunks(d, 2 * F / 16);
+      c->gch_down = gemm_bf16_chunks(F, (d + 15) / 16);
+      ch_qkv = std::max(ch_qkv, c->gch_qkv);
+      ch_o = std::max(ch_o, c->gch_o);
+      ch_gu = std::max(ch_gu, c->gch_gu);
+      ch_down = std::max(ch_down, c->gch_down);
+      c->kv_rows = std::max(c->kv_rows, std::min(1024, round_up(g.max_ctx, 64)));
+    }
   }
   // one pass carries the query rows of up to DART_SEQ_GROUP sequences
   c->ws_rows = std::max(R, std::min(g.max_batch, DART_SEQ_GROUP) * g.max_K);
@@ -218,10 +229,16 @@ dart_status from_hip(hipError_t e) {
 // out[chunk][m][j] with row stride out_stride and chunk stride chunk_stride.
 // split: extra k-split of the matrix (fixed per matrix at create time so that every call cuts
 // k the same way; 1 where the output must be complete in one chunk).
+// gch > 0: take the multi-row kernel with gch k-chunks (the batched entry point).
 hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows, const float *X,
-                   int M, float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
-                   hipStream_t st) {
+                   int M, float *out, int out_stride, size_t chunk_stride, int split, int gch,
+                   int *chunks, hipStream_t st) {
   const int R = DART_SKINNY_ROWS;
+  if (c->cfg.dtype == DART_BF16 && gch > 0) {
+    *chunks = gch;
+    return launch_gemm_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride, gch,
+                            0, st);
+  }
   if (c->cfg.dtype == DART_BF16) {
     if (M <= R || gemv_bf16_row_tiles(W.Kd, split) >= 2)
       return launch_gemv_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride,
@@ -248,7 +265,7 @@ struct SeqJob {
 
 // K/V-only pass: norm + K and V projection + append for the rows described by sb (sb.K = 0,
 // at most kv_rows rows).
-hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
+hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int M = sb.row_off[sb.B];
   HIP_TRY(launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, c->xn_kv,
@@ -256,23 +273,27 @@ hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
   const size_t cs = (size_t)c->kv_rows * 2 * c->kv_dim;
   int chunks = 1;
   HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn_kv, M, c->kv_part, 2 * c->kv_dim, cs,
-                  c->split_qkv, &chunks, st));
+                  c->split_qkv, gemm ? c->gch_qkv : 0, &chunks, st));
   return launch_qkv_post(c, sb, c->kv_part, chunks, cs, 2 * c->kv_dim, c->q_dim, st);
 }
 
 // Draft forward of up to DART_SEQ_GROUP sequences; logits [B][K][vocab].
-hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, float *logits,
+// gemm: every projection runs on the multi-row kernel (the batched entry point on bf16
+// weights).  The two kernels add a row's products in different orders, so a K/V slot filled
+// through one entry point is reused by the other only to rounding, not bit for bit.
+hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gemm, float *logits,
                          hipStream_t st) {
   const dart_config &g = c->cfg;
   const int R = DART_SKINNY_ROWS;
+  gemm = gemm && g.dtype == DART_BF16;
   // A single sequence with few new rows takes one pass for all of them; otherwise the prefix
   // rows that are not query rows go through K/V-only passes first.
-  const bool combined = B == 1 && (jobs[0].n - jobs[0].n_cached) + K - 1 <= R;
+  const bool combined = !gemm && B == 1 && (jobs[0].n - jobs[0].n_cached) + K - 1 <= R;
   if (!combined) {
     SeqBatch sb{};
     auto flush = [&]() -> hipError_t {
       if (sb.B == 0) return hipSuccess;
-      hipError_t e = kv_pass(c, sb, st);
+      hipError_t e = kv_pass(c, sb, gemm, st);
       sb = SeqBatch{};
       return e;
     };
@@ -310,24 +331,30 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, float *l
                                 st));
   int chunks = 1;
   size_t cs = W * c->qkv_dim;
-  HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv, &chunks,
-                  st));
+  HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv,
+                  gemm ? c->gch_qkv : 0, &chunks, st));
   HIP_TRY(launch_qkv_post(c, sb, c->qkv, chunks, cs, c->qkv_dim, 0, st));
   HIP_TRY(launch_attention(c, sb, st));
 
   cs = W * g.d;
-  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, QR, c->proj, g.d, cs, c->split_o, &chunks, st));
+  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, QR, c->proj, g.d, cs, c->split_o,
+                  gemm ? c->gch_o : 0, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, QR, g.d,
                             g.rms_eps, c->y, c->yn, st));
   cs = W * 2 * g.ffn;
-  HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, QR, c->proj, 2 * g.ffn, cs, c->split_gu, &chunks,
-                  st));
-  HIP_TRY(launch_swiglu(c->proj, chunks, cs, QR, g.ffn, g.dtype == DART_BF16, c->hmid, st));
+  if (gemm && c->gch_gu == 1) {     // SwiGLU in the projection's epilogue
+    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, c->yn, QR, c->hmid, g.ffn, 0, 1, 1, st));
+  } else {
+    HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, QR, c->proj, 2 * g.ffn, cs, c->split_gu,
+                    gemm ? c->gch_gu : 0, &chunks, st));
+    HIP_TRY(launch_swiglu(c->proj, chunks, cs, QR, g.ffn, g.dtype == DART_BF16, c->hmid, st));
+  }
   cs = W * g.d;
-  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down, &chunks, st));
+  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down,
+                  gemm ? c->gch_down : 0, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
                             c->u, c->yn, st));
-  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, QR, logits, g.vocab, 0, 1, &chunks, st));
+  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
   return hipSuccess;
 }
 
@@ -430,7 +457,7 @@ dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx
   if (s != DART_OK) return s;
   const SeqJob job{seq, hidden, ctx_len, n_cached};
   c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
-  hipError_t e = forward_group(c, 1, &job, K, logits_out, (hipStream_t)stream);
+  hipError_t e = forward_group(c, 1, &job, K, false, logits_out, (hipStream_t)stream);
   if (e != hipSuccess) return from_hip(e);
   c->cached_rows[seq] = ctx_len;
   return DART_OK;
@@ -452,7 +479,7 @@ dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const
       jobs[i] = SeqJob{b0 + i, hidden[b0 + i], ctx_len[b0 + i], n_cached[b0 + i]};
       c->cached_rows[b0 + i] = 0;
     }
-    hipError_t e = forward_group(c, nb, jobs, K, logits_out + (size_t)b0 * K * c->cfg.vocab,
+    hipError_t e = forward_group(c, nb, jobs, K, true, logits_out + (size_t)b0 * K * c->cfg.vocab,
                                  (hipStream_t)stream);
     if (e != hipSuccess) return from_hip(e);
     for (int i = 0; i < nb; ++i) c->cached_rows[b0 + i] = ctx_len[b0 + i];
@@ -571,6 +598,7 @@ int dart_debug_set(const char *name, int value) {
   else if (!strcmp(name, "gemv_depth")) g_gemv_depth = value;
   else if (!strcmp(name, "gemv_nt")) g_gemv_nt = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
+  else if (!strcmp(name, "gemm_wgs")) g_gemm_wgs = value < 1 ? 1 : value;
   else if (!strcmp(name, "attn_mt")) g_attn_mt = value < 1 ? 1 : (value > 3 ? 3 : value);
   else return -1;
   return 0;
@@ -581,8 +609,8 @@ int dart_debug_set(const char *name, int value) {
 dart_status dart_debug_lm_head(dart_ctx *c, int K, float *logits_out, void *stream) {
   if (!c || !logits_out || K < 1 || K > c->cfg.max_K) return DART_ERR_ARG;
   int chunks = 1;
-  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, 1, &chunks,
-                          (hipStream_t)stream));
+  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, 1, 0,
+                          &chunks, (hipStream_t)stream));
 }
 
 // Diagnostic: copy a named fp32 workspace of the last forward to host memory (synchronises).

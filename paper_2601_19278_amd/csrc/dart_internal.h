@@ -99,6 +99,7 @@ struct dart_ctx {
   float *xn_kv = nullptr;         // [kv_rows][d]
   float *kv_part = nullptr;       // [chunks][kv_rows][2*kv_dim]
   int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // extra k-split per matrix
+  int gch_qkv = 1, gch_o = 1, gch_gu = 1, gch_down = 1;           // k-chunks on the multi-row path
   int max_rows;                   // max_batch * max_K
   int max_splits;                 // key splits the attention workspaces hold per query vector
   // top-k workspace
@@ -120,7 +121,7 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 }
 
 // Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_attn_mt;
+extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_attn_mt, g_gemm_wgs;
 
 // All launchers only enqueue work on `st` and return the launch status.
 
@@ -142,6 +143,18 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
 int gemv_bf16_split(int Kd, int nstrips);     // extra k-split that balances the workgroups
 int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may carry per row block
+
+// bf16 multi-row GEMM on packed weights (any M); nchunks is fixed per matrix, see gemm_bf16_chunks.
+// epi 1: the strips are interleaved gate/up rows and out receives silu(gate) * up, [M][out_stride].
+hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
+                            float *out, int out_stride, size_t chunk_stride, int nchunks, int epi,
+                            hipStream_t st);
+int gemm_bf16_chunks(int Kd, int nstrips);
+
+// First k-step of k-chunk c when KT k-steps are cut into nchunks (multiples of 4 k-steps).
+__host__ __device__ inline int gemm_chunk_begin(int KT, int nchunks, int c) {
+  return c >= nchunks ? KT : (int)((int64_t)KT * c / nchunks) / 4 * 4;
+}
 
 hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
                          int interleaved, float *h, hipStream_t st);

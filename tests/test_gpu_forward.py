@@ -129,6 +129,39 @@ def test_batched_ragged_sequences():
     ctx.close()
 
 
+@pytest.mark.parametrize("batch,K,over", [
+    (6, 8, dict(d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1536, vocab=8200, ctx=150)),
+    (16, 8, dict(d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=5632, vocab=1000, ctx=120)),
+    (2, 3, dict(d=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1024, vocab=40000, ctx=70,
+                qk_norm=False)),
+    (20, 2, dict(d=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=512, vocab=2048, ctx=40)),
+])
+def test_batched_multi_row_kernel_matches_oracle_cold_and_warm(batch, K, over):
+    """The batched entry point runs every projection on the multi-row MFMA kernel: 48 and 128
+    row passes, ragged vocab / strip tails, k-chunked matrices, more sequences than one pass
+    holds; a warm call (cached prefix) reproduces the cold call bit for bit."""
+    cfg = ds.scaled_config("C2", K=K, batch=batch, **over)
+    ctx, W = make_context(cfg, 2500)
+    rng = np.random.default_rng(2500 + batch)
+    lens = [int(v) for v in rng.integers(5, cfg.ctx + 1, size=batch)]
+    lens[0] = cfg.ctx
+    hiddens = [ds.make_hidden(cfg, 2501 + b, n=lens[b]) for b in range(batch)]
+    devs = [hidden_to_device(cfg, h) for h in hiddens]
+    cold = ctx.draft_forward_batched(devs, lens, [0] * batch, K).cpu().numpy()
+    for b in range(batch):
+        ref = odf.draft_forward(cfg, W, hiddens[b], K)
+        ok, msg = logits_close(cold[b], ref, **BF16_TOL)
+        assert ok, (b, lens[b], msg)
+    # shorter prefixes first, then the full ones with those rows cached
+    part = [max(1, n - 1 - (b % 4)) for b, n in enumerate(lens)]
+    for b in range(batch):
+        ctx.reset(b)
+    ctx.draft_forward_batched(devs, part, [0] * batch, K)
+    warm = ctx.draft_forward_batched(devs, lens, part, K).cpu().numpy()
+    np.testing.assert_array_equal(warm, cold)
+    ctx.close()
+
+
 def test_error_statuses():
     import torch
     import paper_2601_19278_amd as dart
