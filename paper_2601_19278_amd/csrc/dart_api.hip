@@ -210,6 +210,11 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   HIP_TRY(dev_alloc(&c->yn, W * d));
   HIP_TRY(dev_alloc(&c->hmid, W * F));
   HIP_TRY(dev_alloc(&c->u, W * d));
+  if (g.dtype == DART_BF16) {
+    size_t pb = gemm_bf16_pack_bytes(c->kv_rows, d);
+    for (int kd : {d, c->q_dim, F}) pb = std::max(pb, gemm_bf16_pack_bytes(c->ws_rows, kd));
+    HIP_TRY(hipMalloc(&c->xpack, pb));
+  }
   HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * d));
   HIP_TRY(dev_alloc(&c->kv_part, (size_t)ch_qkv * c->kv_rows * 2 * c->kv_dim));
 
@@ -236,8 +241,8 @@ hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows
   const int R = DART_SKINNY_ROWS;
   if (c->cfg.dtype == DART_BF16 && gch > 0) {
     *chunks = gch;
-    return launch_gemm_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, out, out_stride, chunk_stride, gch,
-                            0, st);
+    return launch_gemm_bf16(W, row0 / 16, (nrows + 15) / 16, X, M, c->xpack, out, out_stride,
+                            chunk_stride, gch, 0, st);
   }
   if (c->cfg.dtype == DART_BF16) {
     if (M <= R || gemv_bf16_row_tiles(W.Kd, split) >= 2)
@@ -343,7 +348,8 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
                             g.rms_eps, c->y, c->yn, st));
   cs = W * 2 * g.ffn;
   if (gemm && c->gch_gu == 1) {     // SwiGLU in the projection's epilogue
-    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, c->yn, QR, c->hmid, g.ffn, 0, 1, 1, st));
+    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, c->yn, QR, c->xpack, c->hmid, g.ffn, 0, 1, 1,
+                             st));
   } else {
     HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, QR, c->proj, 2 * g.ffn, cs, c->split_gu,
                     gemm ? c->gch_gu : 0, &chunks, st));
@@ -438,7 +444,7 @@ void dart_destroy(dart_ctx *c) {
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
-                  c->xn_kv, c->kv_part};
+                  c->xn_kv, c->kv_part, c->xpack};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
   free(c->cached_rows);

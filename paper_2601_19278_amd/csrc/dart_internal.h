@@ -100,6 +100,7 @@ struct dart_ctx {
   float *kv_part = nullptr;       // [chunks][kv_rows][2*kv_dim]
   int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // extra k-split per matrix
   int gch_qkv = 1, gch_o = 1, gch_gu = 1, gch_down = 1;           // k-chunks on the multi-row path
+  void *xpack = nullptr;          // activations of one multi-row projection in MFMA operand order
   int max_rows;                   // max_batch * max_K
   int max_splits;                 // key splits the attention workspaces hold per query vector
   // top-k workspace
@@ -146,10 +147,12 @@ int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may car
 
 // bf16 multi-row GEMM on packed weights (any M); nchunks is fixed per matrix, see gemm_bf16_chunks.
 // epi 1: the strips are interleaved gate/up rows and out receives silu(gate) * up, [M][out_stride].
+// pack: scratch of gemm_bf16_pack_bytes(M, W.Kd) bytes for the activations in operand order.
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
-                            float *out, int out_stride, size_t chunk_stride, int nchunks, int epi,
-                            hipStream_t st);
+                            void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
+                            int epi, hipStream_t st);
 int gemm_bf16_chunks(int Kd, int nstrips);
+size_t gemm_bf16_pack_bytes(int M, int Kd);
 
 // First k-step of k-chunk c when KT k-steps are cut into nchunks (multiples of 4 k-steps).
 __host__ __device__ inline int gemm_chunk_begin(int KT, int nchunks, int c) {

@@ -1,4 +1,4 @@
-// Multi-row projection on bf16 weights: out[m][n] = sum_k X[m][k] W[n][k] for M > 16 rows.
+// Multi-row projection on bf16 weights: out[m][n] = sum_k X[m][k] W[n][k] for many rows.
 //
 // This is the contraction of the batched draft step (e.g. 16 sequences x K = 8 masked
 // positions = 128 rows against the LM head, paper Sec. 3.2) and of the K/V build of many
@@ -9,11 +9,12 @@
 // Roles: weights are the MFMA A operand, read straight from global memory in the packed tile
 // layout (1 KiB per 16 outputs x 32 inputs, already in operand order) -- each tile is used by
 // exactly one wavefront, so staging it in LDS would buy nothing.  Activations are the B
-// operand: a block of up to 128 rows is converted once per workgroup from fp32 to bf16
-// hi + lo parts (x ~= hi + lo to 2^-17, weights stay the exact bf16 values), written to LDS
-// in operand order, and shared by the 4 wavefronts (one per SIMD, so that each can hold
-// 8 strips x 8 row tiles of fp32 accumulators = 256 registers next to its operands), each of
-// which applies it to its own strips of 16 outputs.
+// operand.  pack_rows_kernel converts them once from fp32 to bf16 hi + lo parts
+// (x ~= hi + lo to 2^-17, weights stay the exact bf16 values) in operand order, 1 KiB tiles of
+// 16 rows x 32 inputs; the GEMM workgroup copies the tiles of its row block (up to 128 rows)
+// for two k-steps at a time from global memory straight into LDS (no registers involved) and
+// its 8 wavefronts share them, each applying them to its own strips of 16 outputs.  A
+// wavefront holds up to 4 strips x 8 row tiles of fp32 accumulators.
 //
 // Work units: (row block of 16*NCT rows, contiguous strip range, k-chunk).  Strip ranges are
 // a balanced partition, so a launch with one range per compute unit has no tail; a range
@@ -25,94 +26,130 @@
 
 namespace dart {
 
-constexpr int GEMM_WAVES = 4;       // one wavefront per SIMD: each may use the full 512 registers
+constexpr int GEMM_WAVES = 8;
 constexpr int GEMM_THREADS = GEMM_WAVES * 64;
-constexpr int GEMM_SMAX = 8;        // strips per wavefront per pass
-constexpr int GEMM_KS = 2;          // k-steps (of 32 inputs) per LDS stage
-constexpr int GEMM_PD = 2;          // k-steps of weight tiles in flight per wavefront
-constexpr int GEMM_UNR = 2;         // k-steps per loop body: one LDS stage, one turn of the ring
+constexpr int GEMM_SMAX = 4;        // strips per wavefront per pass
+constexpr int GEMM_KS = 2;          // k-steps (of 32 inputs) per LDS stage = per loop body
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
 
-__device__ __forceinline__ void gemm_lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// One LDS stage: the hi and lo operand tiles of NCT row tiles for GEMM_KS k-steps.
+template <int NCT>
+struct GemmStage {
+  u32x4_t t[GEMM_KS][NCT * 2][64];
+};
+
+// The main loop keeps three kinds of memory traffic in flight at once: weight tiles for the
+// next two k-steps (global -> registers), the next stage of activation tiles (global -> LDS,
+// bypassing registers) and the LDS reads of the current stage.  The compiler cannot tell which
+// LDS stage a global -> LDS copy targets, so with compiler-visible copies it makes the next
+// LDS read wait for every outstanding load, the weight prefetch included.  The loads of the
+// loop are therefore issued from inline assembly and waited for by count: loads complete in
+// issue order, so "at most N outstanding" identifies exactly which ones have landed.
+//
+// load_tile: 16 bytes per lane from base + off, non-temporal (weights are read once).  The
+// destination is a read-write operand so that the value keeps one register from the load to
+// the wait that precedes its first use.
+__device__ __forceinline__ void load_tile_async(u32x4_t &dst, uint32_t off, const u32x4_t *base) {
+  asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "+v"(dst) : "v"(off), "s"(base) : "memory");
+}
+// One wavefront copies 1 KiB from global memory (lane l: 16 bytes at base + off) to LDS (lane
+// l: 16 bytes at lds_base + 16*l); lds_base is wave-uniform.
+__device__ __forceinline__ void copy_tile_to_lds_async(uint32_t lds_base, uint32_t off,
+                                                       const u32x4_t *base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_base), "v"(off), "s"(base)
+               : "memory");
+}
+// Wait until at most N of the loads above are outstanding; the tiles named here are the ones
+// this wait makes valid (the operands tie their first use to the wait).
+template <int N, int SP>
+__device__ __forceinline__ void wait_tiles(u32x4_t (&t)[SP]) {
+  if constexpr (SP == 4)
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]) : "n"(N));
+  else if constexpr (SP == 2)
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(t[0]), "+v"(t[1]) : "n"(N));
+  else
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(t[0]) : "n"(N));
+}
+
+// Packed activations: [k-step][row tile][hi, lo][64 lanes][8 bf16]; lane l of a tile holds
+// inputs 8*(l/16)..+7 of row l%16 (the B operand of v_mfma_f32_16x16x32_bf16).  Row tiles
+// beyond M and, when KT is odd, one extra k-step are zero, so the consumer needs no guards.
+__global__ __launch_bounds__(256) void pack_rows_kernel(const float *__restrict__ X, int M, int Kd,
+                                                        int ntiles, int ksteps,
+                                                        u32x4_t *__restrict__ Xp) {
+  const int item = blockIdx.x * 256 + threadIdx.x;       // (k-step, row tile, lane)
+  const int lane = item & 63, tile = (item >> 6) % ntiles, t = (item >> 6) / ntiles;
+  if (t >= ksteps) return;
+  const int r = tile * 16 + (lane & 15), k = t * 32 + 8 * (lane >> 4);
+  uint32_t h[4] = {0, 0, 0, 0}, l[4] = {0, 0, 0, 0};
+  if (r < M && k < Kd) {
+    const float *src = X + (size_t)r * Kd + k;
+    const float4 a = *reinterpret_cast<const float4 *>(src);
+    const float4 b = *reinterpret_cast<const float4 *>(src + 4);
+    const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bf16_t h0 = f32_to_bf16(x[2 * e]), h1 = f32_to_bf16(x[2 * e + 1]);
+      const bf16_t l0 = f32_to_bf16(x[2 * e] - bf16_to_f32(h0));
+      const bf16_t l1 = f32_to_bf16(x[2 * e + 1] - bf16_to_f32(h1));
+      h[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      l[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+  }
+  u32x4_t *dst = Xp + ((size_t)t * ntiles + tile) * 128 + lane;
+  dst[0] = u32x4_t{h[0], h[1], h[2], h[3]};
+  dst[64] = u32x4_t{l[0], l[1], l[2], l[3]};
 }
 
 struct GemmArgs {
   const u32x4_t *Wp;     // packed weight tiles
-  const float *X;        // [M][Kd]
+  const u32x4_t *Xp;     // packed activations, ntiles row tiles per k-step
   float *out;            // [nchunks][M][out_stride] (EPI 1: [M][out_stride] SwiGLU products)
   size_t chunk_stride;
   int M, KT, nchunks, strip0, nstrips, n_cols, ngroups, out_stride;
-  int row_blocks, units;
+  int row_blocks, units, ntiles;
 };
 
 // EPI 0: store the accumulators.  EPI 1: the strips hold interleaved gate/up features
 // (g f, g f+1, u f, u f+1), one group per lane; store silu(g) * u (needs nchunks == 1).
 template <int NCT, int SP, int EPI>
-__device__ __forceinline__ void gemm_pass(const GemmArgs &a, u32x4_t (*bst)[GEMM_KS][NCT * 2][64],
-                                          int m0, int chunk, int k0, int nk, int sfirst, int ns) {
+__device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0,
+                                          GemmStage<NCT> *st1, int rb, int chunk, int k0, int nk,
+                                          int sfirst, int ns, int wave) {
   const int lane = threadIdx.x & 63;
-  const int Kd = a.KT * 32;
   const int kend = k0 + nk;                               // k-steps [k0, kend) of this chunk
-  const int nkp = (nk + GEMM_UNR - 1) / GEMM_UNR * GEMM_UNR;
+  const int nkp = (nk + GEMM_KS - 1) / GEMM_KS * GEMM_KS;  // an odd tail reads the zero k-step
 
-  // weight tile pointers of this wavefront's strips (absent strips alias the first one: their
-  // products are computed and dropped, which keeps the loop free of branches)
-  // (sfirst and ns are wave-uniform, so these pointers live in scalar registers)
+  // weight tiles of this wavefront's strips (absent strips alias the first one: their
+  // products are computed and dropped, which keeps the loop free of branches); sfirst and ns
+  // are wave-uniform, so the strip bases live in scalar registers and one vector register
+  // holds the byte offset of (k-step, lane) for all of them
   const u32x4_t *wrow[SP];
 #pragma unroll
   for (int s = 0; s < SP; ++s) {
     const int strip = a.strip0 + sfirst + (s < ns ? s : 0);
     wrow[s] = a.Wp + (size_t)strip * a.KT * 64;
   }
-  u32x4_t aop[GEMM_PD][SP];
-#pragma unroll
-  for (int p = 0; p < GEMM_PD; ++p)
-#pragma unroll
-    for (int s = 0; s < SP; ++s)
-      aop[p][s] = __builtin_nontemporal_load(wrow[s] + (size_t)min(k0 + p, kend - 1) * 64 + lane);
+  auto tile_off = [&](int kstep) { return (uint32_t)(min(kstep, kend - 1) * 64 + lane) * 16u; };
 
-  // staging: item i of a stage is (row r, group q of 8 inputs among the stage's 64); lanes
-  // walk r fastest so that the 16-byte LDS writes of a wavefront fall into distinct banks
-  constexpr int ITEMS = NCT * 16 * GEMM_KS * 4;
-  constexpr int IPT = (ITEMS + GEMM_THREADS - 1) / GEMM_THREADS;
-  float4 xr[IPT][2];
-  auto stage_load = [&](int kstage) {                     // first k-step of the stage (relative)
+  // stage copy: the NCT*2 operand tiles of GEMM_KS k-steps, 1 KiB each; wavefront w moves
+  // tiles w, w+8, ...: exactly TPW copies per wavefront and stage
+  constexpr int NT = GEMM_KS * NCT * 2;
+  static_assert(NT % GEMM_WAVES == 0, "every wavefront must issue the same number of copies");
+  constexpr int TPW = NT / GEMM_WAVES;
+  const u32x4_t *xbase = a.Xp + (size_t)rb * NCT * 128;   // uniform
+  const uint32_t xstep = (uint32_t)a.ntiles * 2048u;      // bytes of one k-step
+  auto stage_copy = [&](int kstage, GemmStage<NCT> *dst) {   // kstage: first k-step, absolute
 #pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const int i = threadIdx.x + j * GEMM_THREADS;
-      const int r = (i & 15) + 16 * (i / (16 * GEMM_KS * 4)), q = (i >> 4) & (GEMM_KS * 4 - 1);
-      const int kk = kstage + (q >> 2);
-      xr[j][0] = xr[j][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (i < ITEMS && m0 + r < a.M && kk < nk) {
-        const float *src = a.X + (size_t)(m0 + r) * Kd + (size_t)(k0 + kk) * 32 + 8 * (q & 3);
-        xr[j][0] = *reinterpret_cast<const float4 *>(src);
-        xr[j][1] = *reinterpret_cast<const float4 *>(src + 4);
-      }
-    }
-  };
-  auto stage_store = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const int i = threadIdx.x + j * GEMM_THREADS;
-      if (i < ITEMS) {
-        const int r = (i & 15) + 16 * (i / (16 * GEMM_KS * 4)), q = (i >> 4) & (GEMM_KS * 4 - 1);
-        const float x[8] = {xr[j][0].x, xr[j][0].y, xr[j][0].z, xr[j][0].w,
-                            xr[j][1].x, xr[j][1].y, xr[j][1].z, xr[j][1].w};
-        uint32_t h[4], l[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bf16_t h0 = f32_to_bf16(x[2 * e]), h1 = f32_to_bf16(x[2 * e + 1]);
-          const bf16_t l0 = f32_to_bf16(x[2 * e] - bf16_to_f32(h0));
-          const bf16_t l1 = f32_to_bf16(x[2 * e + 1] - bf16_to_f32(h1));
-          h[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-          l[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-        }
-        const int slot = (q & 3) * 16 + (r & 15), c = r >> 4;
-        bst[buf][q >> 2][2 * c][slot] = u32x4_t{h[0], h[1], h[2], h[3]};
-        bst[buf][q >> 2][2 * c + 1][slot] = u32x4_t{l[0], l[1], l[2], l[3]};
-      }
+    for (int i = 0; i < TPW; ++i) {
+      const int tile = wave + GEMM_WAVES * i;
+      const int u = tile / (NCT * 2), c2 = tile % (NCT * 2);
+      copy_tile_to_lds_async((uint32_t)(uintptr_t)(lptr_t)&dst->t[u][c2][0],
+                             (uint32_t)(kstage + u) * xstep + (uint32_t)(c2 * 64 + lane) * 16u, xbase);
     }
   };
 
@@ -122,46 +159,64 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, u32x4_t (*bst)[GEMM
 #pragma unroll
     for (int c = 0; c < NCT; ++c) acc[s][c] = {0.f, 0.f, 0.f, 0.f};
 
-  stage_load(0);
-  stage_store(0);
-  gemm_lds_barrier();
-
-  for (int t0 = 0; t0 < nkp; t0 += GEMM_UNR) {
+  // prologue: stage 0 and the weight tiles of the first two k-steps
+  u32x4_t aop[GEMM_KS][SP];
+  stage_copy(k0, st0);
 #pragma unroll
-    for (int tu = 0; tu < GEMM_UNR; ++tu) {
-      const int t = t0 + tu;                              // k-step relative to k0
-      const int buf = (t0 / GEMM_KS) & 1, u = tu % GEMM_KS;
-      if (u == 0) stage_load(t + GEMM_KS);                // rows of the next stage, in flight
+  for (int p = 0; p < GEMM_KS; ++p)
+#pragma unroll
+    for (int s = 0; s < SP; ++s) {
+      aop[p][s] = u32x4_t{0, 0, 0, 0};
+      load_tile_async(aop[p][s], tile_off(k0 + p), wrow[s]);
+    }
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
+
+  // One stage: GEMM_KS k-steps out of `cur` while the next stage is copied into `nxt`.
+  // Loads outstanding on entry, oldest first: tiles of k-step 0 (SP), tiles of k-step 1 (SP).
+  auto stage_body = [&](int t0, GemmStage<NCT> *cur, GemmStage<NCT> *nxt) {
+    // next stage (clamped at the end: copied again, never used)
+    stage_copy(min(k0 + t0 + GEMM_KS, k0 + nkp - GEMM_KS), nxt);
+#pragma unroll
+    for (int u = 0; u < GEMM_KS; ++u) {
+      // younger than the tiles of this k-step: the other k-step's tiles and the stage copy
+      wait_tiles<SP + TPW, SP>(aop[u]);
 #pragma unroll
       for (int hl = 0; hl < 2; ++hl) {
         bf16x8_t b[NCT];
 #pragma unroll
-        for (int c = 0; c < NCT; ++c) b[c] = __builtin_bit_cast(bf16x8_t, bst[buf][u][2 * c + hl][lane]);
+        for (int c = 0; c < NCT; ++c) b[c] = __builtin_bit_cast(bf16x8_t, cur->t[u][2 * c + hl][lane]);
 #pragma unroll
         for (int s = 0; s < SP; ++s) {
-          const bf16x8_t av = __builtin_bit_cast(bf16x8_t, aop[tu % GEMM_PD][s]);
+          const bf16x8_t av = __builtin_bit_cast(bf16x8_t, aop[u][s]);
 #pragma unroll
           for (int c = 0; c < NCT; ++c)
             acc[s][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[c], acc[s][c], 0, 0, 0);
         }
       }
       // refill the ring slot just consumed (clamped: reloads of the last tile are never used)
+      const uint32_t off = tile_off(k0 + t0 + u + GEMM_KS);
 #pragma unroll
-      for (int s = 0; s < SP; ++s)
-        aop[tu % GEMM_PD][s] =
-            __builtin_nontemporal_load(wrow[s] + (size_t)min(k0 + t + GEMM_PD, kend - 1) * 64 + lane);
+      for (int s = 0; s < SP; ++s) load_tile_async(aop[u][s], off, wrow[s]);
       // keep the k-steps apart: hoisting the next step's operand reads over this step's
       // products would need more registers than a wavefront has
       __builtin_amdgcn_sched_barrier(0);
-      if (u == GEMM_KS - 1) {
-        stage_store(buf ^ 1);
-        gemm_lds_barrier();
-      }
     }
+    // outstanding, oldest first: the stage copy (TPW), then the GEMM_KS * SP refills: once at
+    // most that many remain, this wavefront's part of the next stage is in LDS and the
+    // barrier publishes it; the weight prefetch stays in flight
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
+  };
+  for (int t0 = 0; t0 < nkp; t0 += 2 * GEMM_KS) {
+    stage_body(t0, st0, st1);
+    if (t0 + GEMM_KS < nkp) stage_body(t0 + GEMM_KS, st1, st0);
   }
+  // the clamped refills and the last stage copy are still in flight: let them land before the
+  // registers and the LDS stages are reused
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // D[i][j] of a tile: output i = 4*(lane/16) + reg of the strip, row j = lane%16 of the tile
   const int j = lane & 15, i4 = (lane >> 4) * 4;
+  const int m0 = rb * 16 * NCT;
 #pragma unroll
   for (int s = 0; s < SP; ++s) {
     if (s < ns) {
@@ -196,7 +251,7 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, u32x4_t (*bst)[GEMM
 
 template <int NCT, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
-  __shared__ u32x4_t bst[2][GEMM_KS][NCT * 2][64];
+  __shared__ GemmStage<NCT> stage0, stage1;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int gc_count = a.ngroups * a.nchunks;
   for (int unit = blockIdx.x; unit < a.units; unit += gridDim.x) {
@@ -210,16 +265,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     const int g1 = (int)((int64_t)a.nstrips * (group + 1) / a.ngroups);
     const int k0 = gemm_chunk_begin(a.KT, a.nchunks, chunk);
     const int nk = gemm_chunk_begin(a.KT, a.nchunks, chunk + 1) - k0;
-    const int m0 = rb * 16 * NCT;
     for (int base = g0; base < g1; base += GEMM_WAVES * GEMM_SMAX) {
       const int P = min(g1 - base, GEMM_WAVES * GEMM_SMAX);
       const int per = (P + GEMM_WAVES - 1) / GEMM_WAVES;          // strips per wavefront
       const int sfirst = min(base + wave * per, g1 - 1);
-      const int ns = max(0, min(per, base + P - (base + wave * per)));
-      if (per > 4) gemm_pass<NCT, 8, EPI>(a, bst, m0, chunk, k0, nk, sfirst, ns);
-      else if (per > 2) gemm_pass<NCT, 4, EPI>(a, bst, m0, chunk, k0, nk, sfirst, ns);
-      else if (per == 2) gemm_pass<NCT, 2, EPI>(a, bst, m0, chunk, k0, nk, sfirst, ns);
-      else gemm_pass<NCT, 1, EPI>(a, bst, m0, chunk, k0, nk, sfirst, ns);
+      const int ns = max(0, min(per, P - wave * per));
+      if (per > 2) gemm_pass<NCT, 4, EPI>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
+      else if (per == 2) gemm_pass<NCT, 2, EPI>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
+      else gemm_pass<NCT, 1, EPI>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
     }
   }
 }
@@ -227,24 +280,33 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 int g_gemm_wgs = 256;      // resident workgroups: one per compute unit
 
 // k-chunks of a matrix on this path: fixed per matrix so that a row's sums do not depend on
-// the call.  Matrices with few strips are cut along k until (strip ranges of >= 8 strips) x
-// chunks fill the compute units; chunks are at least 16 k-steps long.
+// the call.  Matrices with few strips are cut along k until (strip ranges of about 16 strips)
+// x chunks fill the compute units; chunks are at least 16 k-steps long.
 int gemm_bf16_chunks(int Kd, int nstrips) {
   const int KT = Kd / 32;
-  const int groups_max = (nstrips + GEMM_WAVES - 1) / GEMM_WAVES;
-  if (groups_max >= g_gemm_wgs) return 1;
-  int nch = (g_gemm_wgs + groups_max / 2) / groups_max;
+  const int groups = (nstrips + 2 * GEMM_WAVES - 1) / (2 * GEMM_WAVES);
+  if (groups >= g_gemm_wgs / 2) return 1;
+  int nch = (g_gemm_wgs + groups / 2) / groups;
   nch = min(nch, max(1, KT / 16));
   return max(1, nch);
 }
 
+// Row tiles the packed activations of M rows hold (whole row blocks of the kernel variant
+// that M selects) and their size in bytes.
+static int gemm_nct(int M) { return M <= 32 ? 2 : (M <= 64 ? 4 : 8); }
+size_t gemm_bf16_pack_bytes(int M, int Kd) {
+  const int nct = gemm_nct(M), ntiles = (M + 16 * nct - 1) / (16 * nct) * nct;
+  const int ksteps = (Kd / 32 + 1) / 2 * 2;
+  return (size_t)ksteps * ntiles * 2048;
+}
+
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
-                            float *out, int out_stride, size_t chunk_stride, int nchunks, int epi,
-                            hipStream_t st) {
+                            void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
+                            int epi, hipStream_t st) {
   if (M < 1 || nstrips < 1 || nchunks < 1 || (epi == 1 && nchunks != 1)) return hipErrorInvalidValue;
   GemmArgs a;
   a.Wp = (const u32x4_t *)W.data;
-  a.X = X;
+  a.Xp = (const u32x4_t *)pack;
   a.out = out;
   a.chunk_stride = chunk_stride;
   a.M = M;
@@ -254,13 +316,23 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   a.nstrips = nstrips;
   a.n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
   a.out_stride = out_stride;
-  const int nct = M <= 32 ? 2 : (M <= 64 ? 4 : 8);
+  const int nct = gemm_nct(M);
   a.row_blocks = (M + 16 * nct - 1) / (16 * nct);
+  a.ntiles = a.row_blocks * nct;
+  const int ksteps = (a.KT + 1) / 2 * 2;
+  {
+    const int64_t items = (int64_t)ksteps * a.ntiles * 64;
+    hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X,
+                       M, W.Kd, a.ntiles, ksteps, (u32x4_t *)pack);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  // strip ranges: as many as fill the machine, but at least one strip per wavefront
   const int groups_max = (nstrips + GEMM_WAVES - 1) / GEMM_WAVES;
   a.ngroups = max(1, min(groups_max, g_gemm_wgs / (nchunks * a.row_blocks)));
   const int gc = a.ngroups * nchunks;
   a.units = (gc + 7) / 8 * 8 * a.row_blocks;
-  const dim3 grid(min(a.units, 2 * g_gemm_wgs)), block(GEMM_THREADS);
+  const dim3 grid(a.units), block(GEMM_THREADS);
 #define DART_GEMM_GO(NCT_)                                                                   \
   do {                                                                                       \
     if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1>), grid, block, 0, st, a);    \
