@@ -21,6 +21,8 @@
 // longer than 32 strips takes several passes over k.  The sum of a row is one chain per
 // k-chunk in k order (hi product, then lo product, per 32-input step), independent of the
 // number of rows and of the strip grouping; chunk partials are added by the consumer.
+#include <type_traits>
+
 #include "common.h"
 #include "dart_internal.h"
 
@@ -159,56 +161,80 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0
 #pragma unroll
     for (int c = 0; c < NCT; ++c) acc[s][c] = {0.f, 0.f, 0.f, 0.f};
 
-  // prologue: stage 0 and the weight tiles of the first two k-steps
-  u32x4_t aop[GEMM_KS][SP];
-  stage_copy(k0, st0);
+  // Ring of weight tiles: PD k-steps deep, slot t % PD serves k-step t and is refilled (with
+  // k-step t + PD) right after the products that consumed it.  8 to 16 KiB are in flight per
+  // wavefront (64 to 128 KiB per compute unit) whatever the number of strips, so that neither
+  // the full passes nor the ones with few strips per wavefront are bound by memory latency.
+  constexpr int PD = SP == 4 ? 4 : 8 / SP;
+  constexpr int UNR = PD < 4 ? 4 : PD;                    // k-steps per unrolled loop body
+  u32x4_t aop[PD][SP];
+  // prologue: stage 0 and the weight tiles of the first PD k-steps, issued in the same
+  // pattern as the loop issues them (per stage: copies, then two k-steps of tiles; stage 0 is
+  // simply copied PD/2 times), so that the counted waits below hold from the first k-step on
 #pragma unroll
-  for (int p = 0; p < GEMM_KS; ++p)
+  for (int p = 0; p < PD; ++p) {
+    if (p % GEMM_KS == 0) stage_copy(k0, st0);
 #pragma unroll
     for (int s = 0; s < SP; ++s) {
       aop[p][s] = u32x4_t{0, 0, 0, 0};
       load_tile_async(aop[p][s], tile_off(k0 + p), wrow[s]);
     }
+  }
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
 
-  // One stage: GEMM_KS k-steps out of `cur` while the next stage is copied into `nxt`.
-  // Loads outstanding on entry, oldest first: tiles of k-step 0 (SP), tiles of k-step 1 (SP).
-  auto stage_body = [&](int t0, GemmStage<NCT> *cur, GemmStage<NCT> *nxt) {
+  // One stage: GEMM_KS k-steps out of `cur` while the next stage is copied into `nxt`; J is the
+  // position of the stage's first k-step in the unrolled body (ring slots are static).
+  auto stage_body = [&](int t0, auto jtag, GemmStage<NCT> *cur, GemmStage<NCT> *nxt) {
+    constexpr int J = decltype(jtag)::value;
     // next stage (clamped at the end: copied again, never used)
     stage_copy(min(k0 + t0 + GEMM_KS, k0 + nkp - GEMM_KS), nxt);
 #pragma unroll
     for (int u = 0; u < GEMM_KS; ++u) {
-      // younger than the tiles of this k-step: the other k-step's tiles and the stage copy
-      wait_tiles<SP + TPW, SP>(aop[u]);
+      const int slot = (J + u) % PD;
+      // Issued after this k-step's tiles and possibly still in flight: the tiles of the PD - 1
+      // following k-steps and the stage copies of the PD / 2 stage starts since then.
+      wait_tiles<(PD - 1) * SP + (PD / 2) * TPW, SP>(aop[slot]);
+      // operand tiles are read NB at a time (registers), hi then lo of each row tile: every
+      // accumulator still adds its hi product, then its lo product, k-step by k-step
+      constexpr int NB = NCT < 4 ? NCT : 4;
 #pragma unroll
-      for (int hl = 0; hl < 2; ++hl) {
-        bf16x8_t b[NCT];
+      for (int cb = 0; cb < NCT; cb += NB) {
 #pragma unroll
-        for (int c = 0; c < NCT; ++c) b[c] = __builtin_bit_cast(bf16x8_t, cur->t[u][2 * c + hl][lane]);
+        for (int hl = 0; hl < 2; ++hl) {
+          bf16x8_t b[NB];
 #pragma unroll
-        for (int s = 0; s < SP; ++s) {
-          const bf16x8_t av = __builtin_bit_cast(bf16x8_t, aop[u][s]);
+          for (int c = 0; c < NB; ++c)
+            b[c] = __builtin_bit_cast(bf16x8_t, cur->t[u][2 * (cb + c) + hl][lane]);
 #pragma unroll
-          for (int c = 0; c < NCT; ++c)
-            acc[s][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[c], acc[s][c], 0, 0, 0);
+          for (int s = 0; s < SP; ++s) {
+            const bf16x8_t av = __builtin_bit_cast(bf16x8_t, aop[slot][s]);
+#pragma unroll
+            for (int c = 0; c < NB; ++c)
+              acc[s][cb + c] =
+                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[c], acc[s][cb + c], 0, 0, 0);
+          }
         }
       }
       // refill the ring slot just consumed (clamped: reloads of the last tile are never used)
-      const uint32_t off = tile_off(k0 + t0 + u + GEMM_KS);
+      const uint32_t off = tile_off(k0 + t0 + u + PD);
 #pragma unroll
-      for (int s = 0; s < SP; ++s) load_tile_async(aop[u][s], off, wrow[s]);
+      for (int s = 0; s < SP; ++s) load_tile_async(aop[slot][s], off, wrow[s]);
       // keep the k-steps apart: hoisting the next step's operand reads over this step's
       // products would need more registers than a wavefront has
       __builtin_amdgcn_sched_barrier(0);
     }
-    // outstanding, oldest first: the stage copy (TPW), then the GEMM_KS * SP refills: once at
-    // most that many remain, this wavefront's part of the next stage is in LDS and the
-    // barrier publishes it; the weight prefetch stays in flight
+    // outstanding, oldest first: ..., this stage's copies (TPW), then its GEMM_KS * SP refills:
+    // once at most that many remain, this wavefront's part of the next stage is in LDS and
+    // the barrier publishes it; the weight prefetch stays in flight
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
   };
-  for (int t0 = 0; t0 < nkp; t0 += 2 * GEMM_KS) {
-    stage_body(t0, st0, st1);
-    if (t0 + GEMM_KS < nkp) stage_body(t0 + GEMM_KS, st1, st0);
+  for (int t0 = 0; t0 < nkp; t0 += UNR) {
+    stage_body(t0, std::integral_constant<int, 0>{}, st0, st1);
+    if (t0 + 2 < nkp) stage_body(t0 + 2, std::integral_constant<int, 2>{}, st1, st0);
+    if constexpr (UNR == 8) {
+      if (t0 + 4 < nkp) stage_body(t0 + 4, std::integral_constant<int, 4>{}, st0, st1);
+      if (t0 + 6 < nkp) stage_body(t0 + 6, std::integral_constant<int, 6>{}, st1, st0);
+    }
   }
   // the clamped refills and the last stage copy are still in flight: let them land before the
   // registers and the LDS stages are reused
