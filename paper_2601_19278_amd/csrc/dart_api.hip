@@ -195,15 +195,23 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   // one pass carries the query rows of up to DART_SEQ_GROUP sequences
   c->ws_rows = std::max(R, std::min(g.max_batch, DART_SEQ_GROUP) * g.max_K);
   const size_t W = c->ws_rows;
-  c->max_splits = (c->t_cap + ATTN_KEY_CHUNK - 1) / ATTN_KEY_CHUNK;
+  // attention partials: per query vector, one per 128-key split and key sub-range; fewer query
+  // rows per sequence mean more sub-ranges, so size for the worst draft length
+  c->max_splits = c->t_cap / ATTN_KEY_CHUNK;
+  int att_rows = g.max_K;
+  if (g.dtype == DART_BF16)
+    for (int k = 1; k <= g.max_K; ++k)
+      att_rows = std::max(att_rows, k * attn_mfma_nsub(k, g.n_q_heads / g.n_kv_heads));
+  const size_t att_slots = (size_t)std::min(g.max_batch, DART_SEQ_GROUP) * att_rows * g.n_q_heads *
+                           c->max_splits;
   const size_t proj_elems = std::max(std::max((size_t)ch_o * d, (size_t)ch_down * d),
                                      (size_t)ch_gu * 2 * F);
   HIP_TRY(dev_alloc(&c->xn, W * d));
   HIP_TRY(dev_alloc(&c->resid, W * d));
   HIP_TRY(dev_alloc(&c->qkv, (size_t)ch_qkv * W * c->qkv_dim));
   HIP_TRY(hipMalloc(&c->qrot, W * c->q_dim * 4));
-  HIP_TRY(dev_alloc(&c->att_part, W * g.n_q_heads * c->max_splits * hd));
-  HIP_TRY(dev_alloc(&c->att_ml, W * g.n_q_heads * c->max_splits * 2));
+  HIP_TRY(dev_alloc(&c->att_part, att_slots * hd));
+  HIP_TRY(dev_alloc(&c->att_ml, att_slots * 2));
   HIP_TRY(dev_alloc(&c->att_out, W * c->q_dim));
   HIP_TRY(dev_alloc(&c->proj, W * proj_elems));
   HIP_TRY(dev_alloc(&c->y, W * d));
@@ -421,7 +429,7 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
   c->q_dim = q_dim;
   c->kv_dim = g.n_kv_heads * g.head_dim;
   c->qkv_dim = c->q_dim + 2 * c->kv_dim;
-  c->t_cap = round_up(g.max_ctx + g.max_K - 1, 64);
+  c->t_cap = round_up(g.max_ctx + g.max_K - 1, ATTN_KEY_CHUNK);   // whole key chunks per row
   c->cached_rows = (int *)calloc(g.max_batch, sizeof(int));
   if (!c->cached_rows) {
     delete c;

@@ -71,16 +71,25 @@ __host__ __device__ inline void seq_of_row(const SeqBatch &sb, int r, int &b, in
   qi = local - (sb.row_off[b + 1] - sb.row_off[b] - sb.K);
 }
 
+// Where key position pos sits in a row of the transposed V buffer: within every block of 32
+// keys, key x is stored at 8*((x%16)/4) + 4*(x/16) + x%4, so that the 8 keys a lane of the
+// P.V product contracts over (4*gq..+3 and 16+4*gq..+3, the layout the score product leaves
+// the probabilities in) are 16 contiguous bytes.
+__host__ __device__ inline int attn_vt_position(int pos) {
+  const int x = pos & 31;
+  return (pos & ~31) | (8 * ((x & 15) >> 2) + 4 * (x >> 4) + (x & 3));
+}
+
 struct dart_ctx {
   dart_config cfg;
   int q_dim, kv_dim, qkv_dim;
-  int t_cap;                     // K/V rows per (sequence, head): max_ctx + max_K - 1, padded to 64
+  int t_cap;                     // K/V rows per (sequence, head): max_ctx + max_K - 1, padded to whole 128-key chunks
   // weights
   DeviceMatrix wqkv, wo, wgu, wdown, wlm;   // wgu: gate and up rows interleaved (see dart_api.hip)
   void *g_in = nullptr, *g_post = nullptr, *g_final = nullptr, *g_q = nullptr, *g_k = nullptr;
   void *mask_emb = nullptr;
   float *rope_cos = nullptr, *rope_sin = nullptr;   // [t_cap][hd/2]
-  // draft K/V buffers: K [batch][Hkv][t_cap][hd]; V fp32 same, bf16 transposed [batch][Hkv][hd][t_cap]
+  // draft K/V buffers: K [batch][Hkv][t_cap][hd]; V fp32 same, bf16 transposed [batch][Hkv][hd][t_cap] (attn_vt_position order)
   void *kbuf = nullptr, *vbuf = nullptr;
   int *cached_rows = nullptr;     // host, [max_batch]
   // activations / workspaces (device, fp32 unless noted); ws_rows = rows one pass may carry
@@ -141,6 +150,7 @@ hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const flo
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                             hipStream_t st);
+int attn_mfma_nsub(int Kq, int group);        // key sub-ranges per split of the MFMA attention
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
 int gemv_bf16_split(int Kd, int nstrips);     // extra k-split that balances the workgroups
 int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may carry per row block

@@ -55,14 +55,15 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
   }
 }
 
-// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s over the splits that hold keys of
-// the query's sequence (ceil((n + K - 1) / chunk) of the nsplit slots).  A split with l == 0
+// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s over the partials that hold keys of
+// the query's sequence (ceil((n + K - 1) / chunk) splits of nsub sub-ranges each, out of the
+// nsplit slots of the query vector).  A split with l == 0
 // saw no visible key.  One workgroup per query vector, one thread per output dim; the split
 // weights are computed once in parallel and kept in LDS, and the partial rows are then read
 // with independent loads.
-constexpr int ATTN_MAX_SPLITS = 256;
+constexpr int ATTN_MAX_SPLITS = 1024;   // 256 key splits x 4 sub-ranges
 
-__global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, int chunk,
+__global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, int chunk, int nsub,
                                                          const float *__restrict__ o_part,
                                                          const float *__restrict__ ml_part,
                                                          int nsplit, int hd,
@@ -71,7 +72,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, in
   __shared__ float w[ATTN_MAX_SPLITS];
   const int qv = blockIdx.x, t = threadIdx.x;
   const int b = qv / (Hq * sb.K);
-  const int used = (sb.n[b] + sb.K - 1 + chunk - 1) / chunk;    // splits of this sequence
+  const int used = (sb.n[b] + sb.K - 1 + chunk - 1) / chunk * nsub;   // partials of this sequence
   float mx = -3.0e38f;
   for (int s = t; s < used; s += blockDim.x) {
     const size_t slot = (size_t)qv * nsplit + s;
@@ -103,8 +104,8 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, in
   out[(size_t)qv * hd + t] = num / den;
 }
 
-hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, int chunk, int nsplit,
-                                 hipStream_t st);
+hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, int nsplit, hipStream_t st);
+int attn_mfma_nsub(int Kq, int group);
 
 hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
   const dart_config &g = c->cfg;
@@ -115,8 +116,10 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t s
   const int nsplit = (n_max + sb.K - 1 + chunk - 1) / chunk;
   const size_t slot_elems = (size_t)Hkv * c->t_cap * hd;
   const int QVT = sb.B * sb.K * Hq;                      // query vectors of the pass
+  int nsub = 1;
   if (g.dtype == DART_BF16) {
-    hipError_t e = launch_attention_bf16(c, sb, chunk, nsplit, st);
+    nsub = attn_mfma_nsub(sb.K, Hq / Hkv);
+    hipError_t e = launch_attention_bf16(c, sb, nsplit, st);
     if (e != hipSuccess) return e;
   } else {
     const float scale = 1.0f / sqrtf((float)hd);
@@ -134,8 +137,8 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t s
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, Hq, chunk, c->att_part,
-                     c->att_ml, nsplit, hd, c->att_out);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, Hq, chunk, nsub, c->att_part,
+                     c->att_ml, nsplit * nsub, hd, c->att_out);
   return hipGetLastError();
 }
 

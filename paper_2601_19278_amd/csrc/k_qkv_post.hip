@@ -34,7 +34,7 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
   if (!is_q && !is_k) {                           // value head: store as is
     const int g = hh - Hq - Hkv;
     if (v_transposed)
-      vbuf[((size_t)g * hd + t) * t_cap + pos] = from_f32<CT>(x);
+      vbuf[((size_t)g * hd + t) * t_cap + attn_vt_position(pos)] = from_f32<CT>(x);
     else
       vbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(x);
     return;
