@@ -185,11 +185,16 @@ int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_
 
 /* Diagnostic (benchmark only): enqueue only the LM-head projection (the final step of
  * dart_draft_forward, Sec. 3.2) on the final-normed rows the last forward call left in the
- * workspace; logits_out device [K][vocab] fp32.  Used to time that kernel in isolation. */
-dart_status dart_debug_lm_head(dart_ctx *ctx, int K, float *logits_out, void *stream);
+ * workspace; logits_out device [rows][vocab] fp32.  multi_row = 0: the kernel of the
+ * single-sequence call (rows <= 16); 1: the kernels of the batched call (bf16 contexts,
+ * rows <= 16 * max_K): operand conversion pass + contraction; 2: the contraction alone, on the
+ * operand tiles a preceding call with multi_row = 1 and the same rows left behind.  Used to
+ * time those kernels in isolation. */
+dart_status dart_debug_lm_head(dart_ctx *ctx, int rows, int multi_row, float *logits_out,
+                               void *stream);
 
 /* Diagnostic (benchmark sweeps only): override a launch tunable of the kernels by name
- * ("gemv_wgs", "gemv_depth", "gemv_nt", "gemv_split", "attn_mt").  Process-wide,
+ * ("gemv_wgs", "gemv_depth", "gemv_nt", "gemv_split", "gemm_wgs").  Process-wide,
  * not thread-safe.  Returns 0, or -1 for an unknown name. */
 int dart_debug_set(const char *name, int value);
 

@@ -89,7 +89,7 @@ def load_library() -> C.CDLL:
                                     vp, vp]
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
-    lib.dart_debug_lm_head.argtypes = [vp, i32, vp, vp]
+    lib.dart_debug_lm_head.argtypes = [vp, i32, i32, vp, vp]
     lib.dart_debug_set.argtypes = [C.c_char_p, i32]
     _LIB = lib
     return lib
@@ -204,9 +204,9 @@ class DraftContext:
                                    scores.data_ptr(), _stream_ptr(stream)), "dart_topk")
         return ids, scores
 
-    def debug_lm_head(self, K: int, out, stream=None):
-        _check(self._lib.dart_debug_lm_head(self._h, K, out.data_ptr(), _stream_ptr(stream)),
-               "dart_debug_lm_head")
+    def debug_lm_head(self, rows: int, out, stream=None, multi_row: int = 0):
+        _check(self._lib.dart_debug_lm_head(self._h, rows, int(multi_row), out.data_ptr(),
+                                            _stream_ptr(stream)), "dart_debug_lm_head")
         return out
 
     def debug_read(self, name: str, rows: int, cols: int) -> np.ndarray:

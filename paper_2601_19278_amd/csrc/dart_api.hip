@@ -613,18 +613,22 @@ int dart_debug_set(const char *name, int value) {
   else if (!strcmp(name, "gemv_nt")) g_gemv_nt = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
   else if (!strcmp(name, "gemm_wgs")) g_gemm_wgs = value < 1 ? 1 : value;
-  else if (!strcmp(name, "attn_mt")) g_attn_mt = value < 1 ? 1 : (value > 3 ? 3 : value);
   else return -1;
   return 0;
 }
 
 // Diagnostic: run only the LM-head projection again on the final-normed rows the last forward
 // call left in the workspace (used to time that kernel in isolation).
-dart_status dart_debug_lm_head(dart_ctx *c, int K, float *logits_out, void *stream) {
-  if (!c || !logits_out || K < 1 || K > c->cfg.max_K) return DART_ERR_ARG;
+dart_status dart_debug_lm_head(dart_ctx *c, int rows, int multi_row, float *logits_out, void *stream) {
+  if (!c || !logits_out || rows < 1 || rows > c->ws_rows) return DART_ERR_ARG;
+  if (!multi_row && rows > DART_SKINNY_ROWS) return DART_ERR_ARG;
+  if (multi_row && c->cfg.dtype != DART_BF16) return DART_ERR_ARG;
+  if (multi_row == 2)      // contraction only: the operand tiles of the last LM-head call are reused
+    return from_hip(launch_gemm_bf16(c->wlm, 0, (c->cfg.vocab + 15) / 16, nullptr, rows, c->xpack,
+                                     logits_out, c->cfg.vocab, 0, 1, 0, (hipStream_t)stream));
   int chunks = 1;
-  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, K, logits_out, c->cfg.vocab, 0, 1, 0,
-                          &chunks, (hipStream_t)stream));
+  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, rows, logits_out, c->cfg.vocab, 0, 1,
+                          multi_row ? 1 : 0, &chunks, (hipStream_t)stream));
 }
 
 // Diagnostic: copy a named fp32 workspace of the last forward to host memory (synchronises).

@@ -131,7 +131,7 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 }
 
 // Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_attn_mt, g_gemm_wgs;
+extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_gemm_wgs;
 
 // All launchers only enqueue work on `st` and return the launch status.
 
@@ -157,7 +157,8 @@ int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may car
 
 // bf16 multi-row GEMM on packed weights (any M); nchunks is fixed per matrix, see gemm_bf16_chunks.
 // epi 1: the strips are interleaved gate/up rows and out receives silu(gate) * up, [M][out_stride].
-// pack: scratch of gemm_bf16_pack_bytes(M, W.Kd) bytes for the activations in operand order.
+// pack: scratch of gemm_bf16_pack_bytes(M, W.Kd) bytes for the activations in operand order
+// (X == nullptr: pack already holds the operand tiles of these M rows; no conversion pass).
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
                             int epi, hipStream_t st);

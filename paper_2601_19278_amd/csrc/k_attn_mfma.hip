@@ -237,8 +237,6 @@ static hipError_t launch_one(const dart_ctx *c, const SeqBatch &sb, int nsplit, 
   return hipGetLastError();
 }
 
-int g_attn_mt = 3;        // unused (kept for the tunable interface)
-
 // nsplit: 128-key splits of the longest sequence; the partial buffers hold
 // nsplit * attn_mfma_nsub() entries per query vector.
 hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, int nsplit, hipStream_t st) {

@@ -346,7 +346,7 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   a.row_blocks = (M + 16 * nct - 1) / (16 * nct);
   a.ntiles = a.row_blocks * nct;
   const int ksteps = (a.KT + 1) / 2 * 2;
-  {
+  if (X) {                                               // X == nullptr: pack already holds them
     const int64_t items = (int64_t)ksteps * a.ntiles * 64;
     hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X,
                        M, W.Kd, a.ntiles, ksteps, (u32x4_t *)pack);
