@@ -12,18 +12,28 @@
 // (creation = b*k + c).  Larger key = better under both cuts of the algorithm: within one
 // level it orders by (score desc, creation asc) -- the beam cut -- and across levels by
 // (score desc, level asc, creation asc) -- the global theta cut.  Ranking the level's keys
-// (by counting for up to 512 expansions, by a bitonic sort beyond) gives the next beam
+// (by counting for up to 1024 expansions, by a bitonic sort beyond) gives the next beam
 // (first w) and the level's contenders for the global tree (first theta), which are merged
 // into the running best-theta list.  Since the best
 // theta of a union is the best theta of (best theta of one part) + (the other part), the
 // running list equals Alg. 1's "top-theta of T" after the last level.
+//
+// N-gram lookups.  The context a beam entry presents at level L is the last N-1 tokens of its
+// path: (candidate a of level L-2, candidate b of level L-1) for a trigram.  Which paths
+// survive depends on the scores, but the set of contexts that CAN occur does not: it is
+// 1 + k + (K-2) k^2 candidate pairs, known from the candidate lists alone.  When that set is
+// small enough for LDS (k <= 13 at K = 8), the kernel resolves all of them before the first
+// level -- every hash probe and every successor-row read of the call in flight at once, two
+// memory round trips in total -- and the K levels then run without touching memory.
+// Otherwise each level looks up its own beam entries (at most w per level, as in App. C.2).
 #include "common.h"
 #include "dart_internal.h"
 
 namespace dart {
 
-constexpr int PRUNE_THREADS = 256;
-constexpr int PRUNE_FAST = 2;          // expansions per thread on the register-resident path
+constexpr int PRUNE_THREADS = 1024;    // one workgroup per sequence; many phases are item-parallel
+constexpr int PRUNE_NG_CELLS = 16384;  // N-gram scores of all possible (context, candidate) pairs
+constexpr int PRUNE_NG_CTX = 1280;     // possible contexts of one call resolved up front
 
 struct PruneShared {
   uint64_t keys[DART_MAX_LEVEL_NODES];        // this level's expansions
@@ -35,6 +45,14 @@ struct PruneShared {
   int32_t beam_prev[2][DART_MAX_BEAM];
   int32_t beam_cre[2][DART_MAX_BEAM];          // creation index of the entry at its own level
   int32_t beam_row[DART_MAX_BEAM];             // table row of the entry's context, -1 = unseen
+  int32_t rank[PRUNE_THREADS];                 // rank of expansion e among the level's keys
+  int32_t beam_ci[2][DART_MAX_BEAM];           // candidate index of the entry's token at its level
+  int32_t beam_pi[2][DART_MAX_BEAM];           // candidate index of its parent's token
+  // up-front mode: s_ng of candidate c for possible context g at ng[g * k + c]
+  float ng[PRUNE_NG_CELLS];
+  int32_t ctx_row[PRUNE_NG_CTX];               // table row of possible context g, -1 = unseen
+  int32_t hit_ctx[PRUNE_NG_CTX];               // the contexts that have a row
+  int32_t n_hit;
   // N-gram score of every (beam entry, candidate) pair of the level, filled while the beam
   // entries' successor rows stream in
   float s_ng[DART_MAX_LEVEL_NODES];
@@ -105,6 +123,115 @@ __device__ __forceinline__ void score_rows(PruneShared &sh, const NgramTableDev 
   }
 }
 
+// Possible contexts, numbered level by level: level 0 has one (the real tail), level 1 has k
+// (root, candidate), levels >= 2 have k*k (k for a bigram model, whose context is one token).
+__device__ __forceinline__ int ctx_offset(int L, int k, int ctx_len) {
+  if (L == 0) return 0;
+  if (ctx_len < 2) return 1 + (L - 1) * k;
+  return L == 1 ? 1 : 1 + k + (L - 2) * k * k;
+}
+
+// Up-front resolution of every possible context (see the header): fills sh.ng.
+__device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, int K, int k,
+                                     int ctx_len, int prev0, int root, int t) {
+  const int NC = ctx_offset(K, k, ctx_len);
+  for (int e = t; e < NC * k; e += PRUNE_THREADS) sh.ng[e] = tab.logp_miss;
+  if (t == 0) sh.n_hit = 0;
+  __syncthreads();
+  // 1. hash probes, one or two contexts per thread, first slots of all of them in flight together
+  constexpr int Q = (PRUNE_NG_CTX + PRUNE_THREADS - 1) / PRUNE_THREADS;
+  uint64_t packed[Q], hslot[Q];
+  uint4 raw[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int g = t + q * PRUNE_THREADS;
+    if (g < NC) {
+      int L, idx;
+      if (g == 0) {
+        L = 0, idx = 0;
+      } else if (ctx_len < 2) {
+        L = 1 + (g - 1) / k, idx = (g - 1) % k;
+      } else if (g < 1 + k) {
+        L = 1, idx = g - 1;
+      } else {
+        L = 2 + (g - 1 - k) / (k * k), idx = (g - 1 - k) % (k * k);
+      }
+      int prev, tok;
+      if (L == 0) {
+        prev = prev0, tok = root;
+      } else if (ctx_len < 2 || L == 1) {
+        prev = root, tok = sh.cand_id[(L - 1) * k + idx];
+      } else {
+        prev = sh.cand_id[(L - 2) * k + idx / k], tok = sh.cand_id[(L - 1) * k + idx % k];
+      }
+      packed[q] = pack_context(ctx_len, prev, tok);
+      hslot[q] = mix64(packed[q]) & tab.slot_mask;
+      raw[q] = slot_load(tab, hslot[q]);
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int g = t + q * PRUNE_THREADS;
+    if (g < NC) {
+      const int row = ngram_resolve(tab, packed[q], hslot[q], raw[q]);
+      sh.ctx_row[g] = row;
+      if (row >= 0) sh.hit_ctx[atomicAdd(&sh.n_hit, 1)] = g;   // order irrelevant: cells are disjoint
+    }
+  }
+  __syncthreads();
+  // 2. successor rows of the contexts that exist, each successor compared with the k
+  //    candidates of the context's level.  Successor ids are distinct within a row and
+  //    candidate ids within a level, so at most one thread writes a cell.
+  const int S = tab.S, n_hit = sh.n_hit;
+  auto level_of = [&](int g) {
+    if (g == 0) return 0;
+    if (ctx_len < 2) return 1 + (g - 1) / k;
+    return g < 1 + k ? 1 : 2 + (g - 1 - k) / (k * k);
+  };
+  if ((S & 3) == 0) {
+    const int parts = S >> 2;                  // 16-byte pieces per row
+    const int total = n_hit * parts;
+    constexpr int U = 8;
+    for (int i0 = t; i0 < total; i0 += U * PRUNE_THREADS) {
+      // all 2*U loads of a thread are issued before the first use; items past the end are
+      // clamped (loaded twice, used once) so that no branch separates the loads
+      int4 id4[U];
+      float4 lp4[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int item = min(i0 + u * PRUNE_THREADS, total - 1);
+        const size_t at = (size_t)sh.ctx_row[sh.hit_ctx[item / parts]] * S + 4 * (item % parts);
+        id4[u] = *reinterpret_cast<const int4 *>(tab.succ_ids + at);
+        lp4[u] = *reinterpret_cast<const float4 *>(tab.succ_logp + at);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int item = i0 + u * PRUNE_THREADS;
+        if (item < total) {
+          const int g = sh.hit_ctx[item / parts], L = level_of(g);
+          const int idv[4] = {id4[u].x, id4[u].y, id4[u].z, id4[u].w};
+          const float lpv[4] = {lp4[u].x, lp4[u].y, lp4[u].z, lp4[u].w};
+          for (int c = 0; c < k; ++c) {
+            const int want = sh.cand_id[L * k + c];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (idv[r] == want) sh.ng[g * k + c] = lpv[r];
+          }
+        }
+      }
+    }
+  } else {
+    for (int item = t; item < n_hit * S; item += PRUNE_THREADS) {
+      const int g = sh.hit_ctx[item / S], L = level_of(g);
+      const size_t at = (size_t)sh.ctx_row[g] * S + item % S;
+      const int32_t id = tab.succ_ids[at];
+      const float lp = tab.succ_logp[at];
+      for (int c = 0; c < k; ++c)
+        if (sh.cand_id[L * k + c] == id) sh.ng[g * k + c] = lp;
+    }
+  }
+}
+
 __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     const int32_t *__restrict__ ids, const float *__restrict__ scores, int K,
     const int32_t *__restrict__ ctx_tail, NgramTableDev tab, int k, int beam_w, int budget,
@@ -128,17 +255,25 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     sh.cand_sc[e] = scores[e];
   }
   const int root = ctx_tail[ctx_len - 1];
+  const int prev0 = ctx_len >= 2 ? ctx_tail[ctx_len - 2] : 0;
+  // all possible contexts up front when they fit (uniform for the workgroup)
+  const bool pre = ctx_offset(K, k, ctx_len) <= PRUNE_NG_CTX &&
+                   ctx_offset(K, k, ctx_len) * k <= PRUNE_NG_CELLS;
   if (t == 0) {
-    const int prev = ctx_len >= 2 ? ctx_tail[ctx_len - 2] : 0;
     sh.beam_score[0][0] = 0.f;
     sh.beam_tok[0][0] = root;
-    sh.beam_prev[0][0] = prev;
+    sh.beam_prev[0][0] = prev0;
     sh.beam_cre[0][0] = -1;                    // the root
-    sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev, root));
+    sh.beam_ci[0][0] = 0;
+    sh.beam_pi[0][0] = 0;
+    if (!pre) sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev0, root));
   }
   int nb = 1, n_best = 0, cur = 0, bcur = 0;
   __syncthreads();
-  score_rows(sh, tab, 1, k, 0, t);
+  if (pre)
+    resolve_all_contexts(sh, tab, K, k, ctx_len, prev0, root, t);
+  else
+    score_rows(sh, tab, 1, k, 0, t);
   __syncthreads();
 
   for (int L = 0; L < K; ++L) {
@@ -153,7 +288,11 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     auto expansion_key = [&](int e, int &tok_out, int &b_out) -> uint64_t {
       const int b = e / k, c = e - b * k;
       const int tok = sh.cand_id[L * k + c];
-      const float s_ng = sh.s_ng[e];
+      // up-front mode: the entry's context is (its parent's candidate, its own candidate)
+      const int gctx = ctx_offset(L, k, ctx_len) +
+                       (L < 2 || ctx_len < 2 ? sh.beam_ci[cur][b]
+                                             : sh.beam_pi[cur][b] * k + sh.beam_ci[cur][b]);
+      const float s_ng = pre ? sh.ng[gctx * k + c] : sh.s_ng[e];
       const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
       const float g = __fmul_rn(w_ng, s_ng);
       const float inc = __fmul_rn(__fadd_rn(a, g), wv);
@@ -164,60 +303,63 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
              (uint64_t)(0x0FFFFFFF - e);
     };
 
-    if (n_new <= PRUNE_FAST * PRUNE_THREADS) {
-      // Register-resident path: a thread owns up to two expansions, ranks them by counting
-      // the keys that beat them (keys are unique), and -- because it knows the context its
-      // expansion would present at the next level -- fetches that context's hash slot
-      // already now, so the table probe overlaps with the ranking instead of following it.
-      uint64_t key[PRUNE_FAST], packed[PRUNE_FAST], hslot[PRUNE_FAST];
-      uint4 raw[PRUNE_FAST];
-      int tok[PRUNE_FAST], bb[PRUNE_FAST], rank[PRUNE_FAST];
-#pragma unroll
-      for (int q = 0; q < PRUNE_FAST; ++q) {
-        const int e = t + q * PRUNE_THREADS;
-        key[q] = 0;
-        if (e < n_new) {
-          key[q] = expansion_key(e, tok[q], bb[q]);
-          sh.keys[e] = key[q];
-          if (!last) {
-            packed[q] = pack_context(ctx_len, sh.beam_tok[cur][bb[q]], tok[q]);
-            hslot[q] = mix64(packed[q]) & tab.slot_mask;
-            raw[q] = slot_load(tab, hslot[q]);
-          }
+    if (n_new <= PRUNE_THREADS) {
+      // Register-resident path: thread e (< n_new) owns expansion e.  Keys are ranked by
+      // counting the keys that beat them (keys are unique); with few expansions the count of
+      // one key is split over PARTS threads (thread e + i*span counts slice i of the keys),
+      // which shortens the serial loop the level's latency is made of.  In level-by-level
+      // mode the owner knows the context its expansion would present at the next level and
+      // fetches that context's hash slot before ranking, so the probe overlaps with it.
+      const int span = n_new <= PRUNE_THREADS / 4 ? PRUNE_THREADS / 4
+                       : (n_new <= PRUNE_THREADS / 2 ? PRUNE_THREADS / 2 : PRUNE_THREADS);
+      const int parts = PRUNE_THREADS / span;
+      const int e = t % span, part = t / span;
+      const bool owner = part == 0 && e < n_new;
+      uint64_t key = 0, packed = 0, hslot = 0;
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      int tok = 0, bb = 0;
+      if (owner) {
+        key = expansion_key(e, tok, bb);
+        sh.keys[e] = key;
+        sh.rank[e] = 0;
+        if (!last && !pre) {
+          packed = pack_context(ctx_len, sh.beam_tok[cur][bb], tok);
+          hslot = mix64(packed) & tab.slot_mask;
+          raw = slot_load(tab, hslot);
         }
-        rank[q] = 0;
       }
       __syncthreads();
-      for (int j = 0; j < n_new; ++j) {
-        const uint64_t kj = sh.keys[j];
-#pragma unroll
-        for (int q = 0; q < PRUNE_FAST; ++q) rank[q] += kj > key[q];
+      if (e < n_new) {
+        const uint64_t mine = sh.keys[e];
+        const int per = (n_new + parts - 1) / parts;
+        const int j0 = part * per, j1 = min(n_new, j0 + per);
+        int cnt = 0;
+        // (unrolled: eight independent LDS reads in flight instead of one latency per key)
+#pragma unroll 8
+        for (int j = j0; j < j1; ++j) cnt += sh.keys[j] > mine;
+        if (cnt) atomicAdd(&sh.rank[e], cnt);
       }
-#pragma unroll
-      for (int q = 0; q < PRUNE_FAST; ++q) {
-        const int e = t + q * PRUNE_THREADS;
-        if (e < n_new) {
-          const int r = rank[q];
-          if (r < nb_next) {
-            sh.beam_score[nxt][r] = f32_unsortable((uint32_t)(key[q] >> 32));
-            sh.beam_tok[nxt][r] = tok[q];
-            sh.beam_prev[nxt][r] = sh.beam_tok[cur][bb[q]];
-            sh.beam_cre[nxt][r] = e;
-          }
-          if (r < n_lvl) {
-            sh.lvl_key[r] = key[q];
-            sh.lvl_tok[r] = tok[q];
-            sh.lvl_par[r] = sh.beam_cre[cur][bb[q]];
-          }
+      __syncthreads();
+      int r = PRUNE_THREADS;
+      if (owner) {
+        r = sh.rank[e];
+        if (r < nb_next) {
+          sh.beam_score[nxt][r] = f32_unsortable((uint32_t)(key >> 32));
+          sh.beam_tok[nxt][r] = tok;
+          sh.beam_prev[nxt][r] = sh.beam_tok[cur][bb];
+          sh.beam_cre[nxt][r] = e;
+          sh.beam_ci[nxt][r] = e - bb * k;
+          sh.beam_pi[nxt][r] = sh.beam_ci[cur][bb];
+        }
+        if (r < n_lvl) {
+          sh.lvl_key[r] = key;
+          sh.lvl_tok[r] = tok;
+          sh.lvl_par[r] = sh.beam_cre[cur][bb];
         }
       }
-      // beam_row of this level was last read before the barrier above: safe to overwrite
-#pragma unroll
-      for (int q = 0; q < PRUNE_FAST; ++q) {
-        const int e = t + q * PRUNE_THREADS;
-        if (!last && e < n_new && rank[q] < nb_next)
-          sh.beam_row[rank[q]] = ngram_resolve(tab, packed[q], hslot[q], raw[q]);
-      }
+      // beam_row of this level was last read before the barriers above: safe to overwrite
+      if (owner && !last && !pre && r < nb_next)
+        sh.beam_row[r] = ngram_resolve(tab, packed, hslot, raw);
     } else {
       // General path (up to 4096 expansions): bitonic sort of the keys in LDS.
       int P = 2, logP = 1;
@@ -256,7 +398,9 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           sh.beam_tok[nxt][t] = tk;
           sh.beam_prev[nxt][t] = sh.beam_tok[cur][b];
           sh.beam_cre[nxt][t] = e;
-          if (!last) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk));
+          sh.beam_ci[nxt][t] = c;
+          sh.beam_pi[nxt][t] = sh.beam_ci[cur][b];
+          if (!last && !pre) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk));
         }
         if (t < n_lvl) {
           sh.lvl_key[t] = kk;
@@ -280,6 +424,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         tok = sh.best_tok[bcur][t];
         par = sh.best_par[bcur][t];
         rank = t;
+#pragma unroll 8
         for (int j = 0; j < n_lvl; ++j) rank += (sh.lvl_key[j] > key);
       } else {
         const int j0 = t - n_best;
@@ -287,6 +432,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         tok = sh.lvl_tok[j0];
         par = sh.lvl_par[j0];
         rank = j0;
+#pragma unroll 8
         for (int j = 0; j < n_best; ++j) rank += (sh.best_key[bcur][j] > key);
       }
       if (rank < theta) {
@@ -295,7 +441,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         sh.best_par[bnx][rank] = par;
       }
     }
-    if (!last) score_rows(sh, tab, nb_next, k, L + 1, t);
+    if (!last && !pre) score_rows(sh, tab, nb_next, k, L + 1, t);
     n_best = min(theta, n_best + n_lvl);
     bcur = bnx;
     cur = nxt;
@@ -309,6 +455,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   if (t < n_best) {
     const int lev = key_level(sh.best_key[bcur][t]);
     int idx = 1;
+#pragma unroll 8
     for (int j = 0; j < n_best; ++j) {
       const int lj = key_level(sh.best_key[bcur][j]);
       idx += (lj < lev) || (lj == lev && j < t);
@@ -323,6 +470,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     if (lev > 0) {
       parent = -2;                                   // stays -2 only if the set were not ancestor-closed
       const int want = sh.best_par[bcur][t];
+#pragma unroll 8
       for (int j = 0; j < n_best; ++j) {
         const uint64_t kj = sh.best_key[bcur][j];
         if (key_level(kj) == lev - 1 && key_creation(kj) == want) parent = sh.out_idx[j];
@@ -343,14 +491,24 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     tokens_out[i] = -1;
     parents_out[i] = -1;
   }
-  for (int i = t; i < budget * budget; i += PRUNE_THREADS) mask_out[i] = 0;
+  // ancestor mask: built in LDS (the expansion keys are no longer needed), written out once
+  uint8_t *mk = reinterpret_cast<uint8_t *>(sh.keys);
+  const int cells = budget * budget;
+  for (int i = t; i < (cells + 3) / 4; i += PRUNE_THREADS) reinterpret_cast<uint32_t *>(mk)[i] = 0;
   __syncthreads();
   if (t < n_nodes) {
     int j = t;
     for (int hops = 0; j >= 0 && hops <= DART_MAX_K; ++hops) {   // depth <= K: bounded walk
-      mask_out[(size_t)t * budget + j] = 1;
+      mk[t * budget + j] = 1;
       j = sh.out_par[j];
     }
+  }
+  __syncthreads();
+  if ((cells & 3) == 0 && (reinterpret_cast<uintptr_t>(mask_out) & 3) == 0) {
+    for (int i = t; i < cells / 4; i += PRUNE_THREADS)
+      reinterpret_cast<uint32_t *>(mask_out)[i] = reinterpret_cast<const uint32_t *>(mk)[i];
+  } else {
+    for (int i = t; i < cells; i += PRUNE_THREADS) mask_out[i] = mk[i];
   }
 }
 

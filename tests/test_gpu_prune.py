@@ -44,6 +44,10 @@ def _compare(case, model, params, tokens, parents, mask, n_nodes):
     (3, 8, 25, 20, 60, 64),      # paper defaults k=25, w=20, theta=59
     (3, 16, 64, 64, 128, 64),    # every limit at its maximum
     (3, 1, 1, 1, 1, 8), (3, 3, 2, 1, 2, 8), (2, 5, 3, 64, 128, 1),
+    (3, 6, 5, 8, 30, 7),         # successor rows that are not whole 16-byte pieces
+    (3, 8, 13, 20, 60, 64),      # largest k whose possible contexts are all resolved up front
+    (3, 8, 14, 20, 60, 64),      # smallest k that looks up level by level
+    (2, 16, 12, 12, 100, 32),    # bigram model, deepest draft
 ])
 def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
     params = otp.PruneParams(k=k, beam_w=w, budget=budget)
