@@ -52,6 +52,15 @@ def event_time_us(fn, iters: int, torch) -> float:
     return start.elapsed_time(stop) * 1000.0 / iters
 
 
+def copy_calibration(torch, dev) -> None:
+    """A plain 1 GiB device copy: known HBM bytes to scale the FETCH_SIZE / WRITE_SIZE counters by."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+
 def bench_batched(cfg, args, seed) -> dict:
     """Batched preset: step = dart_draft_forward_batched (warm, one new prefix row per sequence)
     -> dart_topk over batch*K rows -> dart_tree_prune over the batch."""
@@ -121,6 +130,8 @@ def bench_batched(cfg, args, seed) -> dict:
     ctx.debug_lm_head(B * K, logits, multi_row=1)      # leaves the operand tiles of the 128 rows
     lm_us = event_time_us(lambda: ctx.debug_lm_head(B * K, logits, multi_row=2), it, torch)
     forward(warm)
+    if args.copy_calibration:
+        copy_calibration(torch, dev)
     p = cfg.n_params()
     lm_bytes = p["lm_head"] * 2 + B * K * cfg.vocab * 4
     kv = sum(2 * cfg.n_kv_heads * (n + K - 1) * cfg.head_dim * 2 for n in lens)
@@ -269,12 +280,7 @@ def main() -> int:
     stages["forward_GBps"] = ab["forward"] / (stages["forward_warm_us"] * 1e-6) / 1e9
 
     if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration(torch, dev)
 
     cpu = None
     if not args.no_cpu_baseline:
