@@ -176,6 +176,31 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
                             int32_t *parents_out, uint8_t *mask_out, int32_t *n_nodes_out,
                             void *stream);
 
+/* Hand-over to the target model's verification pass (Sec. 2.1; Fig. 3 "Tree Attention") for
+ * `batch` trees as dart_tree_prune emits them (tokens, parents, n_nodes; `budget` = row
+ * length of those arrays).  All pointers are device memory; one wavefront per tree.
+ *   ctx_len       [batch] int32 prefix lengths n, or NULL (= 0)
+ *   position_ids  [batch][budget] int32 out, or NULL: ctx_len + depth of the node below the
+ *                 root (the root, t_{n+1}, sits at sequence position n); -1 beyond n_nodes.
+ *                 Together with the ancestor mask this is what tree attention needs.
+ *   target_next   [batch][budget] int32, or NULL to skip the acceptance walk: the token the
+ *                 target model itself produces after each tree node (its arg-max at
+ *                 temperature 0), as read from the verification pass
+ *   accept_path   [batch][path_cap] int32 out: node indices of the accepted path, root
+ *                 first, -1 padded.  A child is accepted iff its token equals target_next
+ *                 of its parent; the walk stops at the first node without such a child.
+ *   n_accepted    [batch] int32 out: accepted draft tokens = path length - 1 (tau of the step)
+ *   next_token    [batch] int32 out: target_next at the last accepted node, i.e. the root of
+ *                 the next draft step
+ * path_cap >= 1 bounds the path (DART_MAX_K + 1 always suffices).
+ * Errors: ARG (NULL tokens/parents/n_nodes; target_next without the three outputs; batch < 1;
+ * budget not in 1..DART_MAX_BUDGET; path_cap < 1), HIP. */
+dart_status dart_tree_verify_greedy(int batch, const int32_t *tokens, const int32_t *parents,
+                                    const int32_t *n_nodes, int budget, const int32_t *ctx_len,
+                                    int32_t *position_ids, const int32_t *target_next,
+                                    int path_cap, int32_t *accept_path, int32_t *n_accepted,
+                                    int32_t *next_token, void *stream);
+
 /* Diagnostic (tests only): copy a named fp32 workspace of the last forward call to host
  * memory after synchronising the device.  Names: "xn" (normed layer input), "resid", "qkv",
  * "att_out" (attention output), "y" (after attention residual), "yn", "hmid" (SwiGLU

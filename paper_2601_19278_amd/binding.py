@@ -13,7 +13,7 @@ _LIB = None
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
     "dart_draft_forward_batched", "dart_topk", "dart_ngram_create", "dart_ngram_destroy",
-    "dart_tree_prune", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
+    "dart_tree_prune", "dart_tree_verify_greedy", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
 )
 
 DART_F32, DART_BF16 = 0, 1
@@ -87,6 +87,7 @@ def load_library() -> C.CDLL:
     lib.dart_ngram_destroy.restype = None
     lib.dart_tree_prune.argtypes = [i32, vp, vp, i32, vp, vp, C.POINTER(_PruneParams), vp, vp, vp,
                                     vp, vp]
+    lib.dart_tree_verify_greedy.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
     lib.dart_debug_lm_head.argtypes = [vp, i32, i32, vp, vp]
@@ -215,6 +216,29 @@ class DraftContext:
         if n < 0:
             raise RuntimeError(f"dart_debug_read({name}) failed")
         return buf[: rows * cols].reshape(rows, cols).copy()
+
+
+def tree_verify_greedy(tokens, parents, n_nodes, ctx_len=None, target_next=None, path_cap: int = 17,
+                       stream=None):
+    """dart_tree_verify_greedy on CUDA int32 tensors [batch][budget] (n_nodes, ctx_len [batch]).
+    Returns (position_ids, accept_path, n_accepted, next_token); the last three are None when
+    target_next is None."""
+    torch = _torch()
+    lib = load_library()
+    B, budget = tokens.shape
+    dev = tokens.device
+    pos = torch.empty((B, budget), dtype=torch.int32, device=dev)
+    path = n_acc = nxt = None
+    if target_next is not None:
+        path = torch.empty((B, path_cap), dtype=torch.int32, device=dev)
+        n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
+        nxt = torch.empty((B,), dtype=torch.int32, device=dev)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib.dart_tree_verify_greedy(B, tokens.data_ptr(), parents.data_ptr(), n_nodes.data_ptr(),
+                                       budget, ptr(ctx_len), pos.data_ptr(), ptr(target_next),
+                                       path_cap, ptr(path), ptr(n_acc), ptr(nxt),
+                                       _stream_ptr(stream)), "dart_tree_verify_greedy")
+    return pos, path, n_acc, nxt
 
 
 class NgramTable:

@@ -605,6 +605,20 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
                                parents_out, mask_out, n_nodes_out, (hipStream_t)stream));
 }
 
+dart_status dart_tree_verify_greedy(int batch, const int32_t *tokens, const int32_t *parents,
+                                    const int32_t *n_nodes, int budget, const int32_t *ctx_len,
+                                    int32_t *position_ids, const int32_t *target_next,
+                                    int path_cap, int32_t *accept_path, int32_t *n_accepted,
+                                    int32_t *next_token, void *stream) {
+  if (!tokens || !parents || !n_nodes) return DART_ERR_ARG;
+  if (batch < 1 || budget < 1 || budget > DART_MAX_BUDGET || path_cap < 1) return DART_ERR_ARG;
+  if (target_next && (!accept_path || !n_accepted || !next_token)) return DART_ERR_ARG;
+  if (!target_next && !position_ids) return DART_ERR_ARG;      // nothing to do
+  return from_hip(launch_tree_verify(batch, tokens, parents, n_nodes, target_next, ctx_len, budget,
+                                     path_cap, position_ids, accept_path, n_accepted, next_token,
+                                     (hipStream_t)stream));
+}
+
 // Diagnostic: set a kernel tunable by name (benchmark sweeps).  Returns 0 if the name is known.
 int dart_debug_set(const char *name, int value) {
   if (!name) return -1;

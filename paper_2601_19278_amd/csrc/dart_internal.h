@@ -183,6 +183,12 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t s
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st);
 
+hipError_t launch_tree_verify(int batch, const int32_t *tokens, const int32_t *parents,
+                              const int32_t *n_nodes, const int32_t *target_next,
+                              const int32_t *ctx_len, int budget, int path_cap,
+                              int32_t *position_ids, int32_t *accept_path, int32_t *n_accepted,
+                              int32_t *next_token, hipStream_t st);
+
 hipError_t launch_prune(int batch, const int32_t *ids, const float *scores, int K,
                         const int32_t *ctx_tail, const NgramTableDev &tab,
                         const dart_prune_params &p, const PruneLevelWeights &lw, int32_t *tokens,

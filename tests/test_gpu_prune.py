@@ -75,6 +75,24 @@ def test_batch_of_sequences_shares_one_table():
         _compare(case, model, params, tokens[b], parents[b], mask[b], n_nodes[b])
 
 
+def test_paper_default_scale_batch_64():
+    """The regime the paper runs on host threads along the batch axis (App. D: k = 25, w = 20,
+    theta = 59): 64 sequences in one call, one workgroup each, one shared table."""
+    K, k = 8, 25
+    params = otp.PruneParams(k=k, beam_w=20, budget=60)
+    base = ds.make_prune_case(7150, vocab=151936, K=K, k=k, n_gram=3, S=64)
+    cases = [base]
+    for b in range(1, 64):
+        other = ds.make_prune_case(7150 + b, vocab=151936, K=K, k=k, n_gram=3, S=64)
+        mix = ds.PruneCase(np.where(np.arange(k)[None, :] % 3 != 0, base.ids, other.ids).astype(np.int32),
+                           other.scores, base.ctx_tail if b % 2 else other.ctx_tail, base.table)
+        cases.append(mix)
+    model = NgramModel(3, base.table.keys, base.table.succ_ids, base.table.succ_counts, 1e-9)
+    tokens, parents, mask, n_nodes = _gpu_prune(cases, params)
+    for b, case in enumerate(cases):
+        _compare(case, model, params, tokens[b], parents[b], mask[b], n_nodes[b])
+
+
 def test_weights_variants_and_empty_table():
     K, k = 6, 5
     case = ds.make_prune_case(7200, vocab=50000, K=K, k=k, n_gram=3, S=32)
