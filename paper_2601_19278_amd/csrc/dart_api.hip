@@ -230,6 +230,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   c->topk_chunks_max = (g.vocab + 4095) / 4096;
   HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
   HIP_TRY(dev_alloc(&c->topk_ms, (size_t)c->max_rows * c->topk_chunks_max * 2));
+  HIP_TRY(dev_alloc(&c->topk_count, (size_t)c->max_rows, true));
   return hipSuccess;
 }
 
@@ -451,7 +452,7 @@ void dart_destroy(dart_ctx *c) {
   void *bufs[] = {c->wqkv.data, c->wo.data, c->wgu.data, c->wdown.data, c->wlm.data, c->g_in,
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
-                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
+                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms, c->topk_count,
                   c->xn_kv, c->kv_part, c->xpack};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
@@ -625,6 +626,7 @@ int dart_debug_set(const char *name, int value) {
   if (!strcmp(name, "gemv_wgs")) g_gemv_wgs = value;
   else if (!strcmp(name, "gemv_depth")) g_gemv_depth = value;
   else if (!strcmp(name, "gemv_nt")) g_gemv_nt = value;
+  else if (!strcmp(name, "gemv_nt_min_mb")) g_gemv_nt_min_mb = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
   else if (!strcmp(name, "gemm_wgs")) g_gemm_wgs = value < 1 ? 1 : value;
   else return -1;

@@ -115,6 +115,7 @@ struct dart_ctx {
   // top-k workspace
   uint64_t *topk_cand = nullptr;  // [rows][chunks][DART_MAX_TOPK]
   float *topk_ms = nullptr;       // [rows][chunks][2]
+  int32_t *topk_count = nullptr;  // [rows] chunks of the row published so far (0 between calls)
   int topk_chunks_max;
 };
 
@@ -131,7 +132,7 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 }
 
 // Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_split, g_gemm_wgs;
+extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs;
 
 // All launchers only enqueue work on `st` and return the launch status.
 

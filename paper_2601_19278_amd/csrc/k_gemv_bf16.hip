@@ -40,6 +40,8 @@ int gemv_bf16_chunks(int Kd) {
 int g_gemv_wgs = 256;      // workgroups per k-chunk group: one per CU
 int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
 int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
+int g_gemv_nt_min_mb = 100;  // ... for matrices (strip ranges) of at least this many MiB: smaller ones
+                             // (QKV, O) partly survive in the last-level cache from step to step (measured -3 us)
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
@@ -196,7 +198,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
 }
 
 template <int KPW, int D, bool EXACT>
-static void gemv_launch(int mt, dim3 grid, hipStream_t st, const u32x4_t *wp, const float *X, int M,
+static void gemv_launch(bool nt, int mt, dim3 grid, hipStream_t st, const u32x4_t *wp, const float *X, int M,
                         int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols, float *out,
                         int out_stride, size_t chunk_stride) {
 #define DART_GEMV_GO(MT_, NT_)                                                                    \
@@ -204,12 +206,12 @@ static void gemv_launch(int mt, dim3 grid, hipStream_t st, const u32x4_t *wp, co
                      wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,         \
                      chunk_stride)
   if constexpr (KPW <= 5) {                            // the row-block variants need short k-slices
-    if (mt == 4) { if (g_gemv_nt) DART_GEMV_GO(4, true); else DART_GEMV_GO(4, false); return; }
-    if (mt == 2) { if (g_gemv_nt) DART_GEMV_GO(2, true); else DART_GEMV_GO(2, false); return; }
+    if (mt == 4) { if (nt) DART_GEMV_GO(4, true); else DART_GEMV_GO(4, false); return; }
+    if (mt == 2) { if (nt) DART_GEMV_GO(2, true); else DART_GEMV_GO(2, false); return; }
   }
-  if (mt == 0 && g_gemv_nt) DART_GEMV_GO(0, true);
+  if (mt == 0 && nt) DART_GEMV_GO(0, true);
   else if (mt == 0) DART_GEMV_GO(0, false);
-  else if (g_gemv_nt) DART_GEMV_GO(1, true);
+  else if (nt) DART_GEMV_GO(1, true);
   else DART_GEMV_GO(1, false);
 #undef DART_GEMV_GO
 }
@@ -279,7 +281,8 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   const u32x4_t *wp = (const u32x4_t *)W.data;
   const int depth = g_gemv_depth;
   const bool m8 = mt == 0;
-#define DART_GEMV_ARGS mt, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
+  const bool nt = g_gemv_nt && (int64_t)nstrips * KT / 1024 >= g_gemv_nt_min_mb;
+#define DART_GEMV_ARGS nt, mt, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
   if (exact && kpw == 20) {
     if (depth == 10 || (depth == 0 && !m8)) gemv_launch<20, 10, true>(DART_GEMV_ARGS);
     else if (depth == 5) gemv_launch<20, 5, true>(DART_GEMV_ARGS);

@@ -63,6 +63,21 @@ def test_repeat_runs_are_bit_identical(ctx):
         assert torch.equal(ids, first[0]) and torch.equal(scores, first[1])
 
 
+def test_128_rows_of_a_batched_step_and_heavy_ties():
+    """The batched step's 128 logit rows in one call; rows whose values tie in large groups
+    (more candidates at the selection threshold than the compaction buffer holds)."""
+    cfg = ds.scaled_config("C1", vocab=151936, K=16, batch=8)
+    c, _ = make_context(cfg, 51, max_K=16)
+    rng = np.random.default_rng(11)
+    logits = (rng.standard_normal((128, 151936)) * 2).astype(np.float32)
+    logits[5] = np.round(logits[5])                  # ~10 distinct values: ties by the thousand
+    logits[6] = 0.25
+    logits[7, ::2] = 4.0
+    _check(c, logits, 10)
+    _check(c, logits[:9], 64)
+    c.close()
+
+
 def test_error_statuses(ctx):
     import torch
     import paper_2601_19278_amd as dart
