@@ -186,6 +186,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--n-new", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--front-end", action="store_true",
+                    help="start from the target's raw outputs: FC over 3 concatenated hidden states + "
+                         "shifted token embeddings, 2d-wide attention input (single-sequence presets)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM bytes) for counter scaling")
     args = ap.parse_args()
@@ -205,11 +208,16 @@ def main() -> int:
         print(json.dumps(bench_batched(cfg, args, seed)))
         return 0
     t0 = time.perf_counter()
-    W = ds.make_weights(cfg, seed)
-    hidden = ds.make_hidden(cfg, seed + 1)
+    fe = args.front_end
+    if fe:
+        W = ds.make_frontend_weights(cfg, seed)
+        hidden, next_tokens = ds.make_features(cfg, seed + 1)
+    else:
+        W = ds.make_weights(cfg, seed)
+        hidden = ds.make_hidden(cfg, seed + 1)
     counts = ds.make_ngram_counts(cfg, seed + 2)
     t_gen = time.perf_counter() - t0
-    ctx = dart.DraftContext(cfg, W, max_batch=1)
+    ctx = dart.DraftContext(cfg, W, max_batch=1, feat_dim=3 * cfg.d if fe else 0)
     table = dart.NgramTable(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
     h_dev = dart.bf16_bits_to_tensor(hidden) if cfg.dtype == "bf16" else torch.from_numpy(hidden).cuda()
     tail_np = counts.keys[0].astype(np.int32)
@@ -225,8 +233,13 @@ def main() -> int:
             torch.empty((1, cfg.budget, cfg.budget), dtype=torch.uint8, device=dev),
             torch.empty((1,), dtype=torch.int32, device=dev))
 
+    tok_dev = torch.from_numpy(next_tokens).cuda() if fe else None
+
     def forward(n_cached):
-        ctx.draft_forward(h_dev, n, K, n_cached=n_cached, out=logits)
+        if fe:
+            ctx.draft_forward_features(h_dev, tok_dev, n, K, n_cached=n_cached, out=logits)
+        else:
+            ctx.draft_forward(h_dev, n, K, n_cached=n_cached, out=logits)
 
     def topk():
         ctx.topk(logits, k, 1e-9, out=tk)
@@ -271,6 +284,10 @@ def main() -> int:
     lm_us = event_time_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
     forward(n - args.n_new)          # leave the buffers consistent
     ab = algorithmic_bytes(cfg, args.n_new)
+    if fe:      # + FC weights, + the second half of the Q/K/V input columns (embedding rows: negligible)
+        extra = 2 * (3 * cfg.d * cfg.d + cfg.d * (cfg.q_dim + 2 * cfg.kv_dim))
+        ab["weights"] += extra
+        ab["forward"] += extra
     achieved = ab["lm_head_kernel"] / (lm_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemv_bf16_kernel (LM head)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
@@ -283,7 +300,7 @@ def main() -> int:
         copy_calibration(torch, dev)
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not fe:
         from oracle import draft_forward as odf, topk as otk, tree_prune as otp
         from oracle.ngram import NgramModel
         try:
@@ -312,7 +329,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: d={cfg.d} heads={cfg.n_q_heads}/{cfg.n_kv_heads}x{cfg.head_dim} "
                                f"ffn={cfg.ffn} vocab={cfg.vocab} ctx={cfg.ctx} K={cfg.K} topk={cfg.topk} "
                                f"beam_w={cfg.beam_w} budget={cfg.budget} trigram_keys={cfg.n_keys} "
-                               f"batch=1 warm n_new={args.n_new}"},
+                               f"batch=1 warm n_new={args.n_new}" + (" front-end(FC 3d->d + embeddings)" if fe else "")},
         "roofline": roofline, "cpu_baseline": cpu,
         "stages": {a: (round(b, 2) if b >= 1.0 else float(f"{b:.3e}")) if isinstance(b, float) else b
                    for a, b in stages.items()},

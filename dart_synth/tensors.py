@@ -86,6 +86,41 @@ def make_weights(cfg: DraftConfig, seed: int, max_K: int | None = None) -> dict:
     return out
 
 
+def make_frontend_weights(cfg: DraftConfig, seed: int, max_K: int | None = None,
+                          feat_dim: int | None = None) -> dict:
+    """Draft-layer tensors for the variant that starts from the target's raw outputs: the
+    FC layer w_fc [d][feat_dim] (feat_dim = 3 d: three target layers), the frozen embedding
+    table embed [vocab][d], a second input gain w_emb_norm [d], Q/K/V over the 2d-wide input
+    and 2d-wide mask rows.  The remaining tensors are those of make_weights (same seed, same
+    values)."""
+    max_K = cfg.K if max_K is None else max_K
+    feat_dim = 3 * cfg.d if feat_dim is None else feat_dim
+    store_bf16 = cfg.dtype == "bf16"
+    out = make_weights(cfg, seed, max_K)
+    extra = {"wq": ((cfg.q_dim, 2 * cfg.d), "small"), "wk": ((cfg.kv_dim, 2 * cfg.d), "small"),
+             "wv": ((cfg.kv_dim, 2 * cfg.d), "small"),
+             "mask_emb": ((max(max_K - 1, 1), 2 * cfg.d), "small"),
+             "w_fc": ((cfg.d, feat_dim), "fc"), "embed": ((cfg.vocab, cfg.d), "unit"),
+             "w_emb_norm": ((cfg.d,), "gain")}
+    for idx, (name, (shape, kind)) in enumerate(extra.items()):
+        t = _draw([seed, 404, idx], shape, "unit" if kind == "fc" else kind, False)
+        if kind == "fc":                       # N(0, 1/feat_dim): g rows of unit scale
+            t = t * np.float32(1.0 / np.sqrt(feat_dim))
+        out[name] = f32_to_bf16_bits(t) if store_bf16 else t
+    return out
+
+
+def make_features(cfg: DraftConfig, seed: int, n: int | None = None, feat_dim: int | None = None):
+    """Raw target outputs of an n-token prefix: features [n][feat_dim] ~ N(0, 1) (three
+    concatenated hidden states) and next_tokens [n] int32, uniform over the vocabulary (the
+    token following each position; the last one stands for the sampled t_{n+1})."""
+    n = cfg.ctx if n is None else n
+    feat_dim = 3 * cfg.d if feat_dim is None else feat_dim
+    feats = _draw([seed, 505], (n, feat_dim), "unit", cfg.dtype == "bf16")
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 506])))
+    return feats, rng.integers(0, cfg.vocab, size=n).astype(np.int32)
+
+
 def make_hidden(cfg: DraftConfig, seed: int, n: int | None = None) -> np.ndarray:
     """Target hidden states of an n-token prefix, N(0, 1), [n][d]."""
     n = cfg.ctx if n is None else n

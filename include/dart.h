@@ -70,6 +70,12 @@ typedef struct {
   int32_t qk_norm;     /* 0/1 */
   float rms_eps;
   float rope_base;
+  /* Front end (Sec. 3.2 "Draft model architecture", App. B): 0 = the calls take the fused
+   * prefix representation z [n][d]; 1 = the context also holds the FC layer and the target's
+   * embedding table, dart_draft_forward_features takes the target's raw outputs, and the layer's
+   * attention input is the 2d-wide z = [g ; e] (see dart_draft_forward_features). */
+  int32_t front_end;
+  int32_t feat_dim;    /* front_end: width of the concatenated target hidden states (3 d) */
 } dart_config;
 
 /* HOST pointers, element type per dart_config.dtype (bf16 = raw 16-bit patterns).
@@ -77,10 +83,15 @@ typedef struct {
  * w_down [d][ffn], w_lm [vocab][d], norm gains [d] (q_norm/k_norm [hd], may be
  * NULL when qk_norm == 0), mask_emb [max_K-1][d] (the trainable <MASK>
  * representation, App. B; may be NULL when max_K == 1).
- * dart_create copies (and re-tiles) everything; the caller keeps its arrays. */
+ * dart_create copies (and re-tiles) everything; the caller keeps its arrays.
+ * With front_end = 1: wq/wk/wv are [..][2d] (columns 0..d-1 act on the g half, d..2d-1 on
+ * the embedding half), mask_emb is [max_K-1][2d], and three more tensors are read: w_fc
+ * [d][feat_dim] (the FC layer, no bias), embed [vocab][d] (the target's frozen embedding
+ * table), w_emb_norm [d] (RMSNorm gain of the embedding half; w_in_norm is the g half's). */
 typedef struct {
   const void *w_in_norm, *wq, *wk, *wv, *q_norm, *k_norm, *wo, *w_post_norm;
   const void *w_gate, *w_up, *w_down, *w_final_norm, *w_lm, *mask_emb;
+  const void *w_fc, *embed, *w_emb_norm;
 } dart_weights;
 
 /* Pruning hyper-parameters (App. D): k candidates per level, beam width w,
@@ -119,6 +130,21 @@ dart_status dart_reset(dart_ctx *ctx, int seq);
  * STATE (n_cached > ctx_len-1 or > rows cached in the slot), HIP. */
 dart_status dart_draft_forward(dart_ctx *ctx, int seq, const void *hidden, int ctx_len,
                                int n_cached, int K, float *logits_out, void *stream);
+
+/* Draft forward from the target model's raw outputs (contexts created with front_end = 1;
+ * Sec. 3.2, Fig. 3): for every new prefix position, g = FC(features) and e = embedding of the
+ * token that follows it (the shifted embeddings e_{2:n+1}); z = [g ; e] is the layer's 2d-wide
+ * attention input, each half under its own RMSNorm, and g is the layer's residual stream.
+ *   features     device [ctx_len][feat_dim] in cfg.dtype: the three target hidden states of
+ *                each position, concatenated; only rows [n_cached, ctx_len) are read
+ *   next_tokens  device [ctx_len] int32: token following each position (the last entry is the
+ *                freshly sampled t_{n+1}); only entries [n_cached, ctx_len) are read; values
+ *                must lie in [0, vocab)
+ * Everything else as dart_draft_forward.  Errors: additionally STATE when the context has no
+ * front end (and dart_draft_forward* return STATE on a context that has one). */
+dart_status dart_draft_forward_features(dart_ctx *ctx, int seq, const void *features,
+                                        const int32_t *next_tokens, int ctx_len, int n_cached,
+                                        int K, float *logits_out, void *stream);
 
 /* Same for `batch` sequences in slots 0..batch-1 (ragged lengths).
  *   hidden      HOST array of `batch` device pointers, each [ctx_len[b]][d]

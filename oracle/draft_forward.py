@@ -6,6 +6,11 @@ the target model", App. B) under a strictly causal mask (Sec. 3.1) -> final norm
 -> LM head.  K logit rows are read out: row 0 from the last prefix position, rows
 1..K-1 from the mask positions ("shifted logits", Sec. 3.2).
 
+`draft_forward` starts from the fused prefix representation z (width d);
+`draft_forward_features` starts one step earlier, from the target model's raw outputs:
+three concatenated hidden states through the FC layer, plus shifted token embeddings
+(Sec. 3.2 "Draft model architecture").
+
 Everything is fp64 numpy; stored bf16 / fp32 inputs are widened exactly first.
 No blocking, caching or fusion: all T = n+K-1 rows go through K/V projection,
 and attention is a per-query loop over the keys that query may see.
@@ -104,6 +109,58 @@ def draft_forward(cfg, weights: dict, hidden: np.ndarray, K: int,
         logits[:, r0:r0 + step] = f @ widen(weights["w_lm"][r0:r0 + step]).T
     if return_intermediates:
         return logits, {"a": a, "q": q, "k": k, "v": v, "o": o, "y": y, "b": b, "u": u, "f": f}
+    return logits
+
+
+def draft_forward_features(cfg, weights: dict, features: np.ndarray, next_tokens: np.ndarray,
+                           K: int, return_intermediates: bool = False):
+    """Logits [K][vocab] (fp64) from the target model's raw outputs (Sec. 3.2, Fig. 3, App. B).
+
+    features [n][feat_dim]: the hidden states of three target layers, concatenated per
+    position.  next_tokens [n]: the token that follows each prefix position (the last one is
+    the freshly sampled t_{n+1}).  Steps, in the paper's order:
+      g = FC(features)                         (output width d, App. B "Trainable parameters")
+      e = Embedding(next_tokens)               (shifted token embeddings e_{2:n+1}, frozen table)
+      z = [g ; e]                              (concatenated along the feature dimension)
+      input sequence [z_1..z_n, MASK x (K-1)]  (a mask slot is a trainable 2d-wide row)
+    The decoder layer takes the 2d-wide rows as attention input, each half under its own
+    RMSNorm, and carries the g half as its residual stream; from the attention output on it
+    is the layer of `draft_forward`.
+    """
+    Hq, Hkv, hd, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d
+    W = {name: widen(a) for name, a in weights.items() if name not in ("w_lm", "embed")}
+    F = widen(features)
+    n = F.shape[0]
+    g = F @ W["w_fc"].T                                                  # [n][d]
+    e = widen(weights["embed"][np.asarray(next_tokens, dtype=np.int64)])  # [n][d]
+    z = np.concatenate([g, e], axis=1)                                   # [n][2d]
+    S = np.concatenate([z, W["mask_emb"][: K - 1]], axis=0)             # [T][2d]
+    T = n + K - 1
+    rows = np.arange(n - 1, T)
+
+    a = np.concatenate([rms_norm(S[:, :d], W["w_in_norm"], cfg.rms_eps),
+                        rms_norm(S[:, d:], W["w_emb_norm"], cfg.rms_eps)], axis=1)
+    k = (a @ W["wk"].T).reshape(T, Hkv, hd)
+    v = (a @ W["wv"].T).reshape(T, Hkv, hd)
+    q = (a[rows] @ W["wq"].T).reshape(K, Hq, hd)
+    if cfg.qk_norm:
+        q = rms_norm(q, W["q_norm"], cfg.rms_eps)
+        k = rms_norm(k, W["k_norm"], cfg.rms_eps)
+    q = rope(q, rows, cfg.rope_base)
+    k = rope(k, np.arange(T), cfg.rope_base)
+
+    o = attention_rows(q, k, v, rows).reshape(K, Hq * hd)
+    y = S[rows, :d] + o @ W["wo"].T
+    b = rms_norm(y, W["w_post_norm"], cfg.rms_eps)
+    u = y + (silu(b @ W["w_gate"].T) * (b @ W["w_up"].T)) @ W["w_down"].T
+    f = rms_norm(u, W["w_final_norm"], cfg.rms_eps)
+
+    logits = np.empty((K, cfg.vocab), dtype=np.float64)
+    step = 8192
+    for r0 in range(0, cfg.vocab, step):
+        logits[:, r0:r0 + step] = f @ widen(weights["w_lm"][r0:r0 + step]).T
+    if return_intermediates:
+        return logits, {"g": g, "a": a, "o": o, "y": y, "u": u, "f": f}
     return logits
 
 

@@ -12,6 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
+    "dart_draft_forward_features",
     "dart_draft_forward_batched", "dart_topk", "dart_ngram_create", "dart_ngram_destroy",
     "dart_tree_prune", "dart_tree_verify_greedy", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
 )
@@ -28,11 +29,13 @@ class DartError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab",
                                          "max_ctx", "max_K", "max_batch", "dtype", "qk_norm")] + \
-               [("rms_eps", C.c_float), ("rope_base", C.c_float)]
+               [("rms_eps", C.c_float), ("rope_base", C.c_float), ("front_end", C.c_int32),
+                ("feat_dim", C.c_int32)]
 
 
 _WEIGHT_FIELDS = ("w_in_norm", "wq", "wk", "wv", "q_norm", "k_norm", "wo", "w_post_norm",
-                  "w_gate", "w_up", "w_down", "w_final_norm", "w_lm", "mask_emb")
+                  "w_gate", "w_up", "w_down", "w_final_norm", "w_lm", "mask_emb",
+                  "w_fc", "embed", "w_emb_norm")
 
 
 class _Weights(C.Structure):
@@ -79,6 +82,7 @@ def load_library() -> C.CDLL:
     lib.dart_destroy.restype = None
     lib.dart_reset.argtypes = [vp, i32]
     lib.dart_draft_forward.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
+    lib.dart_draft_forward_features.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
     lib.dart_draft_forward_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
                                                C.POINTER(C.c_int32), i32, vp, vp]
     lib.dart_topk.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp]
@@ -129,7 +133,7 @@ class DraftContext:
     """dart_ctx: device weights, draft K/V buffers and workspaces of one draft layer."""
 
     def __init__(self, cfg, weights: dict, max_ctx: int | None = None, max_K: int | None = None,
-                 max_batch: int | None = None):
+                 max_batch: int | None = None, feat_dim: int = 0):
         lib = load_library()
         self.dtype = DART_BF16 if cfg.dtype == "bf16" else DART_F32
         self.vocab, self.d = int(cfg.vocab), int(cfg.d)
@@ -139,7 +143,8 @@ class DraftContext:
         c = _Config(d=cfg.d, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
                     head_dim=cfg.head_dim, ffn=cfg.ffn, vocab=cfg.vocab, max_ctx=self.max_ctx,
                     max_K=self.max_K, max_batch=self.max_batch, dtype=self.dtype,
-                    qk_norm=int(bool(cfg.qk_norm)), rms_eps=cfg.rms_eps, rope_base=cfg.rope_base)
+                    qk_norm=int(bool(cfg.qk_norm)), rms_eps=cfg.rms_eps, rope_base=cfg.rope_base,
+                    front_end=int(feat_dim > 0), feat_dim=int(feat_dim))
         want = np.uint16 if self.dtype == DART_BF16 else np.float32
         keep, w = [], _Weights()
         for name in _WEIGHT_FIELDS:
@@ -176,6 +181,19 @@ class DraftContext:
         _check(self._lib.dart_draft_forward(self._h, seq, hidden.data_ptr(), ctx_len, n_cached, K,
                                             out.data_ptr(), _stream_ptr(stream)),
                "dart_draft_forward")
+        return out
+
+    def draft_forward_features(self, features, next_tokens, ctx_len: int, K: int, n_cached: int = 0,
+                               seq: int = 0, out=None, stream=None):
+        """dart_draft_forward_features: features CUDA [>=ctx_len][feat_dim], next_tokens CUDA int32
+        [>=ctx_len]; returns logits [K][vocab]."""
+        torch = _torch()
+        if out is None:
+            out = torch.empty((K, self.vocab), dtype=torch.float32, device=features.device)
+        _check(self._lib.dart_draft_forward_features(self._h, seq, features.data_ptr(),
+                                                     next_tokens.data_ptr(), ctx_len, n_cached, K,
+                                                     out.data_ptr(), _stream_ptr(stream)),
+               "dart_draft_forward_features")
         return out
 
     def draft_forward_batched(self, hiddens, ctx_lens, n_cached, K: int, out=None, stream=None):

@@ -101,10 +101,11 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   const size_t es = elem_size(g.dtype);
   const int d = g.d, F = g.ffn, hd = g.head_dim;
 
-  RowSource qkv{{}, d};
-  add_rows(qkv, w->wq, c->q_dim, d, es);
-  add_rows(qkv, w->wk, c->kv_dim, d, es);
-  add_rows(qkv, w->wv, c->kv_dim, d, es);
+  const int in_dim = c->in_dim;            // attention input width: d, or 2d with the front end
+  RowSource qkv{{}, in_dim};
+  add_rows(qkv, w->wq, c->q_dim, in_dim, es);
+  add_rows(qkv, w->wk, c->kv_dim, in_dim, es);
+  add_rows(qkv, w->wv, c->kv_dim, in_dim, es);
   HIP_TRY(upload_matrix(g.dtype, qkv, &c->wqkv));
 
   RowSource wo{{}, c->q_dim};
@@ -142,7 +143,14 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     HIP_TRY(upload(w->q_norm, hd * es, &c->g_q));
     HIP_TRY(upload(w->k_norm, hd * es, &c->g_k));
   }
-  if (g.max_K > 1) HIP_TRY(upload(w->mask_emb, (size_t)(g.max_K - 1) * d * es, &c->mask_emb));
+  if (g.max_K > 1) HIP_TRY(upload(w->mask_emb, (size_t)(g.max_K - 1) * in_dim * es, &c->mask_emb));
+  if (g.front_end) {
+    RowSource fc{{}, g.feat_dim};
+    add_rows(fc, w->w_fc, d, g.feat_dim, es);
+    HIP_TRY(upload_matrix(g.dtype, fc, &c->wfc));
+    HIP_TRY(upload(w->embed, (size_t)g.vocab * d * es, &c->embed));
+    HIP_TRY(upload(w->w_emb_norm, d * es, &c->g_emb));
+  }
 
   // rotary tables: angle = position * base^(-2i/hd), evaluated in double
   const int half = hd / 2;
@@ -170,18 +178,20 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   int ch_qkv = 1, ch_o = 1, ch_gu = 1, ch_down = 1;      // k-chunks each projection writes
   c->kv_rows = R;
   if (g.dtype == DART_BF16) {
-    c->split_qkv = gemv_bf16_split(d, c->qkv_dim / 16);
+    c->split_qkv = gemv_bf16_split(in_dim, c->qkv_dim / 16);
+    if (g.front_end) c->split_fc = gemv_bf16_split(g.feat_dim, (d + 15) / 16);
     c->split_o = gemv_bf16_split(c->q_dim, (d + 15) / 16);
     c->split_gu = gemv_bf16_split(d, 2 * F / 16);
     c->split_down = gemv_bf16_split(F, (d + 15) / 16);
-    ch_qkv = gemv_bf16_chunks(d) * c->split_qkv;
+    ch_qkv = gemv_bf16_chunks(in_dim) * c->split_qkv;
     ch_o = gemv_bf16_chunks(c->q_dim) * c->split_o;
     ch_gu = gemv_bf16_chunks(d) * c->split_gu;
     ch_down = gemv_bf16_chunks(F) * c->split_down;
-    if (g.max_ctx > R && gemv_bf16_row_tiles(d, c->split_qkv) >= 4)
+    if (g.max_ctx > R && gemv_bf16_row_tiles(in_dim, c->split_qkv) >= 4 &&
+        (!g.front_end || gemv_bf16_row_tiles(g.feat_dim, c->split_fc) >= 4))
       c->kv_rows = std::min(1024, round_up(g.max_ctx, 64));
     if (g.max_batch > 1) {     // the batched entry point runs on the multi-row kernel
-      c->gch_qkv = gemm_bf16_chunks(d, c->qkv_dim / 16);
+      c->gch_qkv = gemm_bf16_chunks(in_dim, c->qkv_dim / 16);
       c->gch_o = gemm_bf16_chunks(c->q_dim, (d + 15) / 16);
       c->gch_gu = gemm_bf16_chunks(d, 2 * F / 16);
       c->gch_down = gemm_bf16_chunks(F, (d + 15) / 16);
@@ -206,7 +216,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
                            c->max_splits;
   const size_t proj_elems = std::max(std::max((size_t)ch_o * d, (size_t)ch_down * d),
                                      (size_t)ch_gu * 2 * F);
-  HIP_TRY(dev_alloc(&c->xn, W * d));
+  HIP_TRY(dev_alloc(&c->xn, W * in_dim));
   HIP_TRY(dev_alloc(&c->resid, W * d));
   HIP_TRY(dev_alloc(&c->qkv, (size_t)ch_qkv * W * c->qkv_dim));
   HIP_TRY(hipMalloc(&c->qrot, W * c->q_dim * 4));
@@ -219,11 +229,17 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   HIP_TRY(dev_alloc(&c->hmid, W * F));
   HIP_TRY(dev_alloc(&c->u, W * d));
   if (g.dtype == DART_BF16) {
-    size_t pb = gemm_bf16_pack_bytes(c->kv_rows, d);
-    for (int kd : {d, c->q_dim, F}) pb = std::max(pb, gemm_bf16_pack_bytes(c->ws_rows, kd));
+    size_t pb = gemm_bf16_pack_bytes(c->kv_rows, in_dim);
+    for (int kd : {in_dim, c->q_dim, F}) pb = std::max(pb, gemm_bf16_pack_bytes(c->ws_rows, kd));
     HIP_TRY(hipMalloc(&c->xpack, pb));
   }
-  HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * d));
+  HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * in_dim));
+  if (g.front_end) {
+    c->fc_rows = std::max(c->ws_rows, c->kv_rows);
+    const int ch_fc = g.dtype == DART_BF16 ? gemv_bf16_chunks(g.feat_dim) * c->split_fc : 1;
+    HIP_TRY(dev_alloc(&c->feat32, (size_t)c->fc_rows * g.feat_dim));
+    HIP_TRY(dev_alloc(&c->fc_part, (size_t)ch_fc * c->fc_rows * d));
+  }
   HIP_TRY(dev_alloc(&c->kv_part, (size_t)ch_qkv * c->kv_rows * 2 * c->kv_dim));
 
   c->max_rows = g.max_batch * g.max_K;
@@ -273,17 +289,36 @@ hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows
 // One sequence of a forward call.
 struct SeqJob {
   int slot;
-  const void *hidden;
+  const void *hidden;          // prefix representation, or the feature rows with the front end
   int n, n_cached;
+  const int32_t *tokens = nullptr;   // front end: token following each position
 };
+
+// Layer input of the rows of a pass: xn = normed attention input ([rows][in_dim]), resid = raw
+// residual rows of the query rows (may be null for a K/V-only pass).  Without the front end
+// the rows are gathered from the prefix representation / mask embeddings and normed; with it
+// (Sec. 3.2) the feature rows first go through the FC layer and are joined by the shifted
+// token embeddings.
+hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid, hipStream_t st) {
+  const dart_config &g = c->cfg;
+  if (!g.front_end)
+    return launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, xn, resid, st);
+  const int M = sb.row_off[sb.B];
+  HIP_TRY(launch_feature_rows(g.dtype, sb, g.feat_dim, c->feat32, st));
+  const size_t cs = (size_t)c->fc_rows * g.d;
+  int chunks = 1;
+  HIP_TRY(project(c, c->wfc, 0, g.d, c->feat32, M, c->fc_part, g.d, cs, c->split_fc, 0, &chunks, st));
+  return launch_front_norm(g.dtype, sb, c->fc_part, chunks, cs, c->embed, c->mask_emb, c->g_in,
+                           c->g_emb, g.d, g.rms_eps, xn, resid, st);
+}
 
 // K/V-only pass: norm + K and V projection + append for the rows described by sb (sb.K = 0,
 // at most kv_rows rows).
 hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int M = sb.row_off[sb.B];
-  HIP_TRY(launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, c->xn_kv,
-                                nullptr, st));
+  (void)g;
+  HIP_TRY(input_stage(c, sb, c->xn_kv, nullptr, st));
   const size_t cs = (size_t)c->kv_rows * 2 * c->kv_dim;
   int chunks = 1;
   HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn_kv, M, c->kv_part, 2 * c->kv_dim, cs,
@@ -318,6 +353,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
         const int take = std::min(room, jobs[b].n - 1 - r0);
         const int i = sb.B++;
         sb.hidden[i] = jobs[b].hidden;
+        sb.tokens[i] = jobs[b].tokens;
         sb.n[i] = jobs[b].n;
         sb.pos0[i] = r0;
         sb.slot[i] = jobs[b].slot;
@@ -334,6 +370,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   sb.K = K;
   for (int b = 0; b < B; ++b) {
     sb.hidden[b] = jobs[b].hidden;
+    sb.tokens[b] = jobs[b].tokens;
     sb.n[b] = jobs[b].n;
     sb.pos0[b] = combined ? jobs[b].n_cached : jobs[b].n - 1;
     sb.slot[b] = jobs[b].slot;
@@ -341,8 +378,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   }
   const int M = sb.row_off[B], QR = B * K;       // pass rows, query rows
   const size_t W = c->ws_rows;
-  HIP_TRY(launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, c->xn, c->resid,
-                                st));
+  HIP_TRY(input_stage(c, sb, c->xn, c->resid, st));
   int chunks = 1;
   size_t cs = W * c->qkv_dim;
   HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv,
@@ -410,6 +446,13 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
   if (g.n_q_heads % g.n_kv_heads != 0 || g.n_q_heads / g.n_kv_heads > 8) return DART_ERR_ARG;
   if (g.dtype != DART_F32 && g.dtype != DART_BF16) return DART_ERR_ARG;
   const int q_dim = g.n_q_heads * g.head_dim;
+  if (g.front_end != 0 && g.front_end != 1) return DART_ERR_ARG;
+  if (g.front_end) {
+    if (g.feat_dim < 8 || g.feat_dim > 16384 || g.feat_dim % (g.dtype == DART_BF16 ? 32 : 8) ||
+        2 * g.d > 16384)
+      return DART_ERR_ARG;
+    if (!w->w_fc || !w->embed || !w->w_emb_norm) return DART_ERR_ARG;
+  }
   if (g.dtype == DART_BF16) {
     if (g.d % 32 || q_dim % 32 || g.ffn % 32) return DART_ERR_ARG;
     if (gemv_bf16_chunks(g.d) != 1) return DART_ERR_ARG;   // LM head writes caller memory in one pass
@@ -427,6 +470,7 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
   dart_ctx *c = new (std::nothrow) dart_ctx();
   if (!c) return DART_ERR_OOM;
   c->cfg = g;
+  c->in_dim = g.front_end ? 2 * g.d : g.d;
   c->q_dim = q_dim;
   c->kv_dim = g.n_kv_heads * g.head_dim;
   c->qkv_dim = c->q_dim + 2 * c->kv_dim;
@@ -453,7 +497,8 @@ void dart_destroy(dart_ctx *c) {
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms, c->topk_count,
-                  c->xn_kv, c->kv_part, c->xpack};
+                  c->xn_kv, c->kv_part, c->xpack, c->wfc.data, c->embed, c->g_emb, c->feat32,
+                  c->fc_part};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
   free(c->cached_rows);
@@ -466,10 +511,27 @@ dart_status dart_reset(dart_ctx *c, int seq) {
   return DART_OK;
 }
 
+dart_status dart_draft_forward_features(dart_ctx *c, int seq, const void *features,
+                                        const int32_t *next_tokens, int ctx_len, int n_cached,
+                                        int K, float *logits_out, void *stream) {
+  dart_status s = check_forward_args(c, seq, features, ctx_len, n_cached, K, logits_out);
+  if (s != DART_OK) return s;
+  if (!next_tokens) return DART_ERR_ARG;
+  if (!c->cfg.front_end) return DART_ERR_STATE;
+  SeqJob job{seq, features, ctx_len, n_cached};
+  job.tokens = next_tokens;
+  c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
+  hipError_t e = forward_group(c, 1, &job, K, false, logits_out, (hipStream_t)stream);
+  if (e != hipSuccess) return from_hip(e);
+  c->cached_rows[seq] = ctx_len;
+  return DART_OK;
+}
+
 dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx_len, int n_cached,
                                int K, float *logits_out, void *stream) {
   dart_status s = check_forward_args(c, seq, hidden, ctx_len, n_cached, K, logits_out);
   if (s != DART_OK) return s;
+  if (c->cfg.front_end) return DART_ERR_STATE;
   const SeqJob job{seq, hidden, ctx_len, n_cached};
   c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
   hipError_t e = forward_group(c, 1, &job, K, false, logits_out, (hipStream_t)stream);
@@ -483,6 +545,7 @@ dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const
                                        float *logits_out, void *stream) {
   if (!c || !hidden || !ctx_len || !n_cached || !logits_out) return DART_ERR_ARG;
   if (batch < 1 || batch > c->cfg.max_batch) return DART_ERR_ARG;
+  if (c->cfg.front_end) return DART_ERR_STATE;
   for (int b = 0; b < batch; ++b) {
     dart_status s = check_forward_args(c, b, hidden[b], ctx_len[b], n_cached[b], K, logits_out);
     if (s != DART_OK) return s;

@@ -55,7 +55,9 @@ struct PruneLevelWeights {
 #define DART_SEQ_GROUP 16
 struct SeqBatch {
   int B, K;
-  const void *hidden[DART_SEQ_GROUP];   // [n][d] prefix representation of the sequence
+  const void *hidden[DART_SEQ_GROUP];   // [n][d] prefix representation of the sequence (front end:
+                                        // [n][feat_dim] concatenated target hidden states)
+  const int32_t *tokens[DART_SEQ_GROUP];  // front end: [n] token following each position
   int n[DART_SEQ_GROUP];                // prefix length
   int pos0[DART_SEQ_GROUP];             // first position of the sequence's rows in this pass
   int row_off[DART_SEQ_GROUP + 1];
@@ -88,6 +90,14 @@ struct dart_ctx {
   DeviceMatrix wqkv, wo, wgu, wdown, wlm;   // wgu: gate and up rows interleaved (see dart_api.hip)
   void *g_in = nullptr, *g_post = nullptr, *g_final = nullptr, *g_q = nullptr, *g_k = nullptr;
   void *mask_emb = nullptr;
+  // front end (cfg.front_end): FC layer, frozen embedding table, gain of the embedding half;
+  // in_dim = width of the layer's attention input (d, or 2d with the front end)
+  int in_dim = 0;
+  DeviceMatrix wfc;
+  void *embed = nullptr, *g_emb = nullptr;
+  float *feat32 = nullptr;        // [max(ws_rows, kv_rows)][feat_dim] features of a pass as fp32
+  float *fc_part = nullptr;       // [chunks][max(ws_rows, kv_rows)][d] FC partial sums
+  int split_fc = 1, fc_rows = 0;
   float *rope_cos = nullptr, *rope_sin = nullptr;   // [t_cap][hd/2]
   // draft K/V buffers: K [batch][Hkv][t_cap][hd]; V fp32 same, bf16 transposed [batch][Hkv][hd][t_cap] (attn_vt_position order)
   void *kbuf = nullptr, *vbuf = nullptr;
@@ -139,6 +149,16 @@ extern int g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, 
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
                                  const void *gain, int d, float eps, float *xn, float *resid,
                                  hipStream_t st);
+
+// Front end, step 1: the feature rows of a pass as fp32 (mask rows: zeros).
+hipError_t launch_feature_rows(int dtype, const SeqBatch &sb, int feat_dim, float *out, hipStream_t st);
+// Front end, step 2: per pass row, g = sum of the FC partials (prefix rows) and e = embedding
+// of the row's next token, or the two halves of a mask slot; xn[r] = [RMSNorm(g) * gain_g ;
+// RMSNorm(e) * gain_e] (2d wide), resid (query rows) = g.
+hipError_t launch_front_norm(int dtype, const SeqBatch &sb, const float *fc_part, int chunks,
+                             size_t chunk_stride, const void *embed, const void *mask_emb,
+                             const void *gain_g, const void *gain_e, int d, float eps, float *xn,
+                             float *resid, hipStream_t st);
 
 hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,

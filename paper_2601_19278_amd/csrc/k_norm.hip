@@ -72,6 +72,91 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
   }
 }
 
+// Front end (Sec. 3.2): the concatenated target hidden states of the pass rows as fp32, the
+// input format of the FC projection.  Mask rows have no features: zeros (their FC output is
+// not used).  One workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void feature_rows_kernel(SeqBatch sb, int feat_dim,
+                                                                   float *__restrict__ out) {
+  const int i = blockIdx.x;
+  int b, pos, qi;
+  seq_of_row(sb, i, b, pos, qi);
+  const bool prefix = pos < sb.n[b];
+  const T *src = (const T *)sb.hidden[b] + (size_t)(prefix ? pos : 0) * feat_dim;
+  for (int c = threadIdx.x * 8; c < feat_dim; c += ROW_THREADS * 8) {
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (prefix) load8(src + c, v);
+    store8(out + (size_t)i * feat_dim + c, v);
+  }
+}
+
+// Front end (Sec. 3.2): z = [g ; e] of a pass row -- g = FC output (sum of the projection's
+// k-chunk partials, in index order), e = embedding of the token that follows the position
+// (shifted embeddings); a mask row takes both halves from its 2d-wide mask slot.  Each half
+// gets its own RMSNorm; xn[r] = [norm(g) * gain_g ; norm(e) * gain_e], and the g half is the
+// layer's residual stream (written for query rows).  One workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void front_norm_kernel(
+    SeqBatch sb, const float *__restrict__ fc_part, int chunks, size_t chunk_stride,
+    const T *__restrict__ embed, const T *__restrict__ mask_emb, const T *__restrict__ gain_g,
+    const T *__restrict__ gain_e, int d, float eps, float *__restrict__ xn,
+    float *__restrict__ resid) {
+  __shared__ float red[16];
+  const int i = blockIdx.x;
+  int b, pos, qi;
+  seq_of_row(sb, i, b, pos, qi);
+  const int n = sb.n[b];
+  const bool prefix = pos < n;
+  const T *mrow = mask_emb + (size_t)(prefix ? 0 : pos - n) * 2 * d;
+  const T *erow = prefix ? embed + (size_t)sb.tokens[b][pos] * d : mrow + d;
+  float g[ROW_MAXIT][8], e[ROW_MAXIT][8];
+  float sg = 0.f, se = 0.f;
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) {
+      if (prefix) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) g[j][q] = 0.f;
+        for (int k = 0; k < chunks; ++k) {
+          float p[8];
+          load8(fc_part + k * chunk_stride + (size_t)i * d + c, p);
+#pragma unroll
+          for (int q = 0; q < 8; ++q) g[j][q] += p[q];
+        }
+      } else {
+        load8(mrow + c, g[j]);
+      }
+      load8(erow + c, e[j]);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        sg += g[j][q] * g[j][q];
+        se += e[j][q] * e[j][q];
+      }
+    }
+  }
+  sg = block_sum(sg, red);
+  se = block_sum(se, red);
+  const float rg = 1.0f / sqrtf(sg / (float)d + eps), re = 1.0f / sqrtf(se / (float)d + eps);
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) {
+      float wg[8], we[8];
+      load8(gain_g + c, wg);
+      load8(gain_e + c, we);
+      if (qi >= 0) store8(resid + (size_t)(b * sb.K + qi) * d + c, g[j]);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        g[j][q] = g[j][q] * rg * wg[q];
+        e[j][q] = e[j][q] * re * we[q];
+      }
+      store8(xn + (size_t)i * 2 * d + c, g[j]);
+      store8(xn + (size_t)i * 2 * d + d + c, e[j]);
+    }
+  }
+}
+
 // y = resid + sum_c part[c];  yn = RMSNorm(y) * gain.  part[c] row r starts at
 // part + c*chunk_stride + r*row_stride.  Chunk partials are added in index order.
 template <typename T>
@@ -159,6 +244,31 @@ hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask
   else
     hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st, sb,
                        (const float *)mask_emb, (const float *)gain, d, eps, xn, resid);
+  return hipGetLastError();
+}
+
+hipError_t launch_feature_rows(int dtype, const SeqBatch &sb, int feat_dim, float *out, hipStream_t st) {
+  const int M = sb.row_off[sb.B];
+  if (dtype == DART_BF16)
+    hipLaunchKernelGGL(feature_rows_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, sb, feat_dim, out);
+  else
+    hipLaunchKernelGGL(feature_rows_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st, sb, feat_dim, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_front_norm(int dtype, const SeqBatch &sb, const float *fc_part, int chunks,
+                             size_t chunk_stride, const void *embed, const void *mask_emb,
+                             const void *gain_g, const void *gain_e, int d, float eps, float *xn,
+                             float *resid, hipStream_t st) {
+  const int M = sb.row_off[sb.B];
+  if (dtype == DART_BF16)
+    hipLaunchKernelGGL(front_norm_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, sb, fc_part,
+                       chunks, chunk_stride, (const bf16_t *)embed, (const bf16_t *)mask_emb,
+                       (const bf16_t *)gain_g, (const bf16_t *)gain_e, d, eps, xn, resid);
+  else
+    hipLaunchKernelGGL(front_norm_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st, sb, fc_part,
+                       chunks, chunk_stride, (const float *)embed, (const float *)mask_emb,
+                       (const float *)gain_g, (const float *)gain_e, d, eps, xn, resid);
   return hipGetLastError();
 }
 
