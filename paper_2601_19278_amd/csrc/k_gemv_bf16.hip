@@ -37,7 +37,9 @@ int gemv_bf16_chunks(int Kd) {
 }
 
 // Tunables (fixed after measurement; the benchmark harness may override them).
-int g_gemv_wgs = 256;      // workgroups per k-chunk group: one per CU
+int g_gemv_wgs = 184;      // resident workgroups.  Fewer than the 256 compute units on purpose: measured on
+                           // MI355X the weight stream peaks at 176-192 workgroups (LM head 6.6 TB/s against
+                           // 6.2 TB/s with one per compute unit; 160 and fewer fall off again)
 int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
 int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
 int g_gemv_nt_min_mb = 100;  // ... for matrices (strip ranges) of at least this many MiB: smaller ones
