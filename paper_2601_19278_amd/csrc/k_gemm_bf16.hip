@@ -282,10 +282,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int gc_count = a.ngroups * a.nchunks;
   for (int unit = blockIdx.x; unit < a.units; unit += gridDim.x) {
     // row blocks of one (group, chunk) sit 8 units apart: same XCD, about the same time, so
-    // the second reader of a weight tile finds it in that XCD's L2
+    // the second reader of a weight tile finds it in that XCD's L2.
+    // Units are dealt to the 8 XCDs round-robin (unit u runs on XCD u % 8): XCD x owns a
+    // contiguous eighth of the (group, chunk) pairs, so that each L2 streams one region.
     const int blk = unit / (8 * a.row_blocks), within = unit % (8 * a.row_blocks);
-    const int rb = within / 8, gc = blk * 8 + within % 8;
-    if (gc >= gc_count) continue;
+    const int rb = within / 8, x = within % 8, per_x = (gc_count + 7) / 8;
+    const int gc = x * per_x + blk;
+    if (blk >= per_x || gc >= gc_count) continue;
     const int group = gc / a.nchunks, chunk = gc % a.nchunks;
     const int g0 = (int)((int64_t)a.nstrips * group / a.ngroups);
     const int g1 = (int)((int64_t)a.nstrips * (group + 1) / a.ngroups);

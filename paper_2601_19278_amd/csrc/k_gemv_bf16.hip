@@ -40,6 +40,7 @@ int gemv_bf16_chunks(int Kd) {
 int g_gemv_wgs = 184;      // resident workgroups.  Fewer than the 256 compute units on purpose: measured on
                            // MI355X the weight stream peaks at 176-192 workgroups (LM head 6.6 TB/s against
                            // 6.2 TB/s with one per compute unit; 160 and fewer fall off again)
+int g_gemv_xcd = 2;        // strip-to-XCD assignment, see the kernel
 int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
 int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
 int g_gemv_nt_min_mb = 100;  // ... for matrices (strip ranges) of at least this many MiB: smaller ones
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
     const u32x4_t *__restrict__ Wp, // packed tiles, 64 x 16 bytes per tile
     const float *__restrict__ X,    // [M][Kd]
     int M, int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols,
-    float *__restrict__ out, int out_stride, size_t chunk_stride) {
+    float *__restrict__ out, int out_stride, size_t chunk_stride, int xcd_map) {
   static_assert(KPW % D == 0, "a register of the rolling buffer must serve the same slots in every strip");
   constexpr bool M8 = MT == 0;
   constexpr int NMT = M8 ? 1 : MT;                     // column tiles
@@ -91,7 +92,22 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, gq = lane >> 4;
   const int chunk = blockIdx.x % nchunks;
-  const int wg = blockIdx.x / nchunks, nwg = gridDim.x / nchunks;
+  const int nwg = gridDim.x / nchunks;
+  int wg = blockIdx.x / nchunks;
+  // Strip assignment.  Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on
+  // XCD i % 8, each with its own L2 and its own path to memory).  xcd_map 2: every XCD owns a
+  // contiguous eighth of the strips and its workgroups stride through it; 1: the workgroups of
+  // an XCD take adjacent strips of every round; 0: strips dealt in launch order.  Measured on
+  // the LM head (184 workgroups): 235 / 228 / 227 us for modes 0 / 1 / 2.
+  int s_step = nwg, s_end = nstrips;
+  if (nchunks > 1) xcd_map = 0;            // (with k-chunks a workgroup's XCD is not wg % 8)
+  if (xcd_map == 1 && nwg % 8 == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+  if (xcd_map == 2 && nwg % 8 == 0) {
+    const int per_x = (nstrips + 7) / 8, x = wg & 7;
+    s_step = nwg >> 3;
+    s_end = min(nstrips, (x + 1) * per_x);
+    wg = x * per_x + (wg >> 3);
+  }
   const int ks0 = (chunk * GEMV_WAVES + wave) * kpw;
   const int nk = EXACT ? KPW : max(0, min(kpw, KT - ks0));   // wave-uniform
   const int Kd = KT * 32;
@@ -108,7 +124,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   // stream is already running during that set-up.
   u32x4_t aop[D];
   int s = wg;                                          // strip index relative to strip0
-  if (s < nstrips) {
+  if (s < s_end) {
     const u32x4_t *tile = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
 #pragma unroll
     for (int r = 0; r < D; ++r)
@@ -147,10 +163,10 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   }
 
   int buf = 0;
-  for (; s < nstrips; s += nwg) {
-    const int sn = s + nwg;
+  for (; s < s_end; s += s_step) {
+    const int sn = s + s_step;
     const u32x4_t *cur = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
-    const u32x4_t *next = Wp + ((size_t)(strip0 + (sn < nstrips ? sn : s)) * KT + ks0) * 64 + lane;
+    const u32x4_t *next = Wp + ((size_t)(strip0 + (sn < s_end ? sn : s)) * KT + ks0) * 64 + lane;
     f32x4_t acc[NACC];
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[i] = {0.f, 0.f, 0.f, 0.f};
@@ -206,7 +222,7 @@ static void gemv_launch(bool nt, int mt, dim3 grid, hipStream_t st, const u32x4_
 #define DART_GEMV_GO(MT_, NT_)                                                                    \
   hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, MT_, NT_, EXACT>), grid, dim3(GEMV_THREADS), 0, st, \
                      wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,         \
-                     chunk_stride)
+                     chunk_stride, g_gemv_xcd)
   if constexpr (KPW <= 5) {                            // the row-block variants need short k-slices
     if (mt == 4) { if (nt) DART_GEMV_GO(4, true); else DART_GEMV_GO(4, false); return; }
     if (mt == 2) { if (nt) DART_GEMV_GO(2, true); else DART_GEMV_GO(2, false); return; }
