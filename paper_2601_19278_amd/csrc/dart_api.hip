@@ -689,6 +689,7 @@ int dart_debug_set(const char *name, int value) {
   if (!strcmp(name, "gemv_wgs")) g_gemv_wgs = value;
   else if (!strcmp(name, "gemv_depth")) g_gemv_depth = value;
   else if (!strcmp(name, "gemv_xcd")) g_gemv_xcd = value;
+  else if (!strcmp(name, "gemv_wgs_split")) g_gemv_wgs_split = value;
   else if (!strcmp(name, "gemv_nt")) g_gemv_nt = value;
   else if (!strcmp(name, "gemv_nt_min_mb")) g_gemv_nt_min_mb = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;

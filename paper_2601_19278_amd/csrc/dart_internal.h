@@ -142,7 +142,7 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 }
 
 // Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_xcd, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs;
+extern int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs;
 
 // All launchers only enqueue work on `st` and return the launch status.
 

@@ -40,6 +40,7 @@ int gemv_bf16_chunks(int Kd) {
 int g_gemv_wgs = 184;      // resident workgroups.  Fewer than the 256 compute units on purpose: measured on
                            // MI355X the weight stream peaks at 176-192 workgroups (LM head 6.6 TB/s against
                            // 6.2 TB/s with one per compute unit; 160 and fewer fall off again)
+int g_gemv_wgs_split = 224;  // the same for matrices whose k range is cut into chunks (QKV, O, MLP): best at 216-232
 int g_gemv_xcd = 2;        // strip-to-XCD assignment, see the kernel
 int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
 int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
@@ -94,19 +95,21 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   const int chunk = blockIdx.x % nchunks;
   const int nwg = gridDim.x / nchunks;
   int wg = blockIdx.x / nchunks;
-  // Strip assignment.  Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on
-  // XCD i % 8, each with its own L2 and its own path to memory).  xcd_map 2: every XCD owns a
-  // contiguous eighth of the strips and its workgroups stride through it; 1: the workgroups of
-  // an XCD take adjacent strips of every round; 0: strips dealt in launch order.  Measured on
-  // the LM head (184 workgroups): 235 / 228 / 227 us for modes 0 / 1 / 2.
+  // Strip assignment.  Workgroups are dealt to the 8 XCDs round-robin (block i runs on XCD
+  // i % 8, each with its own L2 and its own path to memory); block = wg * nchunks + chunk, so
+  // the workgroups of one k-chunk fall into ncls = 8 / gcd(8, nchunks) classes (wg % ncls)
+  // that share an XCD.  xcd_map 2: every class owns a contiguous 1/ncls of the strips and its
+  // workgroups stride through it; 1: the workgroups of a class take adjacent strips of every
+  // round; 0: strips dealt in launch order.  Measured on the LM head (184 workgroups, one
+  // chunk): 235 / 228 / 227 us for modes 0 / 1 / 2.
   int s_step = nwg, s_end = nstrips;
-  if (nchunks > 1) xcd_map = 0;            // (with k-chunks a workgroup's XCD is not wg % 8)
-  if (xcd_map == 1 && nwg % 8 == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
-  if (xcd_map == 2 && nwg % 8 == 0) {
-    const int per_x = (nstrips + 7) / 8, x = wg & 7;
-    s_step = nwg >> 3;
+  const int ncls = (nchunks & 1) ? 8 : ((nchunks & 2) ? 4 : ((nchunks & 4) ? 2 : 1));
+  if (xcd_map == 1 && nwg % ncls == 0) wg = (wg % ncls) * (nwg / ncls) + wg / ncls;
+  if (xcd_map == 2 && nwg % ncls == 0) {
+    const int per_x = (nstrips + ncls - 1) / ncls, x = wg % ncls;
+    s_step = nwg / ncls;
     s_end = min(nstrips, (x + 1) * per_x);
-    wg = x * per_x + (wg >> 3);
+    wg = x * per_x + wg / ncls;
   }
   const int ks0 = (chunk * GEMV_WAVES + wave) * kpw;
   const int nk = EXACT ? KPW : max(0, min(kpw, KT - ks0));   // wave-uniform
@@ -256,7 +259,7 @@ int gemv_bf16_split(int Kd, int nstrips) {
     return KT % (GEMV_WAVES * nch) == 0 && exact_kpw_supported(KT / (GEMV_WAVES * nch));
   };
   if (g_gemv_split > 0) return valid(g_gemv_split) ? g_gemv_split : 1;
-  const int wgs_base = max(1, min(g_gemv_wgs / base, nstrips));
+  const int wgs_base = max(1, min(g_gemv_wgs_split / base, nstrips));
   if (nstrips / wgs_base >= 12) return 1;
   for (int split = 4; split > 1; split /= 2)
     if (valid(split) && KT / (GEMV_WAVES * base * split) >= 4) return split;
@@ -292,7 +295,7 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
     mt = M > 32 ? 4 : 2;
     row_blocks = (M + 16 * mt - 1) / (16 * mt);
   }
-  int wgs = g_gemv_wgs / (nchunks * row_blocks);
+  int wgs = (nchunks == 1 ? g_gemv_wgs : g_gemv_wgs_split) / (nchunks * row_blocks);
   if (wgs > nstrips) wgs = nstrips;
   if (wgs < 1) wgs = 1;
   dim3 grid(wgs * nchunks, row_blocks);
