@@ -245,7 +245,7 @@ dart_status dart_debug_lm_head(dart_ctx *ctx, int rows, int multi_row, float *lo
                                void *stream);
 
 /* Diagnostic (benchmark sweeps only): override a launch tunable of the kernels by name
- * ("gemv_wgs", "gemv_xcd", "gemv_depth", "gemv_nt", "gemv_nt_min_mb", "gemv_split", "gemm_wgs").  Process-wide,
+ * ("gemv_wgs", "gemv_xcd", "gemv_depth", "gemv_nt", "gemv_nt_min_mb", "gemv_split", "gemm_wgs", "attn_seg").  Process-wide,
  * not thread-safe.  Returns 0, or -1 for an unknown name. */
 int dart_debug_set(const char *name, int value);
 

@@ -15,6 +15,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 
+# The attention kernel rescales its MFMA accumulators after every key block (running soft-max):
+# keep them in ordinary VGPRs, where the multiply needs no copies to and from the accumulation
+# registers (the kernel is far from the register limit).
+PER_FILE = {"k_attn_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
 
 def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
@@ -25,7 +30,7 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
 
     def compile_one(name: str) -> str:
         obj = os.path.join(OBJ, name[:-4] + ".o")
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, name), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *PER_FILE.get(name, []), "-c", os.path.join(CSRC, name), "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         noise = "is not a recognized feature for this target"
         err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)

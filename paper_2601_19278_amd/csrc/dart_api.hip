@@ -694,6 +694,7 @@ int dart_debug_set(const char *name, int value) {
   else if (!strcmp(name, "gemv_nt_min_mb")) g_gemv_nt_min_mb = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
   else if (!strcmp(name, "gemm_wgs")) g_gemm_wgs = value < 1 ? 1 : value;
+  else if (!strcmp(name, "attn_seg")) g_attn_seg = value < 0 ? 0 : (value > 64 ? 64 : value);
   else return -1;
   return 0;
 }

@@ -82,6 +82,36 @@ __host__ __device__ inline int attn_vt_position(int pos) {
   return (pos & ~31) | (8 * ((x & 15) >> 2) + 4 * (x >> 4) + (x & 3));
 }
 
+// bf16 configuration: K and V^T of one (sequence, head) are stored chunk by chunk
+// (ATTN_KEY_CHUNK keys) as the 1 KiB MFMA operand tiles the attention kernel copies to LDS, so
+// that a tile copy reads 1 KiB of contiguous memory and a chunk is one contiguous block.
+// K tile (kt, ks) of a chunk, tile index kt*(hd/32)+ks: 16 keys x 32 dims; lane (gq, col) holds
+// dims 32ks+8gq..+7 of key 16kt+col.
+__host__ __device__ inline size_t attn_k_index(int pos, int dim, int hd) {
+  const int p = pos % ATTN_KEY_CHUNK;
+  const int tile = (p / 16) * (hd / 32) + dim / 32;
+  const int lane = ((dim % 32) / 8) * 16 + p % 16;
+  return (size_t)(pos / ATTN_KEY_CHUNK) * ATTN_KEY_CHUNK * hd + ((size_t)tile * 64 + lane) * 8 + dim % 8;
+}
+// V^T tile (dt, blk), tile index dt*(ATTN_KEY_CHUNK/32)+blk: 16 dims x 32 keys; lane (gq, col)
+// holds the keys stored at places 8gq..+7 of the block (attn_vt_position) for dim 16dt+col.
+__host__ __device__ inline size_t attn_vt_index(int pos, int dim, int hd) {
+  const int x = attn_vt_position(pos) & 31;
+  const int tile = (dim / 16) * (ATTN_KEY_CHUNK / 32) + (pos % ATTN_KEY_CHUNK) / 32;
+  const int lane = (x / 8) * 16 + dim % 16;
+  return (size_t)(pos / ATTN_KEY_CHUNK) * ATTN_KEY_CHUNK * hd + ((size_t)tile * 64 + lane) * 8 + x % 8;
+}
+
+// Unit list of an attention launch (bf16 path).  A unit is one (sequence, K/V head, key chunk);
+// units are numbered sequence-major, then head, then chunk: sequence b has cum[b+1] - cum[b]
+// chunks per head and its units start at cum[b] * Hkv.  Workgroup w takes units
+// [w * per, (w+1) * per); the partial it writes for a (sequence, head) pair is numbered
+// w - (first unit of the pair) / per.
+struct AttnWork {
+  int cum[DART_SEQ_GROUP + 1];
+  int per;
+};
+
 struct dart_ctx {
   dart_config cfg;
   int q_dim, kv_dim, qkv_dim;
@@ -99,7 +129,7 @@ struct dart_ctx {
   float *fc_part = nullptr;       // [chunks][max(ws_rows, kv_rows)][d] FC partial sums
   int split_fc = 1, fc_rows = 0;
   float *rope_cos = nullptr, *rope_sin = nullptr;   // [t_cap][hd/2]
-  // draft K/V buffers: K [batch][Hkv][t_cap][hd]; V fp32 same, bf16 transposed [batch][Hkv][hd][t_cap] (attn_vt_position order)
+  // draft K/V buffers [batch][Hkv][t_cap * hd]: fp32 rows [t_cap][hd]; bf16 operand tiles (attn_k_index, attn_vt_index)
   void *kbuf = nullptr, *vbuf = nullptr;
   int *cached_rows = nullptr;     // host, [max_batch]
   // activations / workspaces (device, fp32 unless noted); ws_rows = rows one pass may carry
@@ -142,7 +172,7 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 }
 
 // Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs;
+extern int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs, g_attn_seg;
 
 // All launchers only enqueue work on `st` and return the launch status.
 

@@ -55,15 +55,15 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
   }
 }
 
-// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s over the partials that hold keys of
-// the query's sequence (ceil((n + K - 1) / chunk) splits of nsub sub-ranges each, out of the
-// nsplit slots of the query vector).  A split with l == 0
-// saw no visible key.  One workgroup per query vector, one thread per output dim; the split
-// weights are computed once in parallel and kept in LDS, and the partial rows are then read
-// with independent loads.
-constexpr int ATTN_MAX_SPLITS = 1024;   // 256 key splits x 4 sub-ranges
+// out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s over the partials of the query's
+// (sequence, K/V head) pair: one per workgroup run that holds units of the pair (AttnWork) and
+// sub-range, out of the nsplit slots of the query vector.  A partial with l == 0 saw no visible
+// key.  One workgroup per query vector, one thread per output dim; the weights are computed
+// once in parallel and kept in LDS, and the partial rows are then read with independent loads.
+constexpr int ATTN_MAX_SPLITS = 1024;   // 256 key chunks x 4 sub-ranges
 
-__global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, int chunk, int nsub,
+__global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork work, int Hq, int group,
+                                                         int nsub,
                                                          const float *__restrict__ o_part,
                                                          const float *__restrict__ ml_part,
                                                          int nsplit, int hd,
@@ -71,8 +71,10 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, in
   __shared__ float red[16];
   __shared__ float w[ATTN_MAX_SPLITS];
   const int qv = blockIdx.x, t = threadIdx.x;
-  const int b = qv / (Hq * sb.K);
-  const int used = (sb.n[b] + sb.K - 1 + chunk - 1) / chunk * nsub;   // partials of this sequence
+  const int b = qv / (Hq * sb.K), g = qv % Hq / group;
+  const int cb = work.cum[b + 1] - work.cum[b];
+  const int pair0 = work.cum[b] * (Hq / group) + g * cb;        // first unit of the pair
+  const int used = ((pair0 + cb - 1) / work.per - pair0 / work.per + 1) * nsub;
   float mx = -3.0e38f;
   for (int s = t; s < used; s += blockDim.x) {
     const size_t slot = (size_t)qv * nsplit + s;
@@ -104,41 +106,59 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, int Hq, in
   out[(size_t)qv * hd + t] = num / den;
 }
 
-hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, int nsplit, hipStream_t st);
+hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, const AttnWork &work,
+                                 int nseg, hipStream_t st);
 int attn_mfma_nsub(int Kq, int group);
+
+// Chunk units per attention workgroup of the bf16 path; 0 = chosen from the amount of work.
+int g_attn_seg = 0;
 
 hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
-  int n_max = 0;
-  for (int b = 0; b < sb.B; ++b) n_max = max(n_max, sb.n[b]);
-  const int chunk = ATTN_KEY_CHUNK;                      // keys per workgroup
-  const int nsplit = (n_max + sb.K - 1 + chunk - 1) / chunk;
+  const int chunk = ATTN_KEY_CHUNK;                      // keys per chunk
+  AttnWork work;
+  work.cum[0] = 0;
+  work.per = 1;
+  int cb_max = 0;
+  for (int b = 0; b < sb.B; ++b) {
+    const int cb = (sb.n[b] + sb.K - 1 + chunk - 1) / chunk;
+    work.cum[b + 1] = work.cum[b] + cb;
+    cb_max = max(cb_max, cb);
+  }
   const size_t slot_elems = (size_t)Hkv * c->t_cap * hd;
   const int QVT = sb.B * sb.K * Hq;                      // query vectors of the pass
-  int nsub = 1;
+  int nsub = 1, nseg = cb_max;
   if (g.dtype == DART_BF16) {
+    // One unit per workgroup while there is at most one per compute unit (lowest latency);
+    // beyond that, runs of several units over one double-buffered workgroup per compute unit
+    // (128 KiB of LDS at head_dim 128; two fit at head_dim 64), so that copies overlap compute,
+    // nothing queues behind a first round, and few partials are written and merged.
+    const int units = work.cum[sb.B] * Hkv;
+    const int resident = hd == 128 ? 256 : 512;
+    work.per = g_attn_seg > 0 ? g_attn_seg : max(1, (units + resident - 1) / resident);
+    nseg = (cb_max + work.per - 2) / work.per + 1;        // most runs a pair can touch
     nsub = attn_mfma_nsub(sb.K, Hq / Hkv);
-    hipError_t e = launch_attention_bf16(c, sb, nsplit, st);
+    hipError_t e = launch_attention_bf16(c, sb, work, nseg, st);
     if (e != hipSuccess) return e;
   } else {
     const float scale = 1.0f / sqrtf((float)hd);
-    dim3 grid(nsplit, QVT);
+    dim3 grid(cb_max, QVT);
     if (hd == 64)
       hipLaunchKernelGGL(attn_split_f32_kernel<64>, grid, dim3(64), 0, st, sb,
                          (const float *)c->qrot, (const float *)c->kbuf, (const float *)c->vbuf,
-                         slot_elems, c->t_cap, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
+                         slot_elems, c->t_cap, Hq, Hq / Hkv, chunk, scale, cb_max, c->att_part,
                          c->att_ml);
     else
       hipLaunchKernelGGL(attn_split_f32_kernel<128>, grid, dim3(64), 0, st, sb,
                          (const float *)c->qrot, (const float *)c->kbuf, (const float *)c->vbuf,
-                         slot_elems, c->t_cap, Hq, Hq / Hkv, chunk, scale, nsplit, c->att_part,
+                         slot_elems, c->t_cap, Hq, Hq / Hkv, chunk, scale, cb_max, c->att_part,
                          c->att_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, Hq, chunk, nsub, c->att_part,
-                     c->att_ml, nsplit * nsub, hd, c->att_out);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, work, Hq, Hq / Hkv, nsub,
+                     c->att_part, c->att_ml, nseg * nsub, hd, c->att_out);
   return hipGetLastError();
 }
 

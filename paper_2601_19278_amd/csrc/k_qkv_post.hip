@@ -17,7 +17,7 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
     int col0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
     const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
     const float *__restrict__ sin_tab, CT *__restrict__ q_out, CT *__restrict__ kbuf,
-    CT *__restrict__ vbuf, size_t slot_elems, int t_cap, int v_transposed) {
+    CT *__restrict__ vbuf, size_t slot_elems, int t_cap, int tiled) {
   __shared__ float red[16];
   __shared__ float sh[128];
   const int i = blockIdx.x, hh = blockIdx.y, t = threadIdx.x;
@@ -33,8 +33,8 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
 
   if (!is_q && !is_k) {                           // value head: store as is
     const int g = hh - Hq - Hkv;
-    if (v_transposed)
-      vbuf[((size_t)g * hd + t) * t_cap + attn_vt_position(pos)] = from_f32<CT>(x);
+    if (tiled)
+      vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t, hd)] = from_f32<CT>(x);
     else
       vbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(x);
     return;
@@ -53,7 +53,10 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
     q_out[((size_t)(b * sb.K + qi) * Hq + hh) * hd + t] = from_f32<CT>(y);
   } else {
     const int g = hh - Hq;
-    kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(y);
+    if (tiled)
+      kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t, hd)] = from_f32<CT>(y);
+    else
+      kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(y);
   }
 }
 
