@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# a plain 1 GiB copy (profiles/lm_head_C4_hbm_counters.txt); re-measure after kernel changes.
-MEASURED_LM_HEAD_TRAFFIC = {"C4": 1601.3e6}
+# a plain 1 GiB copy (profiles/lm_head_C4_hbm_counters.txt, profiles/gemm_lm_head_C5_counters.txt);
+# re-measure after kernel changes.
+MEASURED_LM_HEAD_TRAFFIC = {"C4": 1589.3e6, "C5": 1711.8e6}
 
 
 def algorithmic_bytes(cfg, n_new: int) -> dict:
@@ -139,7 +140,8 @@ def bench_batched(cfg, args, seed) -> dict:
     achieved = lm_bytes / (lm_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (LM head, 128 rows)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_LM_HEAD_TRAFFIC.get(cfg.name),
                 "kernel_us": round(lm_us, 2), "algorithmic_bytes": lm_bytes,
                 "mfma_TFLOPs_algorithmic": round(2.0 * B * K * p["lm_head"] / (lm_us * 1e-6) / 1e12, 1)}
     stages["lm_head_us"] = lm_us
