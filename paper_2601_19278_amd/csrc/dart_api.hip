@@ -183,10 +183,10 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     c->split_o = gemv_bf16_split(c->q_dim, (d + 15) / 16);
     c->split_gu = gemv_bf16_split(d, 2 * F / 16);
     c->split_down = gemv_bf16_split(F, (d + 15) / 16);
-    ch_qkv = gemv_bf16_chunks(in_dim) * c->split_qkv;
-    ch_o = gemv_bf16_chunks(c->q_dim) * c->split_o;
-    ch_gu = gemv_bf16_chunks(d) * c->split_gu;
-    ch_down = gemv_bf16_chunks(F) * c->split_down;
+    ch_qkv = c->split_qkv;
+    ch_o = c->split_o;
+    ch_gu = c->split_gu;
+    ch_down = c->split_down;
     if (g.max_ctx > R && gemv_bf16_row_tiles(in_dim, c->split_qkv) >= 4 &&
         (!g.front_end || gemv_bf16_row_tiles(g.feat_dim, c->split_fc) >= 4))
       c->kv_rows = std::min(1024, round_up(g.max_ctx, 64));
@@ -236,7 +236,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * in_dim));
   if (g.front_end) {
     c->fc_rows = std::max(c->ws_rows, c->kv_rows);
-    const int ch_fc = g.dtype == DART_BF16 ? gemv_bf16_chunks(g.feat_dim) * c->split_fc : 1;
+    const int ch_fc = g.dtype == DART_BF16 ? c->split_fc : 1;
     HIP_TRY(dev_alloc(&c->feat32, (size_t)c->fc_rows * g.feat_dim));
     HIP_TRY(dev_alloc(&c->fc_part, (size_t)ch_fc * c->fc_rows * d));
   }
@@ -257,8 +257,8 @@ dart_status from_hip(hipError_t e) {
 
 // Projection of M rows of X (fp32 [M][W.Kd]) through output rows [row0, row0+nrows) of W;
 // out[chunk][m][j] with row stride out_stride and chunk stride chunk_stride.
-// split: extra k-split of the matrix (fixed per matrix at create time so that every call cuts
-// k the same way; 1 where the output must be complete in one chunk).
+// split: k-chunks of the matrix on the skinny kernel (fixed per matrix at create time so that
+// every call cuts k the same way; 1 where the output must be complete in one chunk).
 // gch > 0: take the multi-row kernel with gch k-chunks (the batched entry point).
 hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows, const float *X,
                    int M, float *out, int out_stride, size_t chunk_stride, int split, int gch,

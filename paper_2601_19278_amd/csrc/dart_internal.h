@@ -147,7 +147,7 @@ struct dart_ctx {
   int kv_rows = 16;
   float *xn_kv = nullptr;         // [kv_rows][d]
   float *kv_part = nullptr;       // [chunks][kv_rows][2*kv_dim]
-  int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // extra k-split per matrix
+  int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // k-chunks per matrix (skinny kernel)
   int gch_qkv = 1, gch_o = 1, gch_gu = 1, gch_down = 1;           // k-chunks on the multi-row path
   void *xpack = nullptr;          // activations of one multi-row projection in MFMA operand order
   int max_rows;                   // max_batch * max_K
@@ -203,8 +203,8 @@ hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
                             hipStream_t st);
 int attn_mfma_nsub(int Kq, int group);        // key sub-ranges per split of the MFMA attention
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
-int gemv_bf16_split(int Kd, int nstrips);     // extra k-split that balances the workgroups
-int gemv_bf16_row_tiles(int Kd, int split);   // 16-row tiles one launch may carry per row block
+int gemv_bf16_split(int Kd, int nstrips);     // k-chunks that balance the workgroups (>= gemv_bf16_chunks)
+int gemv_bf16_row_tiles(int Kd, int nch);     // 16-row tiles one launch may carry per row block
 
 // bf16 multi-row GEMM on packed weights (any M); nchunks is fixed per matrix, see gemm_bf16_chunks.
 // epi 1: the strips are interleaved gate/up rows and out receives silu(gate) * up, [M][out_stride].

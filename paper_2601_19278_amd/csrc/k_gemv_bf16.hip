@@ -237,15 +237,17 @@ static void gemv_launch(bool nt, int mt, dim3 grid, hipStream_t st, const u32x4_
 #undef DART_GEMV_GO
 }
 
-// Extra k-split for matrices with few strips.  With one workgroup per CU, 320 strips of a
+// Number of k-chunks for a matrix with few strips.  With one workgroup per CU, 320 strips of a
 // 5120-row matrix leave a quarter of the CUs with twice the work of the rest, and a short
-// kernel also pays for each wavefront's activation set-up.  Cutting k into `split` times more
-// chunks gives (strip, chunk) units that divide evenly over the CUs and shortens the set-up;
-// the consumer adds the extra partials.  Measured on MI355X at d = 5120: 7168 rows 25 -> 13 us,
-// 5120 rows 23 -> 11 us, 34816 rows 67 -> 56 us with split 4; matrices with more than ~12
-// strips per workgroup (the LM head) gain nothing.  Only splits that keep every wavefront's
-// k-slice an exact, supported length of at least 4 k-steps are used.
-int g_gemv_split = 0;      // benchmark override (0 = automatic)
+// kernel also pays for each wavefront's activation set-up.  Cutting k into more chunks than
+// the register budget demands gives (strip, chunk) units that divide evenly over the CUs and
+// shortens the set-up; the consumer adds the extra partials.  Measured on MI355X at d = 5120:
+// 7168 rows 25 -> 13 us, 5120 rows 23 -> 11 us, 34816 rows 67 -> 56 us with 4 chunks of 5
+// k-steps per wavefront; 5120 rows x 17408 inputs 38 -> 31 us with 17 chunks of 4 k-steps instead
+// of 4 chunks of 17; matrices with more than ~12 strips per workgroup (the LM head) gain nothing.
+// Only chunk counts that keep every wavefront's k-slice an exact, supported length of at least
+// 4 k-steps are used.
+int g_gemv_split = 0;      // benchmark override: multiple of the minimum chunk count (0 = automatic)
 
 static bool exact_kpw_supported(int kpw) {
   return kpw == 2 || kpw == 4 || kpw == 5 || kpw == 8 || kpw == 10 || kpw == 12 || kpw == 16 ||
@@ -254,43 +256,45 @@ static bool exact_kpw_supported(int kpw) {
 
 int gemv_bf16_split(int Kd, int nstrips) {
   const int KT = Kd / 32, base = gemv_bf16_chunks(Kd);
-  auto valid = [&](int split) {
-    const int nch = base * split;
+  auto valid = [&](int nch) {
     return KT % (GEMV_WAVES * nch) == 0 && exact_kpw_supported(KT / (GEMV_WAVES * nch));
   };
-  if (g_gemv_split > 0) return valid(g_gemv_split) ? g_gemv_split : 1;
+  if (g_gemv_split > 0) return valid(base * g_gemv_split) ? base * g_gemv_split : base;
   const int wgs_base = max(1, min(g_gemv_wgs_split / base, nstrips));
-  if (nstrips / wgs_base >= 12) return 1;
-  for (int split = 4; split > 1; split /= 2)
-    if (valid(split) && KT / (GEMV_WAVES * base * split) >= 4) return split;
-  return 1;
+  if (nstrips / wgs_base >= 12) return base;
+  for (int split = 4; split > 1; split /= 2)             // 4 or 2 times the minimum first
+    if (valid(base * split) && KT / (GEMV_WAVES * base * split) >= 4) return base * split;
+  for (int nch = KT / (GEMV_WAVES * 4); nch > base; --nch)   // else the most chunks of >= 4 k-steps
+    if (valid(nch)) return nch;
+  return base;
 }
 
-// Largest row block (in 16-row tiles) the kernel can take for this matrix and split: the
-// activations of a block must fit the register budget next to the weight buffer.
-int gemv_bf16_row_tiles(int Kd, int split) {
-  const int KT = Kd / 32, nch = gemv_bf16_chunks(Kd) * split;
-  if (KT % (GEMV_WAVES * nch) != 0) return 1;
+// Largest row block (in 16-row tiles) the kernel can take for this matrix cut into nch chunks:
+// the activations of a block must fit the register budget next to the weight buffer.
+int gemv_bf16_row_tiles(int Kd, int nch) {
+  const int KT = Kd / 32;
+  if (nch < 1 || KT % (GEMV_WAVES * nch) != 0) return 1;
   const int kpw = KT / (GEMV_WAVES * nch);
   return kpw <= 5 && exact_kpw_supported(kpw) ? 4 : 1;
 }
 
 // Strips [strip0, strip0+nstrips) of the packed matrix; out[chunk][m][j], j < nstrips*16
-// (columns beyond W.n_real - strip0*16 are not written).  split: extra k-split (1 when the
-// output must be complete in a single chunk).  M may exceed 16 only up to
-// 16 * gemv_bf16_row_tiles(Kd, split) * any number of row blocks (grid.y).
+// (columns beyond W.n_real - strip0*16 are not written).  nch: k-chunks (at least
+// gemv_bf16_chunks(Kd); 1 when the output must be complete in a single chunk).  M may exceed 16
+// only up to 16 * gemv_bf16_row_tiles(Kd, nch) * any number of row blocks (grid.y).
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
-                            float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
+                            float *out, int out_stride, size_t chunk_stride, int nch, int *chunks,
                             hipStream_t st) {
   const int KT = W.Kd / 32;
-  const int nchunks = gemv_bf16_chunks(W.Kd) * split;
+  const int nchunks = nch;
+  if (nchunks < gemv_bf16_chunks(W.Kd)) return hipErrorInvalidValue;
   const int kpw = (KT + GEMV_WAVES * nchunks - 1) / (GEMV_WAVES * nchunks);
   const bool exact = kpw * GEMV_WAVES * nchunks == KT;
   if (chunks) *chunks = nchunks;
   const int n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
   int mt = M <= 8 ? 0 : 1, row_blocks = 1;
   if (M > 16) {
-    const int cap = gemv_bf16_row_tiles(W.Kd, split);
+    const int cap = gemv_bf16_row_tiles(W.Kd, nchunks);
     if (cap < 2) return hipErrorInvalidValue;          // caller must pass <= 16 rows per launch
     mt = M > 32 ? 4 : 2;
     row_blocks = (M + 16 * mt - 1) / (16 * mt);

@@ -175,15 +175,23 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
       load8(gain + c, g[j]);
     }
   }
-  for (int k = 0; k < chunks; ++k) {
+  // chunk partials: up to 8 loads in flight per column group, added in index order
+  constexpr int U = 8;
+  for (int k0 = 0; k0 < chunks; k0 += U) {
 #pragma unroll
     for (int j = 0; j < ROW_MAXIT; ++j) {
       const int c = (j * ROW_THREADS + threadIdx.x) * 8;
       if (c < d) {
-        float p[8];
-        load8(part + k * chunk_stride + (size_t)r * row_stride + c, p);
+        float p[U][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[j][e] += p[e];
+        for (int u = 0; u < U; ++u)
+          if (k0 + u < chunks)
+            load8(part + (size_t)(k0 + u) * chunk_stride + (size_t)r * row_stride + c, p[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (k0 + u < chunks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[j][e] += p[u][e];
       }
     }
   }
