@@ -12,11 +12,14 @@
 // (creation = b*k + c).  Larger key = better under both cuts of the algorithm: within one
 // level it orders by (score desc, creation asc) -- the beam cut -- and across levels by
 // (score desc, level asc, creation asc) -- the global theta cut.  Ranking the level's keys
-// (by counting for up to 1024 expansions, by a bitonic sort beyond) gives the next beam
-// (first w) and the level's contenders for the global tree (first theta), which are merged
-// into the running best-theta list.  Since the best
-// theta of a union is the best theta of (best theta of one part) + (the other part), the
-// running list equals Alg. 1's "top-theta of T" after the last level.
+// gives the next beam (first w) and the level's contenders for the global tree (first theta),
+// which are merged into the running best-theta list.  Since the best theta of a union is the
+// best theta of (best theta of one part) + (the other part), the running list equals Alg. 1's
+// "top-theta of T" after the last level.  Three ways of ranking a level: up to 256 expansions
+// with every N-gram score already in LDS (the presets: w*k = 200) -- one wavefront selects the
+// max(w, theta) expansions that matter by a threshold search and ranks only those, one barrier
+// per level (see the kernel); up to 1024 expansions -- ranking by counting over all threads;
+// beyond -- a bitonic sort.
 //
 // N-gram lookups.  The context a beam entry presents at level L is the last N-1 tokens of its
 // path: (candidate a of level L-2, candidate b of level L-1) for a trigram.  Which paths
@@ -26,14 +29,18 @@
 // level -- every hash probe and every successor-row read of the call in flight at once, two
 // memory round trips in total -- and the K levels then run without touching memory.
 // Otherwise each level looks up its own beam entries (at most w per level, as in App. C.2).
+// A loaded successor is matched against its level's k candidates through a small bucketed
+// table of the candidate ids in LDS (one 16-byte read per successor instead of k compares).
 #include "common.h"
 #include "dart_internal.h"
 
 namespace dart {
 
 constexpr int PRUNE_THREADS = 1024;    // one workgroup per sequence; many phases are item-parallel
+static_assert(DART_MAX_LEVEL_NODES <= 16384, "a level's pair scores share the ng array");
 constexpr int PRUNE_NG_CELLS = 16384;  // N-gram scores of all possible (context, candidate) pairs
 constexpr int PRUNE_NG_CTX = 1280;     // possible contexts of one call resolved up front
+constexpr int PRUNE_SMALL = 256;       // expansions per level the short-level loop handles (w * k)
 
 struct PruneShared {
   uint64_t keys[DART_MAX_LEVEL_NODES];        // this level's expansions
@@ -48,26 +55,39 @@ struct PruneShared {
   int32_t rank[PRUNE_THREADS];                 // rank of expansion e among the level's keys
   int32_t beam_ci[2][DART_MAX_BEAM];           // candidate index of the entry's token at its level
   int32_t beam_pi[2][DART_MAX_BEAM];           // candidate index of its parent's token
-  // up-front mode: s_ng of candidate c for possible context g at ng[g * k + c]
+  // up-front mode: s_ng of candidate c for possible context g at ng[g * k + c];
+  // level-by-level mode: s_ng of every (beam entry b, candidate c) pair of the level at
+  // ng[b * k + c], filled while the beam entries' successor rows stream in
   float ng[PRUNE_NG_CELLS];
   int32_t ctx_row[PRUNE_NG_CTX];               // table row of possible context g, -1 = unseen
   int32_t hit_ctx[PRUNE_NG_CTX];               // the contexts that have a row
   int32_t n_hit;
-  // N-gram score of every (beam entry, candidate) pair of the level, filled while the beam
-  // entries' successor rows stream in
-  float s_ng[DART_MAX_LEVEL_NODES];
   // the level's best min(theta, n_new) expansions, sorted by key descending
-  uint64_t lvl_key[DART_MAX_BUDGET];
-  int32_t lvl_tok[DART_MAX_BUDGET];
-  int32_t lvl_par[DART_MAX_BUDGET];
+  uint64_t lvl_key[2][DART_MAX_BUDGET];       // ([0] only, outside the short-level mode)
+  int32_t lvl_tok[2][DART_MAX_BUDGET];
+  int32_t lvl_par[2][DART_MAX_BUDGET];
   // running best list (double buffered), sorted by key descending
   uint64_t best_key[2][DART_MAX_BUDGET];
   int32_t best_tok[2][DART_MAX_BUDGET];
   int32_t best_par[2][DART_MAX_BUDGET];        // creation index of the parent at level-1
+  // candidate ids of every level in a bucketed table (cand_buckets() buckets of four ids per
+  // level): which candidate of level L, if any, is token id?  One 16-byte read answers it.
+  __align__(16) int32_t ch_id[DART_MAX_K * DART_MAX_TOPK * 4];   // -1 = empty
+  uint8_t ch_c[DART_MAX_K * DART_MAX_TOPK * 4];
+  int32_t ch_over[DART_MAX_K];                  // a bucket of the level overflowed: search linearly
   // emission
   int32_t out_idx[DART_MAX_BUDGET];
   int32_t out_par[DART_MAX_BUDGET];
+  // short-level mode (at most PRUNE_SMALL expansions per level)
+  __align__(16) uint32_t sel_sc[PRUNE_SMALL];  // sortable scores of the level's expansions that matter
+  int32_t sel_e[PRUNE_SMALL];                  // ... and their (creation index << 16) | (beam entry << 8) | candidate
+  __align__(16) uint32_t lvl_sc[2][DART_MAX_BUDGET];   // scores of lvl_key[][], padded with 0 to a multiple of 4
+  __align__(16) uint32_t best_sc[2][DART_MAX_BUDGET];  // scores of best_key[][], likewise
+  uint8_t pos[DART_MAX_K * PRUNE_SMALL];       // output index of the node (level, creation)
+  int32_t lvl_cnt[2][DART_MAX_K];              // selected nodes per level, per wavefront
 };
+
+static_assert(sizeof(PruneShared) <= 160 * 1024, "one workgroup's state must fit the 160 KiB of LDS");
 
 __device__ __forceinline__ uint64_t pack_context(int ctx_len, int prev, int tok) {
   return ctx_len >= 2 ? ((uint64_t)(uint32_t)prev << 32) | (uint32_t)tok : (uint64_t)(uint32_t)tok;
@@ -101,15 +121,59 @@ __device__ __forceinline__ int key_creation(uint64_t key) {
   return 0x0FFFFFFF - (int)(key & 0x0FFFFFFF);
 }
 
+// Buckets per level of the candidate table: a power of two >= k.
+__device__ __forceinline__ int cand_buckets(int k) {
+  int H = 1;
+  while (H < k) H <<= 1;
+  return H;
+}
+__device__ __forceinline__ uint32_t cand_hash(int32_t id, int H) {
+  return ((uint32_t)id * 2654435761u >> 16) & (uint32_t)(H - 1);
+}
+
+// Enter the K*k candidates (ids distinct within a level).  Ends with a barrier.
+__device__ void build_cand_table(PruneShared &sh, int K, int k, int t) {
+  const int H = cand_buckets(k);
+  for (int i = t; i < K * H * 4; i += PRUNE_THREADS) sh.ch_id[i] = -1;
+  if (t < K) sh.ch_over[t] = 0;
+  __syncthreads();
+  for (int e = t; e < K * k; e += PRUNE_THREADS) {
+    const int L = e / k, c = e - L * k;
+    const int32_t id = sh.cand_id[e];
+    const int base = (L * H + (int)cand_hash(id, H)) * 4;
+    bool placed = false;
+    for (int s = 0; s < 4 && !placed; ++s)
+      if (atomicCAS(&sh.ch_id[base + s], -1, id) == -1) {
+        sh.ch_c[base + s] = (uint8_t)c;
+        placed = true;
+      }
+    if (!placed) sh.ch_over[L] = 1;
+  }
+  __syncthreads();
+}
+
+// Index of token id among the candidates of level L, or -1.
+__device__ __forceinline__ int cand_find(const PruneShared &sh, int L, int H, int k, int32_t id) {
+  if (id < 0) return -1;                                 // unused successor slot
+  const int base = (L * H + (int)cand_hash(id, H)) * 4;
+  const int4 b = *reinterpret_cast<const int4 *>(&sh.ch_id[base]);
+  const int s = b.x == id ? 0 : (b.y == id ? 1 : (b.z == id ? 2 : (b.w == id ? 3 : -1)));
+  if (s >= 0) return sh.ch_c[base + s];
+  if (sh.ch_over[L])
+    for (int c = 0; c < k; ++c)
+      if (sh.cand_id[L * k + c] == id) return c;
+  return -1;
+}
+
 // N-gram scores of level L for the nb current beam entries: s_ng[b*k + c] = stored score of
 // candidate c among the successors of beam entry b's context, else the miss score.  The
 // successor rows are read once, coalesced, all loads independent; each loaded successor is
-// compared with the level's k candidates (LDS broadcast reads).  Successor ids are distinct
-// within a row and candidate ids within a level, so at most one thread writes a cell.
+// looked up in the level's candidate table.  Successor ids are distinct within a row and
+// candidate ids within a level, so at most one thread writes a cell.
 __device__ __forceinline__ void score_rows(PruneShared &sh, const NgramTableDev &tab, int nb, int k,
                                            int L, int t) {
-  const int S = tab.S;
-  for (int e = t; e < nb * k; e += PRUNE_THREADS) sh.s_ng[e] = tab.logp_miss;
+  const int S = tab.S, H = cand_buckets(k);
+  for (int e = t; e < nb * k; e += PRUNE_THREADS) sh.ng[e] = tab.logp_miss;
   __syncthreads();
   for (int idx = t; idx < nb * S; idx += PRUNE_THREADS) {
     const int b = idx / S, j = idx - b * S;
@@ -117,8 +181,8 @@ __device__ __forceinline__ void score_rows(PruneShared &sh, const NgramTableDev 
     if (row >= 0) {
       const int32_t id = tab.succ_ids[(size_t)row * S + j];
       const float lp = tab.succ_logp[(size_t)row * S + j];
-      for (int c = 0; c < k; ++c)
-        if (sh.cand_id[L * k + c] == id) sh.s_ng[b * k + c] = lp;
+      const int c = cand_find(sh, L, H, k, id);
+      if (c >= 0) sh.ng[b * k + c] = lp;
     }
   }
 }
@@ -132,6 +196,49 @@ __device__ __forceinline__ int ctx_offset(int L, int k, int ctx_len) {
 }
 
 // Up-front resolution of every possible context (see the header): fills sh.ng.
+// Number of entries of a score list that beat a score: entries of blocks below jt count when
+// they are >= mine (they win ties), the others when they are > mine.  s4: the list in LDS, n4
+// (1..64) groups of four, padded with 0 (scores are > 0).  The order of the count does not
+// matter, so every lane starts at a different group and walks the list cyclically: the lanes
+// of a wavefront then read different LDS addresses in every step.
+__device__ __forceinline__ int count_above(const uint4 *s4, int n4, uint32_t mine, int jt) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t inv = (65536u + n4 - 1) / n4;
+  int idx = lane - (int)(((uint32_t)lane * inv) >> 16) * n4;      // lane mod n4
+  int r = 0;
+  // four compares into four mask registers, then four add-with-carry: written out because the
+  // compiler routes every compare through VCC and pays wait states after each one
+  auto add4 = [&](const uint4 &v, uint32_t thr) {
+    uint64_t m0, m1, m2, m3;
+    asm("v_cmp_gt_u32_e64 %[m0], %[x], %[t]\n\t"
+        "v_cmp_gt_u32_e64 %[m1], %[y], %[t]\n\t"
+        "v_cmp_gt_u32_e64 %[m2], %[z], %[t]\n\t"
+        "v_cmp_gt_u32_e64 %[m3], %[w], %[t]\n\t"
+        "v_addc_co_u32_e64 %[r], %[m0], 0, %[r], %[m0]\n\t"
+        "v_addc_co_u32_e64 %[r], %[m1], 0, %[r], %[m1]\n\t"
+        "v_addc_co_u32_e64 %[r], %[m2], 0, %[r], %[m2]\n\t"
+        "v_addc_co_u32_e64 %[r], %[m3], 0, %[r], %[m3]"
+        : [r] "+v"(r), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3)
+        : [x] "v"(v.x), [y] "v"(v.y), [z] "v"(v.z), [w] "v"(v.w), [t] "v"(thr));
+  };
+  auto next = [&](int i) { return i + 1 == n4 ? 0 : i + 1; };
+  int j = 0;
+  for (; j + 4 <= n4; j += 4) {              // four groups in flight
+    const int i0 = idx, i1 = next(i0), i2 = next(i1), i3 = next(i2);
+    const uint4 v0 = s4[i0], v1 = s4[i1], v2 = s4[i2], v3 = s4[i3];
+    add4(v0, i0 < jt ? mine - 1 : mine);
+    add4(v1, i1 < jt ? mine - 1 : mine);
+    add4(v2, i2 < jt ? mine - 1 : mine);
+    add4(v3, i3 < jt ? mine - 1 : mine);
+    idx = next(i3);
+  }
+  for (; j < n4; ++j) {
+    add4(s4[idx], idx < jt ? mine - 1 : mine);
+    idx = next(idx);
+  }
+  return r;
+}
+
 __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, int K, int k,
                                      int ctx_len, int prev0, int root, int t) {
   const int NC = ctx_offset(K, k, ctx_len);
@@ -175,59 +282,87 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
     if (g < NC) {
       const int row = ngram_resolve(tab, packed[q], hslot[q], raw[q]);
       sh.ctx_row[g] = row;
-      if (row >= 0) sh.hit_ctx[atomicAdd(&sh.n_hit, 1)] = g;   // order irrelevant: cells are disjoint
+      if (row >= 0) {
+        const int L = g == 0 ? 0
+                      : (ctx_len < 2 ? 1 + (g - 1) / k : (g < 1 + k ? 1 : 2 + (g - 1 - k) / (k * k)));
+        sh.hit_ctx[atomicAdd(&sh.n_hit, 1)] = g | (L << 16);   // order irrelevant: cells are disjoint
+      }
     }
   }
   __syncthreads();
   // 2. successor rows of the contexts that exist, each successor compared with the k
   //    candidates of the context's level.  Successor ids are distinct within a row and
   //    candidate ids within a level, so at most one thread writes a cell.
-  const int S = tab.S, n_hit = sh.n_hit;
-  auto level_of = [&](int g) {
-    if (g == 0) return 0;
-    if (ctx_len < 2) return 1 + (g - 1) / k;
-    return g < 1 + k ? 1 : 2 + (g - 1 - k) / (k * k);
-  };
+  const int S = tab.S, n_hit = sh.n_hit, H = cand_buckets(k);
+  bool over_any = false;
+  for (int L = 0; L < K; ++L) over_any |= sh.ch_over[L] != 0;
   if ((S & 3) == 0) {
     const int parts = S >> 2;                  // 16-byte pieces per row
     const int total = n_hit * parts;
+    // item / parts by a reciprocal: exact while item * parts < 2^20 (items < 1280 * 16)
+    const uint32_t inv = ((1u << 20) + parts - 1) / parts;
     constexpr int U = 8;
     for (int i0 = t; i0 < total; i0 += U * PRUNE_THREADS) {
       // all 2*U loads of a thread are issued before the first use; items past the end are
       // clamped (loaded twice, used once) so that no branch separates the loads
       int4 id4[U];
       float4 lp4[U];
+      int hc[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int item = min(i0 + u * PRUNE_THREADS, total - 1);
-        const size_t at = (size_t)sh.ctx_row[sh.hit_ctx[item / parts]] * S + 4 * (item % parts);
+        const int hi = (int)(((uint32_t)item * inv) >> 20), piece = item - hi * parts;
+        hc[u] = sh.hit_ctx[hi];
+        const size_t at = (size_t)sh.ctx_row[hc[u] & 0xFFFF] * S + 4 * piece;
         id4[u] = *reinterpret_cast<const int4 *>(tab.succ_ids + at);
         lp4[u] = *reinterpret_cast<const float4 *>(tab.succ_logp + at);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int item = i0 + u * PRUNE_THREADS;
-        if (item < total) {
-          const int g = sh.hit_ctx[item / parts], L = level_of(g);
+        if (i0 + u * PRUNE_THREADS < total) {
+          const int g = hc[u] & 0xFFFF, L = hc[u] >> 16;
           const int idv[4] = {id4[u].x, id4[u].y, id4[u].z, id4[u].w};
           const float lpv[4] = {lp4[u].x, lp4[u].y, lp4[u].z, lp4[u].w};
-          for (int c = 0; c < k; ++c) {
-            const int want = sh.cand_id[L * k + c];
+          // the four bucket reads go out together; branches only on a match (rare)
+          int base[4], slot[4];
+          int4 bk[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            base[r] = (L * H + (int)cand_hash(idv[r], H)) * 4;
+            bk[r] = *reinterpret_cast<const int4 *>(&sh.ch_id[base[r]]);
+          }
+          bool any = false;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int id = idv[r];
+            slot[r] = id < 0 ? -1
+                             : (bk[r].x == id ? 0 : (bk[r].y == id ? 1 : (bk[r].z == id ? 2 : (bk[r].w == id ? 3 : -1))));
+            any |= slot[r] >= 0;
+          }
+          if (any) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-              if (idv[r] == want) sh.ng[g * k + c] = lpv[r];
+              if (slot[r] >= 0) sh.ng[g * k + sh.ch_c[base[r] + slot[r]]] = lpv[r];
+          }
+          if (over_any && sh.ch_over[L]) {              // a bucket of this level overflowed
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (slot[r] < 0 && idv[r] >= 0)
+                for (int c = 0; c < k; ++c)
+                  if (sh.cand_id[L * k + c] == idv[r]) sh.ng[g * k + c] = lpv[r];
           }
         }
       }
     }
   } else {
     for (int item = t; item < n_hit * S; item += PRUNE_THREADS) {
-      const int g = sh.hit_ctx[item / S], L = level_of(g);
+      const int hcx = sh.hit_ctx[item / S];
+      const int g = hcx & 0xFFFF, L = hcx >> 16;
       const size_t at = (size_t)sh.ctx_row[g] * S + item % S;
       const int32_t id = tab.succ_ids[at];
       const float lp = tab.succ_logp[at];
-      for (int c = 0; c < k; ++c)
-        if (sh.cand_id[L * k + c] == id) sh.ng[g * k + c] = lp;
+      const int c = cand_find(sh, L, H, k, id);
+      if (c >= 0) sh.ng[g * k + c] = lp;
     }
   }
 }
@@ -270,13 +405,177 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   }
   int nb = 1, n_best = 0, cur = 0, bcur = 0;
   __syncthreads();
+  build_cand_table(sh, K, k, t);
   if (pre)
     resolve_all_contexts(sh, tab, K, k, ctx_len, prev0, root, t);
   else
     score_rows(sh, tab, 1, k, 0, t);
   __syncthreads();
 
-  for (int L = 0; L < K; ++L) {
+  // Short-level mode: every level has at most PRUNE_SMALL expansions and every N-gram score is
+  // already in LDS.  Ranking all w*k expansions of a level by counting costs (w*k)^2 compares,
+  // but only the best max(w, theta) of them are ever used.  So one wavefront holds the level's
+  // scores in registers (four per lane), finds a score T at or just below that of the last
+  // expansion that matters by a bitwise search with ballots, compacts the expansions with
+  // score >= T into LDS in creation order and ranks only those among themselves (32-bit
+  // sortable scores, read four at a time; among equal scores the earlier creation wins, as in
+  // the 64-bit key).  That wavefront runs the whole beam recursion without waiting for anyone;
+  // two other wavefronts merge the previous level's list into the best list meanwhile (the
+  // level lists are double buffered), and a level costs one barrier.
+  const bool small = pre && beam_w * k <= PRUNE_SMALL;
+  if (small) {
+    const int lane = t & 63, wav = t >> 6;
+    int n_lvl_prev = 0;
+    // Both lists are sorted and the level list's entries all have a higher level than the best
+    // list's, so between the lists the score decides and a tie goes to the best list's entry.
+    // Done by threads 64 .. 64 + n_best + n_lvl_prev (at most 2 * 127 of them).
+    auto merge_prev = [&](int lb) {
+      const int bnx = bcur ^ 1;
+      const int n_out = min(theta, n_best + n_lvl_prev);
+      const int tt = t - 64;
+      if (tt >= 0 && tt < n_best + n_lvl_prev) {
+        uint64_t key;
+        uint32_t sc;
+        int tok, par, rank;
+        if (tt < n_best) {
+          key = sh.best_key[bcur][tt];
+          sc = sh.best_sc[bcur][tt];
+          tok = sh.best_tok[bcur][tt];
+          par = sh.best_par[bcur][tt];
+          rank = tt + count_above(reinterpret_cast<const uint4 *>(sh.lvl_sc[lb]),
+                                  (n_lvl_prev + 3) >> 2, sc, 0);
+        } else {
+          const int j0 = tt - n_best;
+          key = sh.lvl_key[lb][j0];
+          sc = sh.lvl_sc[lb][j0];
+          tok = sh.lvl_tok[lb][j0];
+          par = sh.lvl_par[lb][j0];
+          const int b4 = (n_best + 3) >> 2;
+          rank = j0 + (n_best ? count_above(reinterpret_cast<const uint4 *>(sh.best_sc[bcur]), b4, sc, b4) : 0);
+        }
+        if (rank < theta) {
+          sh.best_key[bnx][rank] = key;
+          sh.best_sc[bnx][rank] = sc;
+          sh.best_tok[bnx][rank] = tok;
+          sh.best_par[bnx][rank] = par;
+        }
+      } else if (t >= 512 && t - 512 + n_out < ((n_out + 3) & ~3)) {
+        sh.best_sc[bnx][t - 512 + n_out] = 0;              // padding of the merged list
+      }
+      n_best = n_out;
+      bcur = bnx;
+    };
+    for (int L = 0; L < K; ++L) {
+      const int n_new = nb * k;
+      const int nb_next = min(beam_w, n_new);
+      const int n_lvl = min(theta, n_new);
+      const int need = max(nb_next, n_lvl);      // expansions of this level that matter (<= n_new)
+      const int nxt = cur ^ 1, lb = L & 1;
+      if (wav == 0) {
+        const float wl = lw.w_logit[L], wv = lw.w_level[L];
+        // scores of expansions lane, lane + 64, lane + 128, lane + 192 (0 = none).  Indices are
+        // clamped instead of branched on, so that the four dependent LDS chains overlap;
+        // e / k by a reciprocal (exact for e < 256, k <= 64: e * k < 2^16).
+        uint32_t sc[4];
+        int bc[4];                              // (beam entry << 8) | candidate
+        const uint32_t inv_k = (65536u + k - 1) / k;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int e = min(lane + 64 * i, n_new - 1);
+          const int bb = (int)(((uint32_t)e * inv_k) >> 16), c = e - bb * k;
+          const int p_ci = sh.beam_ci[cur][bb];
+          const int gctx = ctx_offset(L, k, ctx_len) +
+                           (L < 2 || ctx_len < 2 ? p_ci : sh.beam_pi[cur][bb] * k + p_ci);
+          const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
+          const float g = __fmul_rn(w_ng, sh.ng[gctx * k + c]);
+          const float inc = __fmul_rn(__fadd_rn(a, g), wv);
+          const uint32_t v = f32_sortable(__fadd_rn(sh.beam_score[cur][bb], inc));
+          sc[i] = lane + 64 * i < n_new ? v : 0;
+          bc[i] = (bb << 8) | c;
+        }
+        // A threshold T with at least `need` scores >= T, found bit by bit from the top (every
+        // accepted bit keeps that property).  The search stops as soon as few more than `need`
+        // scores are left above T: any such T selects a superset of the expansions that matter.
+        uint32_t T = 0;
+        int above = n_new;
+        const int enough = need <= 64 ? 64 : need + 8;   // up to 64 are ranked in one pass
+        for (int bit = 31; bit >= 0 && above > enough; --bit) {
+          const uint32_t trial = T | (1u << bit);
+          const int cnt = __popcll(__ballot(sc[0] >= trial)) + __popcll(__ballot(sc[1] >= trial)) +
+                          __popcll(__ballot(sc[2] >= trial)) + __popcll(__ballot(sc[3] >= trial));
+          if (cnt >= need) {
+            T = trial;
+            above = cnt;
+          }
+        }
+        // the expansions with score >= T (real scores are > 0, T >= the smallest of them), in
+        // creation order
+        int m = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool in = sc[i] >= T && sc[i] != 0;
+          const uint64_t mask = __ballot(in);
+          if (in) {
+            const int at = m + __popcll(mask & (((uint64_t)1 << lane) - 1));
+            sh.sel_sc[at] = sc[i];
+            sh.sel_e[at] = ((lane + 64 * i) << 16) | bc[i];
+          }
+          m += __popcll(mask);
+        }
+        if (lane < ((m + 3) & ~3) - m) sh.sel_sc[m + lane] = 0;      // pad the last group of four
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // rank among the selected = rank among all: scores above mine + equal scores created
+        // before me (= earlier in the list)
+        const uint4 *s4 = reinterpret_cast<const uint4 *>(sh.sel_sc);
+        for (int p0 = lane; p0 < m; p0 += 64) {
+          const uint32_t mine = sh.sel_sc[p0];
+          const int ebc = sh.sel_e[p0];
+          const int e = ebc >> 16, bb = (ebc >> 8) & 0xFF, c = ebc & 0xFF;
+          const int jt = p0 >> 2;
+          int r = count_above(s4, (m + 3) >> 2, mine, jt);
+          {
+            const uint4 v = s4[jt];                        // my own group: ties before me
+            const int i = p0 & 3;
+            r += (i > 0 && v.x == mine) + (i > 1 && v.y == mine) + (i > 2 && v.z == mine);
+          }
+          if (r < need) {
+            const int tok = sh.cand_id[L * k + c];
+            if (r < nb_next) {
+              sh.beam_score[nxt][r] = f32_unsortable(mine);
+              sh.beam_tok[nxt][r] = tok;
+              sh.beam_prev[nxt][r] = sh.beam_tok[cur][bb];
+              sh.beam_cre[nxt][r] = e;
+              sh.beam_ci[nxt][r] = c;
+              sh.beam_pi[nxt][r] = sh.beam_ci[cur][bb];
+            }
+            if (r < n_lvl) {
+              sh.lvl_key[lb][r] = ((uint64_t)mine << 32) | ((uint64_t)(15 - L) << 28) |
+                                  (uint64_t)(0x0FFFFFFF - e);
+              sh.lvl_sc[lb][r] = mine;
+              sh.lvl_tok[lb][r] = tok;
+              sh.lvl_par[lb][r] = sh.beam_cre[cur][bb];
+            }
+          }
+        }
+        if (lane < ((n_lvl + 3) & ~3) - n_lvl) sh.lvl_sc[lb][n_lvl + lane] = 0;   // padding
+        // the next level's scores read what this level placed
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+      if (L > 0) merge_prev(lb ^ 1);
+      __syncthreads();
+      n_lvl_prev = n_lvl;
+      cur = nxt;
+      nb = nb_next;
+    }
+    merge_prev((K - 1) & 1);
+    __syncthreads();
+  }
+
+  for (int L = 0; !small && L < K; ++L) {
     const int n_new = nb * k;
     const int nb_next = min(beam_w, n_new);
     const int n_lvl = min(theta, n_new);
@@ -292,7 +591,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
       const int gctx = ctx_offset(L, k, ctx_len) +
                        (L < 2 || ctx_len < 2 ? sh.beam_ci[cur][b]
                                              : sh.beam_pi[cur][b] * k + sh.beam_ci[cur][b]);
-      const float s_ng = pre ? sh.ng[gctx * k + c] : sh.s_ng[e];
+      const float s_ng = pre ? sh.ng[gctx * k + c] : sh.ng[e];
       const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
       const float g = __fmul_rn(w_ng, s_ng);
       const float inc = __fmul_rn(__fadd_rn(a, g), wv);
@@ -352,9 +651,9 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           sh.beam_pi[nxt][r] = sh.beam_ci[cur][bb];
         }
         if (r < n_lvl) {
-          sh.lvl_key[r] = key;
-          sh.lvl_tok[r] = tok;
-          sh.lvl_par[r] = sh.beam_cre[cur][bb];
+          sh.lvl_key[0][r] = key;
+          sh.lvl_tok[0][r] = tok;
+          sh.lvl_par[0][r] = sh.beam_cre[cur][bb];
         }
       }
       // beam_row of this level was last read before the barriers above: safe to overwrite
@@ -403,9 +702,9 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           if (!last && !pre) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk));
         }
         if (t < n_lvl) {
-          sh.lvl_key[t] = kk;
-          sh.lvl_tok[t] = tk;
-          sh.lvl_par[t] = sh.beam_cre[cur][b];
+          sh.lvl_key[0][t] = kk;
+          sh.lvl_tok[0][t] = tk;
+          sh.lvl_par[0][t] = sh.beam_cre[cur][b];
         }
       }
       __syncthreads();
@@ -425,12 +724,12 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         par = sh.best_par[bcur][t];
         rank = t;
 #pragma unroll 8
-        for (int j = 0; j < n_lvl; ++j) rank += (sh.lvl_key[j] > key);
+        for (int j = 0; j < n_lvl; ++j) rank += (sh.lvl_key[0][j] > key);
       } else {
         const int j0 = t - n_best;
-        key = sh.lvl_key[j0];
-        tok = sh.lvl_tok[j0];
-        par = sh.lvl_par[j0];
+        key = sh.lvl_key[0][j0];
+        tok = sh.lvl_tok[0][j0];
+        par = sh.lvl_par[0][j0];
         rank = j0;
 #pragma unroll 8
         for (int j = 0; j < n_best; ++j) rank += (sh.best_key[bcur][j] > key);
@@ -452,34 +751,75 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   // emission: root, then level-major; inside a level the best list's order already is
   // (score desc, creation asc)
   const int n_nodes = 1 + n_best;
-  if (t < n_best) {
-    const int lev = key_level(sh.best_key[bcur][t]);
-    int idx = 1;
-#pragma unroll 8
-    for (int j = 0; j < n_best; ++j) {
-      const int lj = key_level(sh.best_key[bcur][j]);
-      idx += (lj < lev) || (lj == lev && j < t);
+  if (small) {
+    // Output index = 1 + selected nodes of lower levels + my place among those of my level
+    // (ballots: at most 127 selected nodes, two wavefronts); the parent's index is then looked
+    // up by (level, creation), 0xFF = not selected.
+    const int wav = t >> 6, lane = t & 63;
+    uint64_t key = 0;
+    int lev = -1, within = 0;
+    if (t < n_best) {
+      key = sh.best_key[bcur][t];
+      lev = key_level(key);
     }
-    sh.out_idx[t] = idx;
-  }
-  __syncthreads();
-  if (t < n_best) {
-    const uint64_t key = sh.best_key[bcur][t];
-    const int lev = key_level(key);
-    int parent = 0;
-    if (lev > 0) {
-      parent = -2;                                   // stays -2 only if the set were not ancestor-closed
-      const int want = sh.best_par[bcur][t];
-#pragma unroll 8
-      for (int j = 0; j < n_best; ++j) {
-        const uint64_t kj = sh.best_key[bcur][j];
-        if (key_level(kj) == lev - 1 && key_creation(kj) == want) parent = sh.out_idx[j];
+    if (t < 128) {
+      for (int l = 0; l < K; ++l) {
+        const uint64_t m = __ballot(lev == l);
+        if (lev == l) within = __popcll(m & (((uint64_t)1 << lane) - 1));
+        if (lane == 0) sh.lvl_cnt[wav][l] = __popcll(m);
       }
     }
-    const int idx = sh.out_idx[t];
-    sh.out_par[idx] = parent;
-    tokens_out[idx] = sh.best_tok[bcur][t];
-    parents_out[idx] = parent;
+    for (int i = t; i < K * PRUNE_SMALL / 16; i += PRUNE_THREADS)
+      reinterpret_cast<uint4 *>(sh.pos)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
+    __syncthreads();
+    if (t < n_best) {
+      int idx = 1 + within + (wav == 1 ? sh.lvl_cnt[0][lev] : 0);
+      for (int l = 0; l < lev; ++l) idx += sh.lvl_cnt[0][l] + sh.lvl_cnt[1][l];
+      sh.out_idx[t] = idx;
+      sh.pos[lev * PRUNE_SMALL + key_creation(key)] = (uint8_t)idx;
+    }
+    __syncthreads();
+    if (t < n_best) {
+      int parent = 0;
+      if (lev > 0) {
+        const int v = sh.pos[(lev - 1) * PRUNE_SMALL + sh.best_par[bcur][t]];
+        parent = v == 0xFF ? -2 : v;                   // -2 only if the set were not ancestor-closed
+      }
+      const int idx = sh.out_idx[t];
+      sh.out_par[idx] = parent;
+      tokens_out[idx] = sh.best_tok[bcur][t];
+      parents_out[idx] = parent;
+    }
+  } else {
+    if (t < n_best) {
+      const int lev = key_level(sh.best_key[bcur][t]);
+      int idx = 1;
+#pragma unroll 8
+      for (int j = 0; j < n_best; ++j) {
+        const int lj = key_level(sh.best_key[bcur][j]);
+        idx += (lj < lev) || (lj == lev && j < t);
+      }
+      sh.out_idx[t] = idx;
+    }
+    __syncthreads();
+    if (t < n_best) {
+      const uint64_t key = sh.best_key[bcur][t];
+      const int lev = key_level(key);
+      int parent = 0;
+      if (lev > 0) {
+        parent = -2;                                   // stays -2 only if the set were not ancestor-closed
+        const int want = sh.best_par[bcur][t];
+#pragma unroll 8
+        for (int j = 0; j < n_best; ++j) {
+          const uint64_t kj = sh.best_key[bcur][j];
+          if (key_level(kj) == lev - 1 && key_creation(kj) == want) parent = sh.out_idx[j];
+        }
+      }
+      const int idx = sh.out_idx[t];
+      sh.out_par[idx] = parent;
+      tokens_out[idx] = sh.best_tok[bcur][t];
+      parents_out[idx] = parent;
+    }
   }
   if (t == 0) {
     sh.out_par[0] = -1;
