@@ -48,6 +48,9 @@ def _compare(case, model, params, tokens, parents, mask, n_nodes):
     (3, 8, 13, 20, 60, 64),      # largest k whose possible contexts are all resolved up front
     (3, 8, 14, 20, 60, 64),      # smallest k that looks up level by level
     (2, 16, 12, 12, 100, 32),    # bigram model, deepest draft
+    (3, 8, 8, 32, 60, 64),       # 256 expansions per level: the most the single-wavefront level loop takes
+    (3, 8, 8, 32, 128, 64),      # ... with more than 64 of them kept per level (two ranking passes)
+    (3, 8, 9, 29, 60, 64),       # 261 expansions: just beyond it
 ])
 def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
     params = otp.PruneParams(k=k, beam_w=w, budget=budget)
@@ -119,6 +122,19 @@ def test_all_scores_tie():
     model = NgramModel(2, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
     for budget in (2, 5, 14, 40):
         params = otp.PruneParams(k=k, beam_w=2, budget=budget, w_ng=0.0)
+        tokens, parents, mask, n_nodes = _gpu_prune([case], params)
+        _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
+
+
+def test_wide_levels_of_tied_scores():
+    """Every expansion of a level ties (256 of them at the widest): the threshold search cannot
+    separate them, all are ranked, and creation order decides."""
+    K, k = 5, 8
+    case = ds.make_prune_case(7350, vocab=151936, K=K, k=k, n_gram=3, S=64)
+    case = ds.PruneCase(case.ids, np.zeros_like(case.scores), case.ctx_tail, case.table)
+    model = NgramModel(3, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
+    for w, budget in ((32, 60), (32, 128), (20, 100)):
+        params = otp.PruneParams(k=k, beam_w=w, budget=budget, w_ng=0.0)
         tokens, parents, mask, n_nodes = _gpu_prune([case], params)
         _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
 
