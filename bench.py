@@ -71,13 +71,20 @@ def bench_batched(cfg, args, seed) -> dict:
     import paper_2601_19278_amd as dart
     from dart_synth.tensors import make_ragged_lengths
 
+    fe = args.front_end
     t0 = time.perf_counter()
-    W = ds.make_weights(cfg, seed)
     lens = make_ragged_lengths(cfg, seed + 1).tolist()
-    hiddens = [ds.make_hidden(cfg, seed + 2 + b, n=lens[b]) for b in range(cfg.batch)]
+    if fe:          # the target's raw outputs: 3 concatenated hidden states + following tokens
+        W = ds.make_frontend_weights(cfg, seed)
+        raw = [ds.make_features(cfg, seed + 2 + b, n=lens[b]) for b in range(cfg.batch)]
+        hiddens = [f for f, _ in raw]
+        tok_devs = [torch.from_numpy(t).cuda() for _, t in raw]
+    else:
+        W = ds.make_weights(cfg, seed)
+        hiddens = [ds.make_hidden(cfg, seed + 2 + b, n=lens[b]) for b in range(cfg.batch)]
     counts = ds.make_ngram_counts(cfg, seed + 3)
     t_gen = time.perf_counter() - t0
-    ctx = dart.DraftContext(cfg, W)
+    ctx = dart.DraftContext(cfg, W, feat_dim=3 * cfg.d if fe else 0)
     table = dart.NgramTable(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
     devs = [dart.bf16_bits_to_tensor(h) for h in hiddens]
     B, K, k = cfg.batch, cfg.K, cfg.topk
@@ -94,7 +101,10 @@ def bench_batched(cfg, args, seed) -> dict:
     warm = [n - 1 for n in lens]
 
     def forward(cached):
-        ctx.draft_forward_batched(devs, lens, cached, K, out=logits)
+        if fe:
+            ctx.draft_forward_features_batched(devs, tok_devs, lens, cached, K, out=logits)
+        else:
+            ctx.draft_forward_batched(devs, lens, cached, K, out=logits)
 
     def topk():
         ctx.topk(logits.view(B * K, cfg.vocab), k, 1e-9, out=tk)
@@ -137,6 +147,8 @@ def bench_batched(cfg, args, seed) -> dict:
     lm_bytes = p["lm_head"] * 2 + B * K * cfg.vocab * 4
     kv = sum(2 * cfg.n_kv_heads * (n + K - 1) * cfg.head_dim * 2 for n in lens)
     fwd_bytes = p["total"] * 2 + kv + B * K * cfg.vocab * 4
+    if fe:      # FC layer and the second half of the 2d-wide Q/K/V input
+        fwd_bytes += (3 * cfg.d * cfg.d + cfg.d * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim) * 2
     achieved = lm_bytes / (lm_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (LM head, 128 rows)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -154,7 +166,8 @@ def bench_batched(cfg, args, seed) -> dict:
         b = int(np.argmin(lens))
         model = NgramModel(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
         t0 = time.perf_counter()
-        ref = odf.draft_forward(cfg, W, hiddens[b], K)
+        ref = (odf.draft_forward_features(cfg, W, hiddens[b], raw[b][1], K) if fe
+               else odf.draft_forward(cfg, W, hiddens[b], K))
         ids, scores = otk.topk_rows(ref, k, 1e-9)
         otp.tree_prune(ids, scores, counts.keys[b].astype(np.int32), model,
                        otp.PruneParams(k=k, beam_w=cfg.beam_w, budget=cfg.budget))
@@ -172,7 +185,8 @@ def bench_batched(cfg, args, seed) -> dict:
         "config": {"workload": f"{cfg.name}: d={cfg.d} heads={cfg.n_q_heads}/{cfg.n_kv_heads}x{cfg.head_dim} "
                                f"ffn={cfg.ffn} vocab={cfg.vocab} ragged ctx {min(lens)}..{max(lens)} K={cfg.K} "
                                f"topk={cfg.topk} beam_w={cfg.beam_w} budget={cfg.budget} "
-                               f"trigram_keys={cfg.n_keys} batch={B} warm n_new=1"},
+                               f"trigram_keys={cfg.n_keys} batch={B} warm n_new=1"
+                               + (" front-end(FC 3d->d + embeddings)" if fe else "")},
         "roofline": roofline, "cpu_baseline": cpu,
         "stages": {a: (round(v, 2) if v >= 1.0 else float(f"{v:.3e}")) if isinstance(v, float) else v
                    for a, v in stages.items()},

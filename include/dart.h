@@ -154,6 +154,19 @@ dart_status dart_draft_forward_batched(dart_ctx *ctx, int batch, const void *con
                                        const int32_t *ctx_len, const int32_t *n_cached, int K,
                                        float *logits_out, void *stream);
 
+/* dart_draft_forward_features for `batch` sequences in slots 0..batch-1 (ragged lengths;
+ * contexts created with front_end = 1; Sec. 3.2, Fig. 3).
+ *   features     HOST array of `batch` device pointers, each [ctx_len[b]][feat_dim]
+ *   next_tokens  HOST array of `batch` device pointers, each [ctx_len[b]] int32
+ *   ctx_len, n_cached   HOST arrays [batch]
+ *   logits_out   device [batch][K][vocab] fp32
+ * Errors as dart_draft_forward_batched; STATE on a context without the front end. */
+dart_status dart_draft_forward_features_batched(dart_ctx *ctx, int batch,
+                                                const void *const *features,
+                                                const int32_t *const *next_tokens,
+                                                const int32_t *ctx_len, const int32_t *n_cached,
+                                                int K, float *logits_out, void *stream);
+
 /* Per-row top-k with log-softmax scores (Alg. 1, App. D "s_logit").
  *   logits      device [rows][vocab] fp32 (finite values), rows <= max_batch*max_K
  *   ids_out     device [rows][k] int32, by (logit descending, token id ascending)

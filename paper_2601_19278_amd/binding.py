@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
-    "dart_draft_forward_features",
+    "dart_draft_forward_features", "dart_draft_forward_features_batched",
     "dart_draft_forward_batched", "dart_topk", "dart_ngram_create", "dart_ngram_destroy",
     "dart_tree_prune", "dart_tree_verify_greedy", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
 )
@@ -85,6 +85,9 @@ def load_library() -> C.CDLL:
     lib.dart_draft_forward_features.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
     lib.dart_draft_forward_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
                                                C.POINTER(C.c_int32), i32, vp, vp]
+    lib.dart_draft_forward_features_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp),
+                                                        C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                                        i32, vp, vp]
     lib.dart_topk.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp]
     lib.dart_ngram_create.argtypes = [i32, i64, i32, vp, vp, vp, f32, C.POINTER(vp)]
     lib.dart_ngram_destroy.argtypes = [vp]
@@ -207,6 +210,23 @@ class DraftContext:
         _check(self._lib.dart_draft_forward_batched(self._h, B, ptrs, lens, cached, K,
                                                     out.data_ptr(), _stream_ptr(stream)),
                "dart_draft_forward_batched")
+        return out
+
+    def draft_forward_features_batched(self, features, next_tokens, ctx_lens, n_cached, K: int,
+                                       out=None, stream=None):
+        """dart_draft_forward_features_batched: lists of CUDA tensors (features [n_b][feat_dim],
+        next_tokens int32 [n_b]) and of lengths; returns logits [B][K][vocab]."""
+        torch = _torch()
+        B = len(features)
+        if out is None:
+            out = torch.empty((B, K, self.vocab), dtype=torch.float32, device=features[0].device)
+        fptrs = (C.c_void_p * B)(*[f.data_ptr() for f in features])
+        tptrs = (C.c_void_p * B)(*[t.data_ptr() for t in next_tokens])
+        lens = (C.c_int32 * B)(*[int(v) for v in ctx_lens])
+        cached = (C.c_int32 * B)(*[int(v) for v in n_cached])
+        _check(self._lib.dart_draft_forward_features_batched(self._h, B, fptrs, tptrs, lens, cached,
+                                                             K, out.data_ptr(), _stream_ptr(stream)),
+               "dart_draft_forward_features_batched")
         return out
 
     def topk(self, logits, k: int, eps: float = 1e-9, stream=None, out=None):

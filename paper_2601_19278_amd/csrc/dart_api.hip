@@ -195,6 +195,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
       c->gch_o = gemm_bf16_chunks(c->q_dim, (d + 15) / 16);
       c->gch_gu = gemm_bf16_chunks(d, 2 * F / 16);
       c->gch_down = gemm_bf16_chunks(F, (d + 15) / 16);
+      if (g.front_end) c->gch_fc = gemm_bf16_chunks(g.feat_dim, (d + 15) / 16);
       ch_qkv = std::max(ch_qkv, c->gch_qkv);
       ch_o = std::max(ch_o, c->gch_o);
       ch_gu = std::max(ch_gu, c->gch_gu);
@@ -231,12 +232,14 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   if (g.dtype == DART_BF16) {
     size_t pb = gemm_bf16_pack_bytes(c->kv_rows, in_dim);
     for (int kd : {in_dim, c->q_dim, F}) pb = std::max(pb, gemm_bf16_pack_bytes(c->ws_rows, kd));
+    if (g.front_end)
+      pb = std::max(pb, gemm_bf16_pack_bytes(std::max(c->ws_rows, c->kv_rows), g.feat_dim));
     HIP_TRY(hipMalloc(&c->xpack, pb));
   }
   HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * in_dim));
   if (g.front_end) {
     c->fc_rows = std::max(c->ws_rows, c->kv_rows);
-    const int ch_fc = g.dtype == DART_BF16 ? c->split_fc : 1;
+    const int ch_fc = g.dtype == DART_BF16 ? std::max(c->split_fc, c->gch_fc) : 1;
     HIP_TRY(dev_alloc(&c->feat32, (size_t)c->fc_rows * g.feat_dim));
     HIP_TRY(dev_alloc(&c->fc_part, (size_t)ch_fc * c->fc_rows * d));
   }
@@ -299,7 +302,8 @@ struct SeqJob {
 // the rows are gathered from the prefix representation / mask embeddings and normed; with it
 // (Sec. 3.2) the feature rows first go through the FC layer and are joined by the shifted
 // token embeddings.
-hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid, hipStream_t st) {
+hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid, bool gemm,
+                       hipStream_t st) {
   const dart_config &g = c->cfg;
   if (!g.front_end)
     return launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, xn, resid, st);
@@ -307,7 +311,8 @@ hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid,
   HIP_TRY(launch_feature_rows(g.dtype, sb, g.feat_dim, c->feat32, st));
   const size_t cs = (size_t)c->fc_rows * g.d;
   int chunks = 1;
-  HIP_TRY(project(c, c->wfc, 0, g.d, c->feat32, M, c->fc_part, g.d, cs, c->split_fc, 0, &chunks, st));
+  HIP_TRY(project(c, c->wfc, 0, g.d, c->feat32, M, c->fc_part, g.d, cs, c->split_fc,
+                  gemm ? c->gch_fc : 0, &chunks, st));
   return launch_front_norm(g.dtype, sb, c->fc_part, chunks, cs, c->embed, c->mask_emb, c->g_in,
                            c->g_emb, g.d, g.rms_eps, xn, resid, st);
 }
@@ -318,7 +323,7 @@ hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int M = sb.row_off[sb.B];
   (void)g;
-  HIP_TRY(input_stage(c, sb, c->xn_kv, nullptr, st));
+  HIP_TRY(input_stage(c, sb, c->xn_kv, nullptr, gemm, st));
   const size_t cs = (size_t)c->kv_rows * 2 * c->kv_dim;
   int chunks = 1;
   HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn_kv, M, c->kv_part, 2 * c->kv_dim, cs,
@@ -378,7 +383,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   }
   const int M = sb.row_off[B], QR = B * K;       // pass rows, query rows
   const size_t W = c->ws_rows;
-  HIP_TRY(input_stage(c, sb, c->xn, c->resid, st));
+  HIP_TRY(input_stage(c, sb, c->xn, c->resid, gemm, st));
   int chunks = 1;
   size_t cs = W * c->qkv_dim;
   HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv,
@@ -540,21 +545,24 @@ dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx
   return DART_OK;
 }
 
-dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const *hidden,
-                                       const int32_t *ctx_len, const int32_t *n_cached, int K,
-                                       float *logits_out, void *stream) {
-  if (!c || !hidden || !ctx_len || !n_cached || !logits_out) return DART_ERR_ARG;
+// Shared body of the two batched entry points (tokens = null without the front end).
+static dart_status forward_batched(dart_ctx *c, int batch, const void *const *rows,
+                                   const int32_t *const *tokens, const int32_t *ctx_len,
+                                   const int32_t *n_cached, int K, float *logits_out, void *stream) {
+  if (!c || !rows || !ctx_len || !n_cached || !logits_out) return DART_ERR_ARG;
   if (batch < 1 || batch > c->cfg.max_batch) return DART_ERR_ARG;
-  if (c->cfg.front_end) return DART_ERR_STATE;
+  if ((c->cfg.front_end != 0) != (tokens != nullptr)) return DART_ERR_STATE;
   for (int b = 0; b < batch; ++b) {
-    dart_status s = check_forward_args(c, b, hidden[b], ctx_len[b], n_cached[b], K, logits_out);
+    dart_status s = check_forward_args(c, b, rows[b], ctx_len[b], n_cached[b], K, logits_out);
     if (s != DART_OK) return s;
+    if (tokens && !tokens[b]) return DART_ERR_ARG;
   }
   for (int b0 = 0; b0 < batch; b0 += DART_SEQ_GROUP) {
     const int nb = std::min(DART_SEQ_GROUP, batch - b0);
     SeqJob jobs[DART_SEQ_GROUP];
     for (int i = 0; i < nb; ++i) {
-      jobs[i] = SeqJob{b0 + i, hidden[b0 + i], ctx_len[b0 + i], n_cached[b0 + i]};
+      jobs[i] = SeqJob{b0 + i, rows[b0 + i], ctx_len[b0 + i], n_cached[b0 + i]};
+      if (tokens) jobs[i].tokens = tokens[b0 + i];
       c->cached_rows[b0 + i] = 0;
     }
     hipError_t e = forward_group(c, nb, jobs, K, true, logits_out + (size_t)b0 * K * c->cfg.vocab,
@@ -563,6 +571,20 @@ dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const
     for (int i = 0; i < nb; ++i) c->cached_rows[b0 + i] = ctx_len[b0 + i];
   }
   return DART_OK;
+}
+
+dart_status dart_draft_forward_batched(dart_ctx *c, int batch, const void *const *hidden,
+                                       const int32_t *ctx_len, const int32_t *n_cached, int K,
+                                       float *logits_out, void *stream) {
+  return forward_batched(c, batch, hidden, nullptr, ctx_len, n_cached, K, logits_out, stream);
+}
+
+dart_status dart_draft_forward_features_batched(dart_ctx *c, int batch, const void *const *features,
+                                                const int32_t *const *next_tokens,
+                                                const int32_t *ctx_len, const int32_t *n_cached,
+                                                int K, float *logits_out, void *stream) {
+  if (!next_tokens) return DART_ERR_ARG;
+  return forward_batched(c, batch, features, next_tokens, ctx_len, n_cached, K, logits_out, stream);
 }
 
 dart_status dart_topk(dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,

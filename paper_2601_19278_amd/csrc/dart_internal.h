@@ -127,7 +127,7 @@ struct dart_ctx {
   void *embed = nullptr, *g_emb = nullptr;
   float *feat32 = nullptr;        // [max(ws_rows, kv_rows)][feat_dim] features of a pass as fp32
   float *fc_part = nullptr;       // [chunks][max(ws_rows, kv_rows)][d] FC partial sums
-  int split_fc = 1, fc_rows = 0;
+  int split_fc = 1, gch_fc = 1, fc_rows = 0;
   float *rope_cos = nullptr, *rope_sin = nullptr;   // [t_cap][hd/2]
   // draft K/V buffers [batch][Hkv][t_cap * hd]: fp32 rows [t_cap][hd]; bf16 operand tiles (attn_k_index, attn_vt_index)
   void *kbuf = nullptr, *vbuf = nullptr;

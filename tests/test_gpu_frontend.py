@@ -101,3 +101,32 @@ def test_front_end_full_size_1p7b_shapes():
     warm = ctx.draft_forward_features(f_dev, t_dev, cfg.ctx, cfg.K, n_cached=cfg.ctx - 4).cpu().numpy()
     np.testing.assert_array_equal(warm, cold)
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["bf16_small", "bf16_mid"])
+def test_front_end_batched_matches_oracle_cold_and_warm(name):
+    """dart_draft_forward_features_batched: ragged sequences share every launch (FC and the other
+    projections on the multi-row kernel); each sequence against the oracle, and a warm call
+    reproduces the cold one bit for bit."""
+    import torch
+    import paper_2601_19278_amd as dart
+    cfg, feat_dim = CASES[name]
+    lens = [cfg.ctx, 17, cfg.ctx // 2 + 3, 64, 1]
+    W = ds.make_frontend_weights(cfg, 6300, feat_dim=feat_dim)
+    seqs = [ds.make_features(cfg, 6301 + b, n=n, feat_dim=feat_dim) for b, n in enumerate(lens)]
+    refs = [odf.draft_forward_features(cfg, W, f, t, cfg.K) for f, t in seqs]
+    ctx = dart.DraftContext(cfg, W, max_batch=len(lens), feat_dim=feat_dim)
+    f_dev = [hidden_to_device(cfg, f) for f, _ in seqs]
+    t_dev = [torch.from_numpy(t).cuda() for _, t in seqs]
+    cold = ctx.draft_forward_features_batched(f_dev, t_dev, lens, [0] * len(lens), cfg.K).cpu().numpy()
+    for b in range(len(lens)):
+        ok, msg = logits_close(cold[b], refs[b], **BF16_TOL)
+        assert ok, f"{name} sequence {b} (n={lens[b]}): {msg}"
+    for cached in ([n - 1 for n in lens], [max(0, n - 5) for n in lens], [0, 16, 3, 63, 0]):
+        warm = ctx.draft_forward_features_batched(f_dev, t_dev, lens, cached, cfg.K).cpu().numpy()
+        np.testing.assert_array_equal(warm, cold)
+    # the fused-input batched call is refused on a front-end context
+    with pytest.raises(dart.DartError) as ei:
+        ctx.draft_forward_batched(f_dev, lens, [0] * len(lens), cfg.K)
+    assert ei.value.status == 5
+    ctx.close()
