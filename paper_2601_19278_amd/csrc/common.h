@@ -70,6 +70,46 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 
 // Wavefront-wide max of a 64-bit key: max of the high words, then max of the low words among
 // the lanes that hold that high word.
+// Wavefront-wide float sum / max and integer inclusive prefix sum on the DPP data path: row
+// shifts by 1, 2, 4, 8 build an inclusive scan inside each row of 16 lanes (a lane without a
+// source takes the identity), row_bcast:15 into rows 1 and 3 and row_bcast:31 into rows 2 and 3
+// extend it over the wavefront; lane 63 then holds the total.  A few cycles per step, where the
+// __shfl forms go through the LDS crossbar.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float identity, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v), CTRL,
+                                                     ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v += dpp_f32<0x111, 0xf>(0.f, v);
+  v += dpp_f32<0x112, 0xf>(0.f, v);
+  v += dpp_f32<0x114, 0xf>(0.f, v);
+  v += dpp_f32<0x118, 0xf>(0.f, v);
+  v += dpp_f32<0x142, 0xa>(0.f, v);
+  v += dpp_f32<0x143, 0xc>(0.f, v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+__device__ __forceinline__ float wave_max_dpp(float v) {
+  const float lo = -3.0e38f;
+  v = fmaxf(v, dpp_f32<0x111, 0xf>(lo, v));
+  v = fmaxf(v, dpp_f32<0x112, 0xf>(lo, v));
+  v = fmaxf(v, dpp_f32<0x114, 0xf>(lo, v));
+  v = fmaxf(v, dpp_f32<0x118, 0xf>(lo, v));
+  v = fmaxf(v, dpp_f32<0x142, 0xa>(lo, v));
+  v = fmaxf(v, dpp_f32<0x143, 0xc>(lo, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// Inclusive prefix sum over the lanes (lane i: sum of lanes 0..i).
+__device__ __forceinline__ int wave_scan_add_dpp(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
+  return v;
+}
+
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   const uint32_t hi = (uint32_t)(v >> 32);
   const uint32_t mh = wave_max_u32(hi);

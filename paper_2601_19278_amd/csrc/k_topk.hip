@@ -11,8 +11,8 @@
 // depend on which workgroup happens to be last.
 //
 // Selection inside a wavefront (wave_select): the k-th largest of the 64 lane maxima is a
-// lower bound T of the k-th largest value, found by a bitwise search with ballots; the
-// entries >= T (at least k, in practice few more) are compacted into LDS and ranked by
+// lower bound T of the k-th largest value, found (to 16 bits) by a bitwise search with ballots;
+// the entries >= T (at least k, in practice few more) are compacted into LDS and ranked by
 // counting.  This replaces k dependent wavefront-wide max reductions by a handful of
 // independent steps.  If ties make the candidate set overflow its LDS buffer the code falls
 // back to the k sequential extractions.
@@ -59,21 +59,20 @@ __device__ __forceinline__ void wave_select(const uint64_t (&key)[N], int k, uin
   uint32_t hm = 0;                       // lane maximum of the value words (real keys are > 0)
 #pragma unroll
   for (int e = 0; e < N; ++e) hm = max(hm, (uint32_t)(key[e] >> 32));
-  uint32_t T = 0;                        // largest T with at least k lane maxima >= T
-  for (int bit = 31; bit >= 0; --bit) {
+  // T: at least k lane maxima are >= T.  Searched bit by bit from the top and only down to bit
+  // 16 (sign, exponent and 7 significand bits): the low bits would only trim the few entries
+  // that share that prefix with the k-th lane maximum, and each step is a dependent
+  // compare-ballot-count round trip.
+  uint32_t T = 0;
+  for (int bit = 31; bit >= 16; --bit) {
     const uint32_t trial = T | (1u << bit);
     if (__popcll(__ballot(hm >= trial)) >= k) T = trial;
   }
   int c = 0;
 #pragma unroll
   for (int e = 0; e < N; ++e) c += key[e] != 0 && (uint32_t)(key[e] >> 32) >= T;
-  int incl = c;                          // inclusive prefix sum over the lanes
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int v = __shfl_up(incl, off, DART_WAVE);
-    if (lane >= off) incl += v;
-  }
-  const int m = __shfl(incl, 63, DART_WAVE);
+  const int incl = wave_scan_add_dpp(c);  // inclusive prefix sum over the lanes
+  const int m = __builtin_amdgcn_readlane(incl, 63);
   if (m > TOPK_CAP) {                    // heavy ties: sequential extraction
     wave_extract(key, k, [&](int it, uint64_t best) {
       if (lane == 0) emit(it, best);
@@ -138,12 +137,12 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
       key[e] = 0;                                  // below every real key
     }
   }
-  mx = wave_max(mx);
+  mx = wave_max_dpp(mx);
   float se = 0.f;
 #pragma unroll
   for (int e = 0; e < TOPK_PER_THREAD; ++e)
     if (key[e] != 0) se += expf(val[e] - mx);
-  se = wave_sum(se);
+  se = wave_sum_dpp(se);
   if (lane == 0) {
     wms[wave][0] = mx;
     wms[wave][1] = se;
@@ -182,13 +181,13 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
   // the row's last chunk is in: log-sum-exp from the chunk statistics (fixed order)
   float rmx = -3.0e38f;
   for (int c = lane; c < nchunks; c += 64) rmx = fmaxf(rmx, fetch(&ms[((size_t)row * nchunks + c) * 2]));
-  rmx = wave_max(rmx);
+  rmx = wave_max_dpp(rmx);
   float rse = 0.f;
   for (int c = lane; c < nchunks; c += 64) {
     const size_t sl = (size_t)row * nchunks + c;
     rse += fetch(&ms[sl * 2 + 1]) * expf(fetch(&ms[sl * 2]) - rmx);
   }
-  rse = wave_sum(rse);
+  rse = wave_sum_dpp(rse);
   const float lse = rmx + logf(rse);
   auto emit = [&](int it, uint64_t best) {
     const float logit = f32_unsortable((uint32_t)(best >> 32));
