@@ -306,7 +306,8 @@ hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid,
                        hipStream_t st) {
   const dart_config &g = c->cfg;
   if (!g.front_end)
-    return launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, xn, resid, st);
+    return launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, xn, resid,
+                                 gemm ? c->xpack : nullptr, st);
   const int M = sb.row_off[sb.B];
   HIP_TRY(launch_feature_rows(g.dtype, sb, g.feat_dim, c->feat32, st));
   const size_t cs = (size_t)c->fc_rows * g.d;
@@ -322,11 +323,11 @@ hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid,
 hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int M = sb.row_off[sb.B];
-  (void)g;
   HIP_TRY(input_stage(c, sb, c->xn_kv, nullptr, gemm, st));
   const size_t cs = (size_t)c->kv_rows * 2 * c->kv_dim;
   int chunks = 1;
-  HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, c->xn_kv, M, c->kv_part, 2 * c->kv_dim, cs,
+  const float *xin = gemm && !g.front_end ? nullptr : c->xn_kv;    // null: operand tiles already packed
+  HIP_TRY(project(c, c->wqkv, c->q_dim, 2 * c->kv_dim, xin, M, c->kv_part, 2 * c->kv_dim, cs,
                   c->split_qkv, gemm ? c->gch_qkv : 0, &chunks, st));
   return launch_qkv_post(c, sb, c->kv_part, chunks, cs, 2 * c->kv_dim, c->q_dim, st);
 }
@@ -386,7 +387,8 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   HIP_TRY(input_stage(c, sb, c->xn, c->resid, gemm, st));
   int chunks = 1;
   size_t cs = W * c->qkv_dim;
-  HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, c->xn, M, c->qkv, c->qkv_dim, cs, c->split_qkv,
+  HIP_TRY(project(c, c->wqkv, 0, c->qkv_dim, gemm && !g.front_end ? nullptr : c->xn, M, c->qkv,
+                  c->qkv_dim, cs, c->split_qkv,
                   gemm ? c->gch_qkv : 0, &chunks, st));
   HIP_TRY(launch_qkv_post(c, sb, c->qkv, chunks, cs, c->qkv_dim, 0, st));
   HIP_TRY(launch_attention(c, sb, st));
@@ -394,14 +396,16 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   cs = W * g.d;
   HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, QR, c->proj, g.d, cs, c->split_o,
                   gemm ? c->gch_o : 0, &chunks, st));
+  // on the multi-row path the norm kernels write the next projection's operand tiles themselves
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, QR, g.d,
-                            g.rms_eps, c->y, c->yn, st));
+                            g.rms_eps, c->y, c->yn, gemm ? c->xpack : nullptr, st));
+  const float *yn_in = gemm ? nullptr : c->yn;
   cs = W * 2 * g.ffn;
   if (gemm && c->gch_gu == 1) {     // SwiGLU in the projection's epilogue
-    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, c->yn, QR, c->xpack, c->hmid, g.ffn, 0, 1, 1,
+    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, yn_in, QR, c->xpack, c->hmid, g.ffn, 0, 1, 1,
                              st));
   } else {
-    HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, c->yn, QR, c->proj, 2 * g.ffn, cs, c->split_gu,
+    HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, yn_in, QR, c->proj, 2 * g.ffn, cs, c->split_gu,
                     gemm ? c->gch_gu : 0, &chunks, st));
     HIP_TRY(launch_swiglu(c->proj, chunks, cs, QR, g.ffn, g.dtype == DART_BF16, c->hmid, st));
   }
@@ -409,8 +413,8 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down,
                   gemm ? c->gch_down : 0, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
-                            c->u, c->yn, st));
-  HIP_TRY(project(c, c->wlm, 0, g.vocab, c->yn, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
+                            c->u, c->yn, gemm ? c->xpack : nullptr, st));
+  HIP_TRY(project(c, c->wlm, 0, g.vocab, yn_in, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
   return hipSuccess;
 }
 

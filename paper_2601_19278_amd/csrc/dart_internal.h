@@ -176,9 +176,11 @@ extern int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_
 
 // All launchers only enqueue work on `st` and return the launch status.
 
+// pack != null (bf16): the normed rows go to the packed operand tiles of a multi-row projection
+// (launch_gemm_bf16 with X = null consumes them) instead of xn.
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
                                  const void *gain, int d, float eps, float *xn, float *resid,
-                                 hipStream_t st);
+                                 void *pack, hipStream_t st);
 
 // Front end, step 1: the feature rows of a pass as fp32 (mask rows: zeros).
 hipError_t launch_feature_rows(int dtype, const SeqBatch &sb, int feat_dim, float *out, hipStream_t st);
@@ -190,9 +192,11 @@ hipError_t launch_front_norm(int dtype, const SeqBatch &sb, const float *fc_part
                              const void *gain_g, const void *gain_e, int d, float eps, float *xn,
                              float *resid, hipStream_t st);
 
+// pack != null (bf16): yn is also written as the packed operand tiles of a multi-row projection
+// of `rows` rows (launch_gemm_bf16 with X = null consumes them).
 hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
-                             float eps, float *y, float *yn, hipStream_t st);
+                             float eps, float *y, float *yn, void *pack, hipStream_t st);
 
 hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const float *X, int M,
                            float *out, int out_stride, hipStream_t st);

@@ -87,24 +87,16 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const float *__restrict_
   const int lane = item & 63, tile = (item >> 6) % ntiles, t = (item >> 6) / ntiles;
   if (t >= ksteps) return;
   const int r = tile * 16 + (lane & 15), k = t * 32 + 8 * (lane >> 4);
-  uint32_t h[4] = {0, 0, 0, 0}, l[4] = {0, 0, 0, 0};
+  uint4 *pk = reinterpret_cast<uint4 *>(Xp);
   if (r < M && k < Kd) {
     const float *src = X + (size_t)r * Kd + k;
     const float4 a = *reinterpret_cast<const float4 *>(src);
     const float4 b = *reinterpret_cast<const float4 *>(src + 4);
     const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const bf16_t h0 = f32_to_bf16(x[2 * e]), h1 = f32_to_bf16(x[2 * e + 1]);
-      const bf16_t l0 = f32_to_bf16(x[2 * e] - bf16_to_f32(h0));
-      const bf16_t l1 = f32_to_bf16(x[2 * e + 1] - bf16_to_f32(h1));
-      h[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-      l[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-    }
+    pack_store8(pk, ntiles, r, k, x);
+  } else {
+    pack_zero8(pk, ntiles, r, k);
   }
-  u32x4_t *dst = Xp + ((size_t)t * ntiles + tile) * 128 + lane;
-  dst[0] = u32x4_t{h[0], h[1], h[2], h[3]};
-  dst[64] = u32x4_t{l[0], l[1], l[2], l[3]};
 }
 
 struct GemmArgs {
@@ -323,6 +315,11 @@ int gemm_bf16_chunks(int Kd, int nstrips) {
 // Row tiles the packed activations of M rows hold (whole row blocks of the kernel variant
 // that M selects) and their size in bytes.
 static int gemm_nct(int M) { return M <= 32 ? 2 : (M <= 64 ? 4 : 8); }
+void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps) {
+  const int nct = gemm_nct(M);
+  *ntiles = (M + 16 * nct - 1) / (16 * nct) * nct;
+  *ksteps = (Kd / 32 + 1) / 2 * 2;
+}
 size_t gemm_bf16_pack_bytes(int M, int Kd) {
   const int nct = gemm_nct(M), ntiles = (M + 16 * nct - 1) / (16 * nct) * nct;
   const int ksteps = (Kd / 32 + 1) / 2 * 2;

@@ -32,12 +32,21 @@ __device__ __forceinline__ void store8(float *p, const float *v) {
 // RMS-normed row (times gain) to xn[r] and, for query rows, the raw row to resid[b*K + j].
 // One workgroup per row; the row stays in registers between the two passes, and all loads
 // of a pass are issued before the first use (the kernel is pure latency otherwise).
+// pack != null: the normed rows are written as the packed operand tiles of the multi-row
+// projection that consumes them instead of xn (see resid_norm_kernel).
 template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
     SeqBatch sb, const T *__restrict__ mask_emb, const T *__restrict__ gain, int d, float eps,
-    float *__restrict__ xn, float *__restrict__ resid) {
+    float *__restrict__ xn, float *__restrict__ resid, uint4 *__restrict__ pack, int ntiles,
+    int ksteps) {
   __shared__ float red[16];
   const int i = blockIdx.x;
+  if (i >= sb.row_off[sb.B]) {              // padding rows of the packed operand (uniform)
+    for (int c = threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, i, c);
+    return;
+  }
+  if (pack)
+    for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, i, c);
   int b, pos, qi;
   seq_of_row(sb, i, b, pos, qi);
   const int n = sb.n[b];
@@ -67,7 +76,10 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
       if (qi >= 0) store8(resid + (size_t)(b * sb.K + qi) * d + c, v[j]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
-      store8(xn + (size_t)i * d + c, v[j]);
+      if (pack)
+        pack_store8(pack, ntiles, i, c, v[j]);
+      else
+        store8(xn + (size_t)i * d + c, v[j]);
     }
   }
 }
@@ -159,13 +171,22 @@ __global__ __launch_bounds__(ROW_THREADS) void front_norm_kernel(
 
 // y = resid + sum_c part[c];  yn = RMSNorm(y) * gain.  part[c] row r starts at
 // part + c*chunk_stride + r*row_stride.  Chunk partials are added in index order.
+// pack != null: yn is also written as the packed operand tiles of the multi-row projection
+// that consumes it (ntiles row tiles, ksteps k-steps); the grid then covers the padded rows
+// ntiles*16, and rows >= rows and inputs >= d are written as zeros.
 template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
     const float *__restrict__ resid, const float *__restrict__ part, int chunks, size_t chunk_stride,
-    int row_stride, const T *__restrict__ gain, int d, float eps, float *__restrict__ y,
-    float *__restrict__ yn) {
+    int row_stride, const T *__restrict__ gain, int rows, int d, float eps, float *__restrict__ y,
+    float *__restrict__ yn, uint4 *__restrict__ pack, int ntiles, int ksteps) {
   __shared__ float red[16];
   const int r = blockIdx.x;
+  if (r >= rows) {                          // padding rows of the packed operand (uniform)
+    for (int c = threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, r, c);
+    return;
+  }
+  if (pack)
+    for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, r, c);
   float v[ROW_MAXIT][8], g[ROW_MAXIT][8];
 #pragma unroll
   for (int j = 0; j < ROW_MAXIT; ++j) {
@@ -211,6 +232,7 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
       store8(yn + (size_t)r * d + c, v[j]);
+      if (pack) pack_store8(pack, ntiles, r, c, v[j]);
     }
   }
 }
@@ -242,16 +264,26 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ g
   h[(size_t)r * ffn + f] = g / (1.0f + expf(-g)) * u;
 }
 
+void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps);
+
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
                                  const void *gain, int d, float eps, float *xn, float *resid,
-                                 hipStream_t st) {
+                                 void *pack, hipStream_t st) {
   const int M = sb.row_off[sb.B];
+  int ntiles = 0, ksteps = 0, grid = M;
+  if (pack) {
+    if (dtype != DART_BF16 || (d & 7)) return hipErrorInvalidValue;
+    gemm_bf16_pack_shape(M, d, &ntiles, &ksteps);
+    grid = ntiles * 16;
+  }
   if (dtype == DART_BF16)
-    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, sb,
-                       (const bf16_t *)mask_emb, (const bf16_t *)gain, d, eps, xn, resid);
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(grid), dim3(ROW_THREADS), 0, st, sb,
+                       (const bf16_t *)mask_emb, (const bf16_t *)gain, d, eps, xn, resid,
+                       (uint4 *)pack, ntiles, ksteps);
   else
-    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(M), dim3(ROW_THREADS), 0, st, sb,
-                       (const float *)mask_emb, (const float *)gain, d, eps, xn, resid);
+    hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(grid), dim3(ROW_THREADS), 0, st, sb,
+                       (const float *)mask_emb, (const float *)gain, d, eps, xn, resid,
+                       (uint4 *)nullptr, 0, 0);
   return hipGetLastError();
 }
 
@@ -282,13 +314,21 @@ hipError_t launch_front_norm(int dtype, const SeqBatch &sb, const float *fc_part
 
 hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
-                             float eps, float *y, float *yn, hipStream_t st) {
+                             float eps, float *y, float *yn, void *pack, hipStream_t st) {
+  int ntiles = 0, ksteps = 0, grid = rows;
+  if (pack) {
+    if (dtype != DART_BF16 || (d & 7)) return hipErrorInvalidValue;
+    gemm_bf16_pack_shape(rows, d, &ntiles, &ksteps);
+    grid = ntiles * 16;
+  }
   if (dtype == DART_BF16)
-    hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(rows), dim3(ROW_THREADS), 0, st, resid, part, chunks,
-                       chunk_stride, row_stride, (const bf16_t *)gain, d, eps, y, yn);
+    hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(grid), dim3(ROW_THREADS), 0, st, resid, part,
+                       chunks, chunk_stride, row_stride, (const bf16_t *)gain, rows, d, eps, y, yn,
+                       (uint4 *)pack, ntiles, ksteps);
   else
-    hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(rows), dim3(ROW_THREADS), 0, st, resid, part, chunks,
-                       chunk_stride, row_stride, (const float *)gain, d, eps, y, yn);
+    hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(grid), dim3(ROW_THREADS), 0, st, resid, part,
+                       chunks, chunk_stride, row_stride, (const float *)gain, rows, d, eps, y, yn,
+                       (uint4 *)nullptr, 0, 0);
   return hipGetLastError();
 }
 
