@@ -391,10 +391,12 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
                   c->qkv_dim, cs, c->split_qkv,
                   gemm ? c->gch_qkv : 0, &chunks, st));
   HIP_TRY(launch_qkv_post(c, sb, c->qkv, chunks, cs, c->qkv_dim, 0, st));
-  HIP_TRY(launch_attention(c, sb, st));
+  // (an odd number of 32-input steps would need a zeroed extra step in the packed operand)
+  const bool pack_att = gemm && (c->q_dim / 32) % 2 == 0;
+  HIP_TRY(launch_attention(c, sb, pack_att ? c->xpack : nullptr, st));
 
   cs = W * g.d;
-  HIP_TRY(project(c, c->wo, 0, g.d, c->att_out, QR, c->proj, g.d, cs, c->split_o,
+  HIP_TRY(project(c, c->wo, 0, g.d, pack_att ? nullptr : c->att_out, QR, c->proj, g.d, cs, c->split_o,
                   gemm ? c->gch_o : 0, &chunks, st));
   // on the multi-row path the norm kernels write the next projection's operand tiles themselves
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, QR, g.d,

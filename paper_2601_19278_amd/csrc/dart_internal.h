@@ -233,7 +233,7 @@ hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *q
                            size_t chunk_stride, int row_stride, int col0, hipStream_t st);
 
 // Attention of the B*K query rows of the pass (compact order) over their sequences' K/V.
-hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t st);
+hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, hipStream_t st);
 
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st);

@@ -62,14 +62,18 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
 // once in parallel and kept in LDS, and the partial rows are then read with independent loads.
 constexpr int ATTN_MAX_SPLITS = 1024;   // 256 key chunks x 4 sub-ranges
 
+// pack != null: the result goes to the packed operand tiles of the multi-row O projection
+// (row = query row, input = head * hd + dim; ntiles row tiles) instead of out.
 __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork work, int Hq, int group,
                                                          int nsub,
                                                          const float *__restrict__ o_part,
                                                          const float *__restrict__ ml_part,
                                                          int nsplit, int hd,
-                                                         float *__restrict__ out) {
+                                                         float *__restrict__ out,
+                                                         uint4 *__restrict__ pack, int ntiles) {
   __shared__ float red[16];
   __shared__ float w[ATTN_MAX_SPLITS];
+  __shared__ __align__(16) float row_out[128];
   const int qv = blockIdx.x, t = threadIdx.x;
   const int b = qv / (Hq * sb.K), g = qv % Hq / group;
   const int cb = work.cum[b + 1] - work.cum[b];
@@ -90,8 +94,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork w
     den += ws * l;
   }
   den = block_sum(den, red);          // its barriers also publish w[]
-  if (t >= hd) return;
-  const float *src = o_part + (size_t)qv * nsplit * hd + t;
+  const float *src = o_part + (size_t)qv * nsplit * hd + min(t, hd - 1);
   float num = 0.f;
   int s = 0;
   for (; s + 4 <= used; s += 4) {
@@ -103,7 +106,16 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork w
     num += w[s + 3] * a3;
   }
   for (; s < used; ++s) num += w[s] * src[(size_t)s * hd];
-  out[(size_t)qv * hd + t] = num / den;
+  if (!pack) {
+    if (t < hd) out[(size_t)qv * hd + t] = num / den;
+    return;
+  }
+  row_out[t] = num / den;
+  __syncthreads();
+  if (t < hd / 8) {
+    const int row = qv / Hq, h = qv % Hq;
+    pack_store8(pack, ntiles, row, h * hd + 8 * t, &row_out[8 * t]);
+  }
 }
 
 hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, const AttnWork &work,
@@ -113,7 +125,11 @@ int attn_mfma_nsub(int Kq, int group);
 // Chunk units per attention workgroup of the bf16 path; 0 = chosen from the amount of work.
 int g_attn_seg = 0;
 
-hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t st) {
+void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps);
+
+// pack: where the multi-row O projection expects its operand tiles (bf16 only), else null and
+// the result goes to c->att_out.
+hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
   const int chunk = ATTN_KEY_CHUNK;                      // keys per chunk
@@ -157,8 +173,15 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, hipStream_t s
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  int ntiles = 0, ksteps = 0;
+  if (pack) {
+    // every input of every valid row is written; rows beyond the query rows only feed their own
+    // (discarded) outputs.  An odd number of k-steps would need a zeroed extra step.
+    gemm_bf16_pack_shape(sb.B * sb.K, Hq * hd, &ntiles, &ksteps);
+    if (ksteps * 32 != Hq * hd) return hipErrorInvalidValue;
+  }
   hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, work, Hq, Hq / Hkv, nsub,
-                     c->att_part, c->att_ml, nseg * nsub, hd, c->att_out);
+                     c->att_part, c->att_ml, nseg * nsub, hd, c->att_out, (uint4 *)pack, ntiles);
   return hipGetLastError();
 }
 
