@@ -12,8 +12,9 @@
 // but a real dense one, and the K/V stream (read once) is what bounds it.
 //
 // The product is formed transposed so that a lane owns one query column throughout:
-//   S^T[key][q] = sum_dim K[key][dim] Q[q][dim]      A = K rows (row-major buffer), B = Q
+//   S^T[key][q] = sum_dim K[key][dim] Q[q][dim]      A = K rows, B = Q
 //   O^T[dim][q] = sum_key V^T[dim][key] P^T[key][q]   A = V^T rows (V is stored transposed)
+// (both A operands are stored in the K/V buffers as the 1 KiB operand tiles themselves)
 // The MFMA result layout (lane l: column l%16, rows 4*(l/16)+r) of S^T is, after the
 // soft-max, directly the B operand of the second product if its 32-key contraction index
 // is taken as (lane group, e) <-> key 16*(e/4) + 4*(l/16) + e%4.  V^T is stored with the keys
