@@ -117,11 +117,27 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   return ((uint64_t)mh << 32) | ml;
 }
 
-// Packed activations of the multi-row projection: [k-step][row tile][hi, lo][64 lanes][8 bf16];
-// lane l of a tile holds inputs 8*(l/16)..+7 of row l%16 (the B operand of
-// v_mfma_f32_16x16x32_bf16), x ~= hi + lo.  Eight consecutive inputs c..c+7 (c % 8 == 0) of row r
-// are one lane's 16 bytes of a hi tile and of the lo tile 64 entries further.
-__device__ __forceinline__ void pack_store8(uint4 *pack, int ntiles, int r, int c, const float *x) {
+// Packed activations of the multi-row projection, two formats:
+//   terms = 2: [k-step][row tile][hi, lo][64 lanes][8 bf16], x ~= hi + lo (to 2^-17);
+//   terms = 1: [k-step][row tile][64 lanes][8 fp16], saturated at the fp16 maximum.
+// Lane l of a tile holds inputs 8*(l/16)..+7 of row l%16 (the B operand of the 16x16x32 MFMA).
+// Eight consecutive inputs c..c+7 (c % 8 == 0) of row r are one lane's 16 bytes of a tile.
+__device__ __forceinline__ uint16_t f32_to_f16_sat_bits(float x) {
+  const f16_t h = (f16_t)fminf(fmaxf(x, -65504.f), 65504.f);
+  return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ void pack_store8(uint4 *pack, int ntiles, int terms, int r, int c,
+                                            const float *x) {
+  uint4 *dst = pack + ((size_t)(c >> 5) * ntiles + (r >> 4)) * (64 * terms) +
+               (((c & 31) >> 3) * 16 + (r & 15));
+  if (terms == 1) {
+    uint32_t h[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      h[e] = (uint32_t)f32_to_f16_sat_bits(x[2 * e]) | ((uint32_t)f32_to_f16_sat_bits(x[2 * e + 1]) << 16);
+    dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
+    return;
+  }
   uint32_t h[4], l[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -131,14 +147,14 @@ __device__ __forceinline__ void pack_store8(uint4 *pack, int ntiles, int r, int 
     h[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
     l[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
   }
-  uint4 *dst = pack + ((size_t)(c >> 5) * ntiles + (r >> 4)) * 128 + (((c & 31) >> 3) * 16 + (r & 15));
   dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
   dst[64] = make_uint4(l[0], l[1], l[2], l[3]);
 }
-__device__ __forceinline__ void pack_zero8(uint4 *pack, int ntiles, int r, int c) {
-  uint4 *dst = pack + ((size_t)(c >> 5) * ntiles + (r >> 4)) * 128 + (((c & 31) >> 3) * 16 + (r & 15));
+__device__ __forceinline__ void pack_zero8(uint4 *pack, int ntiles, int terms, int r, int c) {
+  uint4 *dst = pack + ((size_t)(c >> 5) * ntiles + (r >> 4)) * (64 * terms) +
+               (((c & 31) >> 3) * 16 + (r & 15));
   dst[0] = make_uint4(0, 0, 0, 0);
-  dst[64] = make_uint4(0, 0, 0, 0);
+  if (terms == 2) dst[64] = make_uint4(0, 0, 0, 0);
 }
 
 // Block-wide sum / max for blocks of up to 1024 threads; `red` is >= 16 floats of LDS.

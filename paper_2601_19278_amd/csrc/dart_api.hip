@@ -152,6 +152,22 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     HIP_TRY(upload(w->w_emb_norm, d * es, &c->g_emb));
   }
 
+  // The batched entry points run every projection on the multi-row kernel, whose matrix pipe
+  // would be the co-bound at 128 rows with two-term (hi + lo) bf16 activations.  Their
+  // contexts keep an fp16 copy of each matrix (bf16 -> fp16 is exact for 2^-14 <= |w| < 65520)
+  // and feed fp16 activations: one product per tile instead of two, and an input rounding of
+  // 2^-12 relative, an order of magnitude inside the logit tolerance.
+  if (g.dtype == DART_BF16 && g.max_batch > 1) {
+    DeviceMatrix *ms[] = {&c->wqkv, &c->wo, &c->wgu, &c->wdown, &c->wlm, &c->wfc};
+    for (DeviceMatrix *m : ms) {
+      if (!m->data) continue;
+      const size_t elems = (size_t)m->N * m->Kd;
+      HIP_TRY(hipMalloc(&m->data16, elems * 2));
+      HIP_TRY(launch_tiles_to_f16(m->data, m->data16, elems, nullptr));
+    }
+    HIP_TRY(hipDeviceSynchronize());
+  }
+
   // rotary tables: angle = position * base^(-2i/hd), evaluated in double
   const int half = hd / 2;
   std::vector<float> cs((size_t)c->t_cap * half), sn((size_t)c->t_cap * half);
@@ -307,7 +323,7 @@ hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid,
   const dart_config &g = c->cfg;
   if (!g.front_end)
     return launch_rmsnorm_gather(g.dtype, sb, c->mask_emb, c->g_in, g.d, g.rms_eps, xn, resid,
-                                 gemm ? c->xpack : nullptr, st);
+                                 gemm ? c->xpack : nullptr, gemm_bf16_terms(c->wqkv), st);
   const int M = sb.row_off[sb.B];
   HIP_TRY(launch_feature_rows(g.dtype, sb, g.feat_dim, c->feat32, st));
   const size_t cs = (size_t)c->fc_rows * g.d;
@@ -393,14 +409,15 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   HIP_TRY(launch_qkv_post(c, sb, c->qkv, chunks, cs, c->qkv_dim, 0, st));
   // (an odd number of 32-input steps would need a zeroed extra step in the packed operand)
   const bool pack_att = gemm && (c->q_dim / 32) % 2 == 0;
-  HIP_TRY(launch_attention(c, sb, pack_att ? c->xpack : nullptr, st));
+  HIP_TRY(launch_attention(c, sb, pack_att ? c->xpack : nullptr, gemm_bf16_terms(c->wo), st));
 
   cs = W * g.d;
   HIP_TRY(project(c, c->wo, 0, g.d, pack_att ? nullptr : c->att_out, QR, c->proj, g.d, cs, c->split_o,
                   gemm ? c->gch_o : 0, &chunks, st));
   // on the multi-row path the norm kernels write the next projection's operand tiles themselves
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, QR, g.d,
-                            g.rms_eps, c->y, c->yn, gemm ? c->xpack : nullptr, st));
+                            g.rms_eps, c->y, c->yn, gemm ? c->xpack : nullptr,
+                            gemm_bf16_terms(c->wgu), st));
   const float *yn_in = gemm ? nullptr : c->yn;
   cs = W * 2 * g.ffn;
   if (gemm && c->gch_gu == 1) {     // SwiGLU in the projection's epilogue
@@ -415,7 +432,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down,
                   gemm ? c->gch_down : 0, &chunks, st));
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
-                            c->u, c->yn, gemm ? c->xpack : nullptr, st));
+                            c->u, c->yn, gemm ? c->xpack : nullptr, gemm_bf16_terms(c->wlm), st));
   HIP_TRY(project(c, c->wlm, 0, g.vocab, yn_in, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
   return hipSuccess;
 }
@@ -504,7 +521,9 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
 
 void dart_destroy(dart_ctx *c) {
   if (!c) return;
-  void *bufs[] = {c->wqkv.data, c->wo.data, c->wgu.data, c->wdown.data, c->wlm.data, c->g_in,
+  void *bufs[] = {c->wqkv.data16, c->wo.data16, c->wgu.data16, c->wdown.data16, c->wlm.data16,
+                  c->wfc.data16,
+                  c->wqkv.data, c->wo.data, c->wgu.data, c->wdown.data, c->wlm.data, c->g_in,
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms, c->topk_count,

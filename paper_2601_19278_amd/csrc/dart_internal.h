@@ -14,6 +14,7 @@
 // tile lane l owns the 8 consecutive inputs 8*(l/16).. of output row l%16.
 struct DeviceMatrix {
   void *data = nullptr;
+  void *data16 = nullptr;   // bf16 matrices used by the multi-row path: fp16 copy of the tiles
   int N = 0;        // output features (padded to a multiple of 16 for bf16)
   int Kd = 0;       // input features
   int n_real = 0;   // unpadded output features
@@ -180,7 +181,7 @@ extern int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_
 // (launch_gemm_bf16 with X = null consumes them) instead of xn.
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
                                  const void *gain, int d, float eps, float *xn, float *resid,
-                                 void *pack, hipStream_t st);
+                                 void *pack, int terms, hipStream_t st);
 
 // Front end, step 1: the feature rows of a pass as fp32 (mask rows: zeros).
 hipError_t launch_feature_rows(int dtype, const SeqBatch &sb, int feat_dim, float *out, hipStream_t st);
@@ -196,7 +197,7 @@ hipError_t launch_front_norm(int dtype, const SeqBatch &sb, const float *fc_part
 // of `rows` rows (launch_gemm_bf16 with X = null consumes them).
 hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
-                             float eps, float *y, float *yn, void *pack, hipStream_t st);
+                             float eps, float *y, float *yn, void *pack, int terms, hipStream_t st);
 
 hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const float *X, int M,
                            float *out, int out_stride, hipStream_t st);
@@ -219,6 +220,8 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
                             int epi, hipStream_t st);
 int gemm_bf16_chunks(int Kd, int nstrips);
 size_t gemm_bf16_pack_bytes(int M, int Kd);
+int gemm_bf16_terms(const DeviceMatrix &W);   // format of the packed activations W's launches expect
+hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipStream_t st);
 
 // First k-step of k-chunk c when KT k-steps are cut into nchunks (multiples of 4 k-steps).
 __host__ __device__ inline int gemm_chunk_begin(int KT, int nchunks, int c) {
@@ -233,7 +236,7 @@ hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *q
                            size_t chunk_stride, int row_stride, int col0, hipStream_t st);
 
 // Attention of the B*K query rows of the pass (compact order) over their sequences' K/V.
-hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, hipStream_t st);
+hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, int terms, hipStream_t st);
 
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st);

@@ -70,7 +70,8 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork w
                                                          const float *__restrict__ ml_part,
                                                          int nsplit, int hd,
                                                          float *__restrict__ out,
-                                                         uint4 *__restrict__ pack, int ntiles) {
+                                                         uint4 *__restrict__ pack, int ntiles,
+                                                         int terms) {
   __shared__ float red[16];
   __shared__ float w[ATTN_MAX_SPLITS];
   __shared__ __align__(16) float row_out[128];
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork w
   __syncthreads();
   if (t < hd / 8) {
     const int row = qv / Hq, h = qv % Hq;
-    pack_store8(pack, ntiles, row, h * hd + 8 * t, &row_out[8 * t]);
+    pack_store8(pack, ntiles, terms, row, h * hd + 8 * t, &row_out[8 * t]);
   }
 }
 
@@ -129,7 +130,8 @@ void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps);
 
 // pack: where the multi-row O projection expects its operand tiles (bf16 only), else null and
 // the result goes to c->att_out.
-hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, hipStream_t st) {
+hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, int terms,
+                            hipStream_t st) {
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
   const int chunk = ATTN_KEY_CHUNK;                      // keys per chunk
@@ -181,7 +183,7 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, h
     if (ksteps * 32 != Hq * hd) return hipErrorInvalidValue;
   }
   hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, work, Hq, Hq / Hkv, nsub,
-                     c->att_part, c->att_ml, nseg * nsub, hd, c->att_out, (uint4 *)pack, ntiles);
+                     c->att_part, c->att_ml, nseg * nsub, hd, c->att_out, (uint4 *)pack, ntiles, terms);
   return hipGetLastError();
 }
 

@@ -36,10 +36,11 @@ constexpr int GEMM_KS = 2;          // k-steps (of 32 inputs) per LDS stage = pe
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-// One LDS stage: the hi and lo operand tiles of NCT row tiles for GEMM_KS k-steps.
-template <int NCT>
+// One LDS stage: the operand tiles (TERMS per row tile: hi and lo, or one fp16 tile) of NCT row
+// tiles for GEMM_KS k-steps.
+template <int NCT, int TERMS>
 struct GemmStage {
-  u32x4_t t[GEMM_KS][NCT * 2][64];
+  u32x4_t t[GEMM_KS][NCT * TERMS][64];
 };
 
 // The main loop keeps three kinds of memory traffic in flight at once: weight tiles for the
@@ -77,11 +78,10 @@ __device__ __forceinline__ void wait_tiles(u32x4_t (&t)[SP]) {
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(t[0]) : "n"(N));
 }
 
-// Packed activations: [k-step][row tile][hi, lo][64 lanes][8 bf16]; lane l of a tile holds
-// inputs 8*(l/16)..+7 of row l%16 (the B operand of v_mfma_f32_16x16x32_bf16).  Row tiles
+// Packed activations (pack_store8): [k-step][row tile][terms][64 lanes][8 x 16 bit].  Row tiles
 // beyond M and, when KT is odd, one extra k-step are zero, so the consumer needs no guards.
 __global__ __launch_bounds__(256) void pack_rows_kernel(const float *__restrict__ X, int M, int Kd,
-                                                        int ntiles, int ksteps,
+                                                        int ntiles, int ksteps, int terms,
                                                         u32x4_t *__restrict__ Xp) {
   const int item = blockIdx.x * 256 + threadIdx.x;       // (k-step, row tile, lane)
   const int lane = item & 63, tile = (item >> 6) % ntiles, t = (item >> 6) / ntiles;
@@ -93,9 +93,9 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const float *__restrict_
     const float4 a = *reinterpret_cast<const float4 *>(src);
     const float4 b = *reinterpret_cast<const float4 *>(src + 4);
     const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    pack_store8(pk, ntiles, r, k, x);
+    pack_store8(pk, ntiles, terms, r, k, x);
   } else {
-    pack_zero8(pk, ntiles, r, k);
+    pack_zero8(pk, ntiles, terms, r, k);
   }
 }
 
@@ -110,10 +110,12 @@ struct GemmArgs {
 
 // EPI 0: store the accumulators.  EPI 1: the strips hold interleaved gate/up features
 // (g f, g f+1, u f, u f+1), one group per lane; store silu(g) * u (needs nchunks == 1).
-template <int NCT, int SP, int EPI>
-__device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0,
-                                          GemmStage<NCT> *st1, int rb, int chunk, int k0, int nk,
-                                          int sfirst, int ns, int wave) {
+// TERMS 2: bf16 weights, activations as bf16 hi + lo (two products per tile pair).
+// TERMS 1: fp16 weights and fp16 activations (one product).
+template <int NCT, int SP, int EPI, int TERMS>
+__device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERMS> *st0,
+                                          GemmStage<NCT, TERMS> *st1, int rb, int chunk, int k0,
+                                          int nk, int sfirst, int ns, int wave) {
   const int lane = threadIdx.x & 63;
   const int kend = k0 + nk;                               // k-steps [k0, kend) of this chunk
   const int nkp = (nk + GEMM_KS - 1) / GEMM_KS * GEMM_KS;  // an odd tail reads the zero k-step
@@ -130,18 +132,19 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0
   }
   auto tile_off = [&](int kstep) { return (uint32_t)(min(kstep, kend - 1) * 64 + lane) * 16u; };
 
-  // stage copy: the NCT*2 operand tiles of GEMM_KS k-steps, 1 KiB each; wavefront w moves
-  // tiles w, w+8, ...: exactly TPW copies per wavefront and stage
-  constexpr int NT = GEMM_KS * NCT * 2;
-  static_assert(NT % GEMM_WAVES == 0, "every wavefront must issue the same number of copies");
-  constexpr int TPW = NT / GEMM_WAVES;
-  const u32x4_t *xbase = a.Xp + (size_t)rb * NCT * 128;   // uniform
-  const uint32_t xstep = (uint32_t)a.ntiles * 2048u;      // bytes of one k-step
-  auto stage_copy = [&](int kstage, GemmStage<NCT> *dst) {   // kstage: first k-step, absolute
+  // stage copy: the NCT*TERMS operand tiles of GEMM_KS k-steps, 1 KiB each; wavefront w moves
+  // tiles w, w+8, ...: exactly TPW copies per wavefront and stage (with fewer tiles than
+  // wavefronts some tiles are copied twice, so that every wavefront counts the same)
+  constexpr int NT = GEMM_KS * NCT * TERMS;
+  static_assert(NT % GEMM_WAVES == 0 || GEMM_WAVES % NT == 0, "uniform copies per wavefront");
+  constexpr int TPW = NT >= GEMM_WAVES ? NT / GEMM_WAVES : 1;
+  const u32x4_t *xbase = a.Xp + (size_t)rb * NCT * 64 * TERMS;   // uniform
+  const uint32_t xstep = (uint32_t)a.ntiles * 1024u * TERMS;     // bytes of one k-step
+  auto stage_copy = [&](int kstage, GemmStage<NCT, TERMS> *dst) {   // kstage: first k-step, absolute
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-      const int tile = wave + GEMM_WAVES * i;
-      const int u = tile / (NCT * 2), c2 = tile % (NCT * 2);
+      const int tile = (wave + GEMM_WAVES * i) % NT;
+      const int u = tile / (NCT * TERMS), c2 = tile % (NCT * TERMS);
       copy_tile_to_lds_async((uint32_t)(uintptr_t)(lptr_t)&dst->t[u][c2][0],
                              (uint32_t)(kstage + u) * xstep + (uint32_t)(c2 * 64 + lane) * 16u, xbase);
     }
@@ -176,7 +179,7 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0
 
   // One stage: GEMM_KS k-steps out of `cur` while the next stage is copied into `nxt`; J is the
   // position of the stage's first k-step in the unrolled body (ring slots are static).
-  auto stage_body = [&](int t0, auto jtag, GemmStage<NCT> *cur, GemmStage<NCT> *nxt) {
+  auto stage_body = [&](int t0, auto jtag, GemmStage<NCT, TERMS> *cur, GemmStage<NCT, TERMS> *nxt) {
     constexpr int J = decltype(jtag)::value;
     // next stage (clamped at the end: copied again, never used)
     stage_copy(min(k0 + t0 + GEMM_KS, k0 + nkp - GEMM_KS), nxt);
@@ -192,18 +195,23 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0
 #pragma unroll
       for (int cb = 0; cb < NCT; cb += NB) {
 #pragma unroll
-        for (int hl = 0; hl < 2; ++hl) {
-          bf16x8_t b[NB];
+        for (int hl = 0; hl < TERMS; ++hl) {
+          u32x4_t b[NB];
 #pragma unroll
-          for (int c = 0; c < NB; ++c)
-            b[c] = __builtin_bit_cast(bf16x8_t, cur->t[u][2 * (cb + c) + hl][lane]);
+          for (int c = 0; c < NB; ++c) b[c] = cur->t[u][TERMS * (cb + c) + hl][lane];
 #pragma unroll
           for (int s = 0; s < SP; ++s) {
-            const bf16x8_t av = __builtin_bit_cast(bf16x8_t, aop[slot][s]);
 #pragma unroll
-            for (int c = 0; c < NB; ++c)
-              acc[s][cb + c] =
-                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[c], acc[s][cb + c], 0, 0, 0);
+            for (int c = 0; c < NB; ++c) {
+              if constexpr (TERMS == 2)
+                acc[s][cb + c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(bf16x8_t, aop[slot][s]), __builtin_bit_cast(bf16x8_t, b[c]),
+                    acc[s][cb + c], 0, 0, 0);
+              else
+                acc[s][cb + c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                    __builtin_bit_cast(f16x8_t, aop[slot][s]), __builtin_bit_cast(f16x8_t, b[c]),
+                    acc[s][cb + c], 0, 0, 0);
+            }
           }
         }
       }
@@ -267,9 +275,9 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT> *st0
   }
 }
 
-template <int NCT, int EPI>
+template <int NCT, int EPI, int TERMS>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
-  __shared__ GemmStage<NCT> stage0, stage1;
+  __shared__ GemmStage<NCT, TERMS> stage0, stage1;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int gc_count = a.ngroups * a.nchunks;
   for (int unit = blockIdx.x; unit < a.units; unit += gridDim.x) {
@@ -291,11 +299,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int per = (P + GEMM_WAVES - 1) / GEMM_WAVES;          // strips per wavefront
       const int sfirst = min(base + wave * per, g1 - 1);
       const int ns = max(0, min(per, P - wave * per));
-      if (per > 2) gemm_pass<NCT, 4, EPI>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
-      else if (per == 2) gemm_pass<NCT, 2, EPI>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
-      else gemm_pass<NCT, 1, EPI>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
+      if (per > 2) gemm_pass<NCT, 4, EPI, TERMS>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
+      else if (per == 2) gemm_pass<NCT, 2, EPI, TERMS>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
+      else gemm_pass<NCT, 1, EPI, TERMS>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
     }
   }
+}
+
+// fp16 copy of a matrix of packed bf16 tiles (same tile layout: both are 16-bit operands of a
+// 16x16x32 MFMA).  bf16 -> fp16 is exact for 2^-14 <= |w| < 65520; smaller weights round to
+// fp16 subnormals (absolute error <= 2^-25), larger ones saturate.
+__global__ __launch_bounds__(256) void tiles_to_f16_kernel(const uint32_t *__restrict__ src,
+                                                           uint32_t *__restrict__ dst, size_t n_pairs) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_pairs; i += (size_t)gridDim.x * 256) {
+    const uint32_t v = src[i];
+    const float lo = bf16_to_f32((bf16_t)(v & 0xFFFF)), hi = bf16_to_f32((bf16_t)(v >> 16));
+    dst[i] = (uint32_t)f32_to_f16_sat_bits(lo) | ((uint32_t)f32_to_f16_sat_bits(hi) << 16);
+  }
+}
+hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipStream_t st) {
+  hipLaunchKernelGGL(tiles_to_f16_kernel, dim3(2048), dim3(256), 0, st, (const uint32_t *)src,
+                     (uint32_t *)dst, n_elems / 2);
+  return hipGetLastError();
 }
 
 int g_gemm_wgs = 256;      // resident workgroups: one per compute unit
@@ -320,18 +345,23 @@ void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps) {
   *ntiles = (M + 16 * nct - 1) / (16 * nct) * nct;
   *ksteps = (Kd / 32 + 1) / 2 * 2;
 }
-size_t gemm_bf16_pack_bytes(int M, int Kd) {
+size_t gemm_bf16_pack_bytes(int M, int Kd) {      // of the larger (two-term) format
   const int nct = gemm_nct(M), ntiles = (M + 16 * nct - 1) / (16 * nct) * nct;
   const int ksteps = (Kd / 32 + 1) / 2 * 2;
   return (size_t)ksteps * ntiles * 2048;
 }
 
+// The matrix's fp16 copy, when it has one, selects the one-term arithmetic (fp16 activations);
+// the packed activations must be in the matching format (gemm_bf16_terms).
+int gemm_bf16_terms(const DeviceMatrix &W) { return W.data16 ? 1 : 2; }
+
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
                             int epi, hipStream_t st) {
   if (M < 1 || nstrips < 1 || nchunks < 1 || (epi == 1 && nchunks != 1)) return hipErrorInvalidValue;
+  const int terms = gemm_bf16_terms(W);
   GemmArgs a;
-  a.Wp = (const u32x4_t *)W.data;
+  a.Wp = (const u32x4_t *)(terms == 1 ? W.data16 : W.data);
   a.Xp = (const u32x4_t *)pack;
   a.out = out;
   a.chunk_stride = chunk_stride;
@@ -349,7 +379,7 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   if (X) {                                               // X == nullptr: pack already holds them
     const int64_t items = (int64_t)ksteps * a.ntiles * 64;
     hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X,
-                       M, W.Kd, a.ntiles, ksteps, (u32x4_t *)pack);
+                       M, W.Kd, a.ntiles, ksteps, terms, (u32x4_t *)pack);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -359,10 +389,15 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   const int gc = a.ngroups * nchunks;
   a.units = (gc + 7) / 8 * 8 * a.row_blocks;
   const dim3 grid(a.units), block(GEMM_THREADS);
-#define DART_GEMM_GO(NCT_)                                                                   \
-  do {                                                                                       \
-    if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1>), grid, block, 0, st, a);    \
-    else hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 0>), grid, block, 0, st, a);             \
+#define DART_GEMM_GO(NCT_)                                                                        \
+  do {                                                                                            \
+    if (terms == 1) {                                                                             \
+      if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1, 1>), grid, block, 0, st, a);    \
+      else hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 0, 1>), grid, block, 0, st, a);             \
+    } else {                                                                                      \
+      if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1, 2>), grid, block, 0, st, a);    \
+      else hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 0, 2>), grid, block, 0, st, a);             \
+    }                                                                                             \
   } while (0)
   if (nct == 2) DART_GEMM_GO(2);
   else if (nct == 4) DART_GEMM_GO(4);

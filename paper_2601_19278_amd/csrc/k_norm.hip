@@ -38,15 +38,15 @@ template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
     SeqBatch sb, const T *__restrict__ mask_emb, const T *__restrict__ gain, int d, float eps,
     float *__restrict__ xn, float *__restrict__ resid, uint4 *__restrict__ pack, int ntiles,
-    int ksteps) {
+    int ksteps, int terms) {
   __shared__ float red[16];
   const int i = blockIdx.x;
   if (i >= sb.row_off[sb.B]) {              // padding rows of the packed operand (uniform)
-    for (int c = threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, i, c);
+    for (int c = threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, terms, i, c);
     return;
   }
   if (pack)
-    for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, i, c);
+    for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, terms, i, c);
   int b, pos, qi;
   seq_of_row(sb, i, b, pos, qi);
   const int n = sb.n[b];
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
       if (pack)
-        pack_store8(pack, ntiles, i, c, v[j]);
+        pack_store8(pack, ntiles, terms, i, c, v[j]);
       else
         store8(xn + (size_t)i * d + c, v[j]);
     }
@@ -178,15 +178,15 @@ template <typename T>
 __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
     const float *__restrict__ resid, const float *__restrict__ part, int chunks, size_t chunk_stride,
     int row_stride, const T *__restrict__ gain, int rows, int d, float eps, float *__restrict__ y,
-    float *__restrict__ yn, uint4 *__restrict__ pack, int ntiles, int ksteps) {
+    float *__restrict__ yn, uint4 *__restrict__ pack, int ntiles, int ksteps, int terms) {
   __shared__ float red[16];
   const int r = blockIdx.x;
   if (r >= rows) {                          // padding rows of the packed operand (uniform)
-    for (int c = threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, r, c);
+    for (int c = threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, terms, r, c);
     return;
   }
   if (pack)
-    for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, r, c);
+    for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, terms, r, c);
   float v[ROW_MAXIT][8], g[ROW_MAXIT][8];
 #pragma unroll
   for (int j = 0; j < ROW_MAXIT; ++j) {
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
       store8(yn + (size_t)r * d + c, v[j]);
-      if (pack) pack_store8(pack, ntiles, r, c, v[j]);
+      if (pack) pack_store8(pack, ntiles, terms, r, c, v[j]);
     }
   }
 }
@@ -268,7 +268,7 @@ void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps);
 
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
                                  const void *gain, int d, float eps, float *xn, float *resid,
-                                 void *pack, hipStream_t st) {
+                                 void *pack, int terms, hipStream_t st) {
   const int M = sb.row_off[sb.B];
   int ntiles = 0, ksteps = 0, grid = M;
   if (pack) {
@@ -279,11 +279,11 @@ hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask
   if (dtype == DART_BF16)
     hipLaunchKernelGGL(rmsnorm_gather_kernel<bf16_t>, dim3(grid), dim3(ROW_THREADS), 0, st, sb,
                        (const bf16_t *)mask_emb, (const bf16_t *)gain, d, eps, xn, resid,
-                       (uint4 *)pack, ntiles, ksteps);
+                       (uint4 *)pack, ntiles, ksteps, terms);
   else
     hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(grid), dim3(ROW_THREADS), 0, st, sb,
                        (const float *)mask_emb, (const float *)gain, d, eps, xn, resid,
-                       (uint4 *)nullptr, 0, 0);
+                       (uint4 *)nullptr, 0, 0, 2);
   return hipGetLastError();
 }
 
@@ -314,7 +314,7 @@ hipError_t launch_front_norm(int dtype, const SeqBatch &sb, const float *fc_part
 
 hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, int chunks,
                              size_t chunk_stride, int row_stride, const void *gain, int rows, int d,
-                             float eps, float *y, float *yn, void *pack, hipStream_t st) {
+                             float eps, float *y, float *yn, void *pack, int terms, hipStream_t st) {
   int ntiles = 0, ksteps = 0, grid = rows;
   if (pack) {
     if (dtype != DART_BF16 || (d & 7)) return hipErrorInvalidValue;
@@ -324,11 +324,11 @@ hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, i
   if (dtype == DART_BF16)
     hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(grid), dim3(ROW_THREADS), 0, st, resid, part,
                        chunks, chunk_stride, row_stride, (const bf16_t *)gain, rows, d, eps, y, yn,
-                       (uint4 *)pack, ntiles, ksteps);
+                       (uint4 *)pack, ntiles, ksteps, terms);
   else
     hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(grid), dim3(ROW_THREADS), 0, st, resid, part,
                        chunks, chunk_stride, row_stride, (const float *)gain, rows, d, eps, y, yn,
-                       (uint4 *)nullptr, 0, 0);
+                       (uint4 *)nullptr, 0, 0, 2);
   return hipGetLastError();
 }
 
