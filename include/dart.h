@@ -65,7 +65,8 @@ typedef struct {
   int32_t d, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
   int32_t max_ctx;     /* longest prefix n */
   int32_t max_K;       /* <= DART_MAX_K; mask_emb has max_K-1 rows */
-  int32_t max_batch;   /* number of independent sequences (K/V buffer slots) */
+  int32_t max_batch;   /* number of independent sequences (K/V buffer slots); > 1 also keeps an
+                          fp16 copy of the bf16 matrices for the batched calls */
   int32_t dtype;       /* DART_F32 | DART_BF16 */
   int32_t qk_norm;     /* 0/1 */
   float rms_eps;
@@ -149,7 +150,13 @@ dart_status dart_draft_forward_features(dart_ctx *ctx, int seq, const void *feat
 /* Same for `batch` sequences in slots 0..batch-1 (ragged lengths).
  *   hidden      HOST array of `batch` device pointers, each [ctx_len[b]][d]
  *   ctx_len, n_cached   HOST arrays [batch]
- *   logits_out  device [batch][K][vocab] fp32 */
+ *   logits_out  device [batch][K][vocab] fp32
+ * All rows of all sequences share every launch.  On bf16 weights the projections of this call
+ * multiply an fp16 copy of the weights (made by dart_create when max_batch > 1) by fp16
+ * activations, where the single-sequence call feeds two-term bf16 activations: the two calls
+ * agree to rounding (both within the logit tolerance of the fp64 definition), not bit for
+ * bit, and a K/V slot filled by one is reused by the other to rounding only.  Each call
+ * reproduces its own cold result in a warm call bit for bit. */
 dart_status dart_draft_forward_batched(dart_ctx *ctx, int batch, const void *const *hidden,
                                        const int32_t *ctx_len, const int32_t *n_cached, int K,
                                        float *logits_out, void *stream);
