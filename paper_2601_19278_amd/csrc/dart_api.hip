@@ -251,6 +251,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     if (g.front_end)
       pb = std::max(pb, gemm_bf16_pack_bytes(std::max(c->ws_rows, c->kv_rows), g.feat_dim));
     HIP_TRY(hipMalloc(&c->xpack, pb));
+    if (g.max_batch > 1) HIP_TRY(hipMalloc(&c->xpack2, gemm_bf16_pack_bytes(c->ws_rows, F)));
   }
   HIP_TRY(dev_alloc(&c->xn_kv, (size_t)c->kv_rows * in_dim));
   if (g.front_end) {
@@ -420,17 +421,28 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
                             gemm_bf16_terms(c->wgu), st));
   const float *yn_in = gemm ? nullptr : c->yn;
   cs = W * 2 * g.ffn;
-  if (gemm && c->gch_gu == 1) {     // SwiGLU in the projection's epilogue
-    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, yn_in, QR, c->xpack, c->hmid, g.ffn, 0, 1, 1,
-                             st));
+  // SwiGLU in the gate/up projection's epilogue when its k range is not cut; with fp16 operands
+  // the epilogue writes the down projection's operand tiles itself (no fp32 round trip, no
+  // conversion pass; an odd number of 32-input steps would need a zeroed extra step)
+  const bool fuse_act = gemm && c->gch_gu == 1;
+  const bool fuse_pack = fuse_act && c->xpack2 && gemm_bf16_terms(c->wdown) == 1 && (g.ffn / 32) % 2 == 0;
+  if (fuse_act) {
+    HIP_TRY(launch_gemm_bf16(c->wgu, 0, 2 * g.ffn / 16, yn_in, QR, c->xpack, c->hmid, g.ffn, 0, 1,
+                             fuse_pack ? 2 : 1, st, c->xpack2));
   } else {
     HIP_TRY(project(c, c->wgu, 0, 2 * g.ffn, yn_in, QR, c->proj, 2 * g.ffn, cs, c->split_gu,
                     gemm ? c->gch_gu : 0, &chunks, st));
     HIP_TRY(launch_swiglu(c->proj, chunks, cs, QR, g.ffn, g.dtype == DART_BF16, c->hmid, st));
   }
   cs = W * g.d;
-  HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down,
-                  gemm ? c->gch_down : 0, &chunks, st));
+  if (fuse_pack) {
+    chunks = c->gch_down;
+    HIP_TRY(launch_gemm_bf16(c->wdown, 0, (g.d + 15) / 16, nullptr, QR, c->xpack2, c->proj, g.d, cs,
+                             chunks, 0, st));
+  } else {
+    HIP_TRY(project(c, c->wdown, 0, g.d, c->hmid, QR, c->proj, g.d, cs, c->split_down,
+                    gemm ? c->gch_down : 0, &chunks, st));
+  }
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
                             c->u, c->yn, gemm ? c->xpack : nullptr, gemm_bf16_terms(c->wlm), st));
   HIP_TRY(project(c, c->wlm, 0, g.vocab, yn_in, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
@@ -527,7 +539,7 @@ void dart_destroy(dart_ctx *c) {
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms, c->topk_count,
-                  c->xn_kv, c->kv_part, c->xpack, c->wfc.data, c->embed, c->g_emb, c->feat32,
+                  c->xn_kv, c->kv_part, c->xpack, c->xpack2, c->wfc.data, c->embed, c->g_emb, c->feat32,
                   c->fc_part};
   for (void *p : bufs)
     if (p) (void)hipFree(p);

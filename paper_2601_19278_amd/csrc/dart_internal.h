@@ -151,6 +151,7 @@ struct dart_ctx {
   int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // k-chunks per matrix (skinny kernel)
   int gch_qkv = 1, gch_o = 1, gch_gu = 1, gch_down = 1;           // k-chunks on the multi-row path
   void *xpack = nullptr;          // activations of one multi-row projection in MFMA operand order
+  void *xpack2 = nullptr;         // ... of the down projection, written by the gate/up epilogue
   int max_rows;                   // max_batch * max_K
   int max_splits;                 // key splits the attention workspaces hold per query vector
   // top-k workspace
@@ -217,7 +218,8 @@ int gemv_bf16_row_tiles(int Kd, int nch);     // 16-row tiles one launch may car
 // (X == nullptr: pack already holds the operand tiles of these M rows; no conversion pass).
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
-                            int epi, hipStream_t st);
+                            int epi, hipStream_t st,
+                            void *out_pack = nullptr);
 int gemm_bf16_chunks(int Kd, int nstrips);
 size_t gemm_bf16_pack_bytes(int M, int Kd);
 int gemm_bf16_terms(const DeviceMatrix &W);   // format of the packed activations W's launches expect

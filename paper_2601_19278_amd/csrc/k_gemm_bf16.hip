@@ -103,6 +103,8 @@ struct GemmArgs {
   const u32x4_t *Wp;     // packed weight tiles
   const u32x4_t *Xp;     // packed activations, ntiles row tiles per k-step
   float *out;            // [nchunks][M][out_stride] (EPI 1: [M][out_stride] SwiGLU products)
+  uint16_t *out_pack;    // EPI 2: SwiGLU products as one-term operand tiles of the next projection
+  int out_ntiles;        //        (row tiles of that operand)
   size_t chunk_stride;
   int M, KT, nchunks, strip0, nstrips, n_cols, ngroups, out_stride;
   int row_blocks, units, ntiles;
@@ -110,6 +112,8 @@ struct GemmArgs {
 
 // EPI 0: store the accumulators.  EPI 1: the strips hold interleaved gate/up features
 // (g f, g f+1, u f, u f+1), one group per lane; store silu(g) * u (needs nchunks == 1).
+// EPI 2: the same products, written as fp16 straight into the packed operand tiles that the
+// down projection reads (a lane's two features are 4 contiguous bytes of a tile).
 // TERMS 2: bf16 weights, activations as bf16 hi + lo (two products per tile pair).
 // TERMS 1: fp16 weights and fp16 activations (one product).
 template <int NCT, int SP, int EPI, int TERMS>
@@ -252,12 +256,21 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
         const int m = m0 + 16 * c + j;
         if (m < a.M) {
           const f32x4_t v = acc[s][c];
-          if constexpr (EPI == 1) {
+          if constexpr (EPI != 0) {
             if (col < a.n_cols) {
               const float h0 = v[0] / (1.0f + expf(-v[0])) * v[2];
               const float h1 = v[1] / (1.0f + expf(-v[1])) * v[3];
-              *reinterpret_cast<float2 *>(a.out + (size_t)m * a.out_stride + (col >> 1)) =
-                  make_float2(h0, h1);
+              const int f = col >> 1;                    // first of the lane's two features
+              if constexpr (EPI == 1) {
+                *reinterpret_cast<float2 *>(a.out + (size_t)m * a.out_stride + f) = make_float2(h0, h1);
+              } else {
+                // element (row m, input f) of the one-term layout (pack_store8)
+                uint16_t *dst = a.out_pack +
+                                (((size_t)(f >> 5) * a.out_ntiles + (m >> 4)) * 64 +
+                                 (((f & 31) >> 3) * 16 + (m & 15))) * 8 + (f & 7);
+                *reinterpret_cast<uint32_t *>(dst) =
+                    (uint32_t)f32_to_f16_sat_bits(h0) | ((uint32_t)f32_to_f16_sat_bits(h1) << 16);
+              }
             }
           } else {
             float *dst = a.out + chunk * a.chunk_stride + (size_t)m * a.out_stride + col;
@@ -357,9 +370,10 @@ int gemm_bf16_terms(const DeviceMatrix &W) { return W.data16 ? 1 : 2; }
 
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
-                            int epi, hipStream_t st) {
-  if (M < 1 || nstrips < 1 || nchunks < 1 || (epi == 1 && nchunks != 1)) return hipErrorInvalidValue;
+                            int epi, hipStream_t st, void *out_pack) {
+  if (M < 1 || nstrips < 1 || nchunks < 1 || (epi != 0 && nchunks != 1)) return hipErrorInvalidValue;
   const int terms = gemm_bf16_terms(W);
+  if (epi == 2 && (!out_pack || terms != 1)) return hipErrorInvalidValue;
   GemmArgs a;
   a.Wp = (const u32x4_t *)(terms == 1 ? W.data16 : W.data);
   a.Xp = (const u32x4_t *)pack;
@@ -375,6 +389,8 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   const int nct = gemm_nct(M);
   a.row_blocks = (M + 16 * nct - 1) / (16 * nct);
   a.ntiles = a.row_blocks * nct;
+  a.out_pack = (uint16_t *)out_pack;
+  a.out_ntiles = a.ntiles;                // the next projection carries the same rows
   const int ksteps = (a.KT + 1) / 2 * 2;
   if (X) {                                               // X == nullptr: pack already holds them
     const int64_t items = (int64_t)ksteps * a.ntiles * 64;
@@ -392,7 +408,8 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
 #define DART_GEMM_GO(NCT_)                                                                        \
   do {                                                                                            \
     if (terms == 1) {                                                                             \
-      if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1, 1>), grid, block, 0, st, a);    \
+      if (epi == 2) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 2, 1>), grid, block, 0, st, a);    \
+      else if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1, 1>), grid, block, 0, st, a); \
       else hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 0, 1>), grid, block, 0, st, a);             \
     } else {                                                                                      \
       if (epi == 1) hipLaunchKernelGGL((gemm_bf16_kernel<NCT_, 1, 2>), grid, block, 0, st, a);    \
