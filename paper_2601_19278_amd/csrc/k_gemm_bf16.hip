@@ -345,7 +345,7 @@ int gemm_bf16_chunks(int Kd, int nstrips) {
   const int KT = Kd / 32;
   const int groups = (nstrips + 2 * GEMM_WAVES - 1) / (2 * GEMM_WAVES);
   if (groups >= g_gemm_wgs / 2) return 1;
-  int nch = (g_gemm_wgs + groups / 2) / groups;
+  int nch = g_gemm_wgs / groups;          // rounded down: one more unit than workgroups costs a second round
   nch = min(nch, max(1, KT / 16));
   return max(1, nch);
 }
