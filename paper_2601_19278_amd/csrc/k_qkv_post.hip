@@ -28,8 +28,17 @@ __global__ __launch_bounds__(128) void qkv_post_kernel(
   kbuf += (size_t)sb.slot[b] * slot_elems;
   vbuf += (size_t)sb.slot[b] * slot_elems;
   const int col = hh * hd + t - col0;             // q heads, then k heads, then v heads
+  // chunk partials: up to 8 loads in flight, added in index order
   float x = 0.f;
-  for (int c = 0; c < chunks; ++c) x += qkv[c * chunk_stride + (size_t)i * row_stride + col];
+  const float *src = qkv + (size_t)i * row_stride + col;
+  for (int c0 = 0; c0 < chunks; c0 += 8) {
+    float p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) p[u] = c0 + u < chunks ? src[(size_t)(c0 + u) * chunk_stride] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (c0 + u < chunks) x += p[u];
+  }
 
   if (!is_q && !is_k) {                           // value head: store as is
     const int g = hh - Hq - Hkv;
