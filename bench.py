@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
 # a plain 1 GiB copy (profiles/lm_head_C4_hbm_counters.txt, profiles/gemm_lm_head_C5_counters.txt);
 # re-measure after kernel changes.
-MEASURED_LM_HEAD_TRAFFIC = {"C4": 1589.4e6, "C5": 1685.6e6}
+MEASURED_LM_HEAD_TRAFFIC = {"C4": 1589.6e6, "C5": 1685.5e6}
 
 
 def algorithmic_bytes(cfg, n_new: int) -> dict:
