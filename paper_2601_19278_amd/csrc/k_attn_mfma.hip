@@ -49,9 +49,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
 // One wavefront copies 1 KiB to LDS: lane l moves the 16 bytes at base + off to
-// lds_base + 16*l.  lds_base is wave-uniform.  Completion is counted by vmcnt.
+// lds_base + 16*l.  lds_base is wave-uniform.  Completion is counted by vmcnt.  The K/V stream
+// is read once per call: non-temporal (measured 71 -> 67 us at 128 rows, neutral at 8).
 __device__ __forceinline__ void attn_copy_tile(uint32_t lds_base, uint32_t off, const void *base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
                :
                : "s"(lds_base), "v"(off), "s"(base)
                : "memory");
