@@ -496,10 +496,17 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         // A threshold T with at least `need` scores >= T, found bit by bit from the top (every
         // accepted bit keeps that property).  The search stops as soon as few more than `need`
         // scores are left above T: any such T selects a superset of the expansions that matter.
-        uint32_t T = 0;
+        // The bits that all scores of the level share (sign, exponent and often the first
+        // mantissa bits) are taken over at once: T starts as that common prefix, which is <= every
+        // score, and the search begins at the highest bit in which two scores differ.
+        const uint32_t top = wave_max_u32(max(max(sc[0], sc[1]), max(sc[2], sc[3])));
+        const uint32_t bot = ~wave_max_u32(~min(min(sc[0] ? sc[0] : ~0u, sc[1] ? sc[1] : ~0u),
+                                                min(sc[2] ? sc[2] : ~0u, sc[3] ? sc[3] : ~0u)));
+        const int first = 31 - __clz((int)(top ^ bot));           // -1: all scores are equal
+        uint32_t T = first < 0 ? top : top & ~((2u << first) - 1u);
         int above = n_new;
         const int enough = need <= 64 ? 64 : need + 8;   // up to 64 are ranked in one pass
-        for (int bit = 31; bit >= 0 && above > enough; --bit) {
+        for (int bit = first; bit >= 0 && above > enough; --bit) {
           const uint32_t trial = T | (1u << bit);
           const int cnt = __popcll(__ballot(sc[0] >= trial)) + __popcll(__ballot(sc[1] >= trial)) +
                           __popcll(__ballot(sc[2] >= trial)) + __popcll(__ballot(sc[3] >= trial));
