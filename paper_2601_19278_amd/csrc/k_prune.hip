@@ -452,6 +452,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           par = sh.lvl_par[lb][j0];
           const int b4 = (n_best + 3) >> 2;
           rank = j0 + (n_best ? count_above(reinterpret_cast<const uint4 *>(sh.best_sc[bcur]), b4, sc, b4) : 0);
+          if (sc == 0) rank = theta;                       // an entry the level did not keep
         }
         if (rank < theta) {
           sh.best_key[bnx][rank] = key;
@@ -469,7 +470,6 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
       const int n_new = nb * k;
       const int nb_next = min(beam_w, n_new);
       const int n_lvl = min(theta, n_new);
-      const int need = max(nb_next, n_lvl);      // expansions of this level that matter (<= n_new)
       const int nxt = cur ^ 1, lb = L & 1;
       if (wav == 0) {
         const float wl = lw.w_logit[L], wv = lw.w_level[L];
@@ -493,6 +493,17 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           sc[i] = lane + 64 * i < n_new ? v : 0;
           bc[i] = (bb << 8) | c;
         }
+        // Once the best list is full, its last score is a floor: an expansion at or below it
+        // can never enter the tree (a tie goes to the lower level), so the level list needs
+        // only the expansions above the floor.  The list as merged two levels ago is the one
+        // this wavefront may read; its floor is lower than the current one, which is safe.
+        int n_keep = n_lvl;
+        if (n_best == theta) {
+          const uint32_t floor_sc = sh.best_sc[bcur][theta - 1];
+          n_keep = min(n_lvl, (int)(__popcll(__ballot(sc[0] > floor_sc)) + __popcll(__ballot(sc[1] > floor_sc)) +
+                                    __popcll(__ballot(sc[2] > floor_sc)) + __popcll(__ballot(sc[3] > floor_sc))));
+        }
+        const int need = max(nb_next, n_keep);   // expansions of this level that matter (<= n_new)
         // A threshold T with at least `need` scores >= T, found bit by bit from the top (every
         // accepted bit keeps that property).  The search stops as soon as few more than `need`
         // scores are left above T: any such T selects a superset of the expansions that matter.
@@ -557,7 +568,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
               sh.beam_ci[nxt][r] = c;
               sh.beam_pi[nxt][r] = sh.beam_ci[cur][bb];
             }
-            if (r < n_lvl) {
+            if (r < n_keep) {
               sh.lvl_key[lb][r] = ((uint64_t)mine << 32) | ((uint64_t)(15 - L) << 28) |
                                   (uint64_t)(0x0FFFFFFF - e);
               sh.lvl_sc[lb][r] = mine;
@@ -566,7 +577,9 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
             }
           }
         }
-        if (lane < ((n_lvl + 3) & ~3) - n_lvl) sh.lvl_sc[lb][n_lvl + lane] = 0;   // padding
+        // the entries not kept and the padding of the last group of four: score 0, which the
+        // merge ranks below every real entry
+        for (int j = n_keep + lane; j < ((n_lvl + 3) & ~3); j += 64) sh.lvl_sc[lb][j] = 0;
         // the next level's scores read what this level placed
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
