@@ -8,7 +8,11 @@
 // and publishes both.  The workgroup that publishes a row's last chunk (a counter per row,
 // reset by that same workgroup) merges the chunk statistics into the row's log-sum-exp and
 // selects the k largest of the chunk winners: no second launch, and the result does not
-// depend on which workgroup happens to be last.
+// depend on which workgroup happens to be last.  With many rows (a batch) the grid is large
+// enough that waiting for stores and counters inside it costs more than a launch: then the
+// chunk kernel only writes its results and a second, one-wavefront-per-row kernel merges them.
+// That form also needs fewer registers (the merge holds up to 40 keys per lane), so more
+// workgroups are resident per compute unit.
 //
 // Selection inside a wavefront (wave_select): the k-th largest of the 64 lane maxima is a
 // lower bound T of the k-th largest value, found (to 16 bits) by a bitwise search with ballots;
@@ -96,6 +100,53 @@ __device__ __forceinline__ void wave_select(const uint64_t (&key)[N], int k, uin
   for (int r = m + lane; r < k; r += 64) emit(r, (uint64_t)0);
 }
 
+// The same selection for a wavefront's slice of a logit row: lane e-th value v[e] is the
+// order-preserving word of logit index idx0 + 64 * e (idx0 already includes the lane), valid for
+// e < ne.  The 64-bit keys are built only for the few entries that reach the candidate buffer.
+template <int N, typename Emit>
+__device__ __forceinline__ void wave_select_row(const uint32_t (&v)[N], int ne, int idx0, int k,
+                                                uint64_t *buf, Emit emit) {
+  const int lane = threadIdx.x & 63;
+  uint32_t hm = 0;
+#pragma unroll
+  for (int e = 0; e < N; ++e) hm = max(hm, e < ne ? v[e] : 0u);
+  uint32_t T = 0;
+  for (int bit = 31; bit >= 16; --bit) {
+    const uint32_t trial = T | (1u << bit);
+    if (__popcll(__ballot(hm >= trial)) >= k) T = trial;
+  }
+  int c = 0;
+#pragma unroll
+  for (int e = 0; e < N; ++e) c += e < ne && v[e] >= T;
+  const int incl = wave_scan_add_dpp(c);
+  const int m = __builtin_amdgcn_readlane(incl, 63);
+  auto key_of = [&](int e) { return ((uint64_t)v[e] << 32) | (uint32_t)(~(uint32_t)(idx0 + 64 * e)); };
+  if (m > TOPK_CAP) {                    // heavy ties: sequential extraction over full keys
+    uint64_t key[N];
+#pragma unroll
+    for (int e = 0; e < N; ++e) key[e] = e < ne ? key_of(e) : 0;
+    wave_extract(key, k, [&](int it, uint64_t best) {
+      if (lane == 0) emit(it, best);
+    });
+    return;
+  }
+  int at = incl - c;
+#pragma unroll
+  for (int e = 0; e < N; ++e)
+    if (e < ne && v[e] >= T) buf[at++] = key_of(e);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  for (int i = lane; i < m; i += 64) {
+    const uint64_t mine = buf[i];
+    int r = 0;
+#pragma unroll 4
+    for (int j = 0; j < m; ++j) r += buf[j] > mine;
+    if (r < k) emit(r, mine);
+  }
+  for (int r = m + lane; r < k; r += 64) emit(r, (uint64_t)0);
+}
+
 // Results that another workgroup (possibly on another XCD, behind another L2) reads in the same
 // launch are written and read with device-scope accesses: they go to the point of coherence
 // without a cache-wide write-back or invalidate, which a __threadfence() per workgroup would
@@ -110,82 +161,22 @@ __device__ __forceinline__ T fetch(const T *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
-    const float *__restrict__ logits, int vocab, int k, int nchunks, float eps,
-    uint64_t *cand, float *ms, int32_t *row_count,
-    int32_t *__restrict__ ids, float *__restrict__ scores) {
-  __shared__ uint64_t wcand[TOPK_WAVES][DART_MAX_TOPK];
-  __shared__ uint64_t sel[TOPK_WAVES][TOPK_CAP];
-  __shared__ float wms[TOPK_WAVES][2];
-  __shared__ int is_last;
-  const int chunk = blockIdx.x, row = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float *src = logits + (size_t)row * vocab;
-  const int base = chunk * TOPK_CHUNK + wave * (TOPK_CHUNK / TOPK_WAVES);
-  uint64_t key[TOPK_PER_THREAD];
-  float val[TOPK_PER_THREAD];
-  float mx = -3.0e38f;
-#pragma unroll
-  for (int e = 0; e < TOPK_PER_THREAD; ++e) {
-    const int idx = base + e * 64 + lane;
-    if (idx < vocab) {
-      val[e] = src[idx];
-      key[e] = ((uint64_t)f32_sortable(val[e]) << 32) | (uint32_t)(~(uint32_t)idx);
-      mx = fmaxf(mx, val[e]);
-    } else {
-      val[e] = -3.0e38f;
-      key[e] = 0;                                  // below every real key
-    }
-  }
-  mx = wave_max_dpp(mx);
-  float se = 0.f;
-#pragma unroll
-  for (int e = 0; e < TOPK_PER_THREAD; ++e)
-    if (key[e] != 0) se += expf(val[e] - mx);
-  se = wave_sum_dpp(se);
-  if (lane == 0) {
-    wms[wave][0] = mx;
-    wms[wave][1] = se;
-  }
-  wave_select(key, k, sel[wave], [&](int r, uint64_t best) { wcand[wave][r] = best; });
-  __syncthreads();
-  const size_t slot = (size_t)row * nchunks + chunk;
-  if (wave == 0) {
-    // chunk statistics in wavefront order (deterministic), then the chunk's k best of 4 x k
-    float cm = wms[0][0];
-#pragma unroll
-    for (int w = 1; w < TOPK_WAVES; ++w) cm = fmaxf(cm, wms[w][0]);
-    float cs = 0.f;
-#pragma unroll
-    for (int w = 0; w < TOPK_WAVES; ++w) cs += wms[w][1] * expf(wms[w][0] - cm);
-    if (lane == 0) {
-      publish(&ms[slot * 2], cm);
-      publish(&ms[slot * 2 + 1], cs);
-    }
-    uint64_t mine[TOPK_WAVES];
-#pragma unroll
-    for (int w = 0; w < TOPK_WAVES; ++w) mine[w] = lane < k ? wcand[w][lane] : 0;
-    wave_select(mine, k, sel[0], [&](int r, uint64_t best) {
-      publish(&cand[slot * DART_MAX_TOPK + r], best);       // 0 when the chunk ran out
-    });
-    // results first (all lanes' stores acknowledged), then the row's arrival count
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (lane == 0)
-      is_last = __hip_atomic_fetch_add(&row_count[row], 1, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT) == nchunks - 1;
-  }
-  __syncthreads();
-  if (!is_last || wave != 0) return;
-  if (lane == 0) publish(&row_count[row], 0);      // ready for the next call
-
-  // the row's last chunk is in: log-sum-exp from the chunk statistics (fixed order)
+// The row's log-sum-exp from the chunk statistics (fixed order) and the k best of the chunk
+// winners, by one wavefront.  COHERENT: the inputs were written in this launch by other
+// workgroups (device-scope loads); otherwise by an earlier launch.
+template <bool COHERENT>
+__device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps, const uint64_t *cand,
+                                          const float *ms, uint64_t *buf, int32_t *__restrict__ ids,
+                                          float *__restrict__ scores) {
+  const int lane = threadIdx.x & 63;
+  auto ld = [](const auto *p) { return COHERENT ? fetch(p) : *p; };
   float rmx = -3.0e38f;
-  for (int c = lane; c < nchunks; c += 64) rmx = fmaxf(rmx, fetch(&ms[((size_t)row * nchunks + c) * 2]));
+  for (int c = lane; c < nchunks; c += 64) rmx = fmaxf(rmx, ld(&ms[((size_t)row * nchunks + c) * 2]));
   rmx = wave_max_dpp(rmx);
   float rse = 0.f;
   for (int c = lane; c < nchunks; c += 64) {
     const size_t sl = (size_t)row * nchunks + c;
-    rse += fetch(&ms[sl * 2 + 1]) * expf(fetch(&ms[sl * 2]) - rmx);
+    rse += ld(&ms[sl * 2 + 1]) * expf(ld(&ms[sl * 2]) - rmx);
   }
   rse = wave_sum_dpp(rse);
   const float lse = rmx + logf(rse);
@@ -201,15 +192,15 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
 #pragma unroll
     for (int e = 0; e < TOPK_MERGE_REGS; ++e) {
       const int j = e * 64 + lane;
-      mine[e] = j < total ? fetch(&csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k]) : 0;
+      mine[e] = j < total ? ld(&csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k]) : 0;
     }
-    wave_select(mine, k, sel[0], emit);
+    wave_select(mine, k, buf, emit);
   } else {                                          // very large vocab x k: re-read from memory
     uint64_t bound = ~(uint64_t)0;
     for (int it = 0; it < k; ++it) {
       uint64_t best = 0;
       for (int j = lane; j < total; j += 64) {
-        const uint64_t kk = fetch(&csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k]);
+        const uint64_t kk = ld(&csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k]);
         if (kk < bound && kk > best) best = kk;
       }
       best = wave_max_u64(best);
@@ -219,11 +210,108 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
   }
 }
 
+// FUSED: the workgroup that completes a row merges it (one launch); otherwise the chunk results
+// are left for topk_merge_kernel.
+template <bool FUSED>
+__global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
+    const float *__restrict__ logits, int vocab, int k, int nchunks, float eps,
+    uint64_t *cand, float *ms, int32_t *row_count,
+    int32_t *__restrict__ ids, float *__restrict__ scores) {
+  __shared__ uint64_t wcand[TOPK_WAVES][DART_MAX_TOPK];
+  __shared__ uint64_t sel[TOPK_WAVES][TOPK_CAP];
+  __shared__ float wms[TOPK_WAVES][2];
+  const int chunk = blockIdx.x, row = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *src = logits + (size_t)row * vocab;
+  const int idx0 = chunk * TOPK_CHUNK + wave * (TOPK_CHUNK / TOPK_WAVES) + lane;
+  // entries of this lane inside the row: indices idx0 + 64 e < vocab
+  const int ne = idx0 < vocab ? min(TOPK_PER_THREAD, (vocab - idx0 + 63) >> 6) : 0;
+  float val[TOPK_PER_THREAD];
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int e = 0; e < TOPK_PER_THREAD; ++e) {
+    val[e] = e < ne ? src[idx0 + e * 64] : -3.0e38f;
+    mx = fmaxf(mx, val[e]);
+  }
+  mx = wave_max_dpp(mx);
+  float se = 0.f;
+  uint32_t v[TOPK_PER_THREAD];
+#pragma unroll
+  for (int e = 0; e < TOPK_PER_THREAD; ++e) {
+    if (e < ne) se += expf(val[e] - mx);
+    v[e] = f32_sortable(val[e]);
+  }
+  se = wave_sum_dpp(se);
+  if (lane == 0) {
+    wms[wave][0] = mx;
+    wms[wave][1] = se;
+  }
+  wave_select_row(v, ne, idx0, k, sel[wave], [&](int r, uint64_t best) { wcand[wave][r] = best; });
+  __syncthreads();
+  // Wavefront 0 finishes the chunk alone; the others leave now, so that their slots go to the
+  // next workgroup's loads while wavefront 0 waits for its stores and the row counter.
+  if (wave != 0) return;
+  const size_t slot = (size_t)row * nchunks + chunk;
+  // chunk statistics in wavefront order (deterministic), then the chunk's k best of 4 x k
+  float cm = wms[0][0];
+#pragma unroll
+  for (int w = 1; w < TOPK_WAVES; ++w) cm = fmaxf(cm, wms[w][0]);
+  float cs = 0.f;
+#pragma unroll
+  for (int w = 0; w < TOPK_WAVES; ++w) cs += wms[w][1] * expf(wms[w][0] - cm);
+  uint64_t mine[TOPK_WAVES];
+#pragma unroll
+  for (int w = 0; w < TOPK_WAVES; ++w) mine[w] = lane < k ? wcand[w][lane] : 0;
+  if (!FUSED) {
+    if (lane == 0) {
+      ms[slot * 2] = cm;
+      ms[slot * 2 + 1] = cs;
+    }
+    wave_select(mine, k, sel[0], [&](int r, uint64_t best) {
+      cand[slot * DART_MAX_TOPK + r] = best;                // 0 when the chunk ran out
+    });
+    return;
+  }
+  if (lane == 0) {
+    publish(&ms[slot * 2], cm);
+    publish(&ms[slot * 2 + 1], cs);
+  }
+  wave_select(mine, k, sel[0], [&](int r, uint64_t best) {
+    publish(&cand[slot * DART_MAX_TOPK + r], best);
+  });
+  // results first (all lanes' stores acknowledged), then the row's arrival count
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  int arrived = 0;
+  if (lane == 0)
+    arrived = __hip_atomic_fetch_add(&row_count[row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (__builtin_amdgcn_readfirstlane(arrived) != nchunks - 1) return;
+  if (lane == 0) publish(&row_count[row], 0);      // ready for the next call
+  merge_row<true>(row, k, nchunks, eps, cand, ms, sel[0], ids, scores);
+}
+
+// grid = rows, one wavefront each
+__global__ __launch_bounds__(64) void topk_merge_kernel(int k, int nchunks, float eps, const uint64_t *cand,
+                                                        const float *ms, int32_t *__restrict__ ids,
+                                                        float *__restrict__ scores) {
+  __shared__ uint64_t buf[TOPK_CAP];
+  merge_row<false>(blockIdx.x, k, nchunks, eps, cand, ms, buf, ids, scores);
+}
+
+// Rows up to this many take the one-launch form.
+constexpr int TOPK_FUSED_ROWS = 16;
+
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st) {
   const int nchunks = (vocab + TOPK_CHUNK - 1) / TOPK_CHUNK;
-  hipLaunchKernelGGL(topk_kernel, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab, k,
-                     nchunks, eps, c->topk_cand, c->topk_ms, c->topk_count, ids, scores);
+  if (rows <= TOPK_FUSED_ROWS) {
+    hipLaunchKernelGGL(topk_kernel<true>, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab,
+                       k, nchunks, eps, c->topk_cand, c->topk_ms, c->topk_count, ids, scores);
+  } else {
+    hipLaunchKernelGGL(topk_kernel<false>, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab,
+                       k, nchunks, eps, c->topk_cand, c->topk_ms, c->topk_count, ids, scores);
+    hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, nchunks, eps, c->topk_cand,
+                       c->topk_ms, ids, scores);
+  }
   return hipGetLastError();
 }
 

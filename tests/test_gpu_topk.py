@@ -75,6 +75,17 @@ def test_128_rows_of_a_batched_step_and_heavy_ties():
     logits[7, ::2] = 4.0
     _check(c, logits, 10)
     _check(c, logits[:9], 64)
+    # more than 16 rows take the two-launch form: its edge shapes, and repeatability
+    _check(c, logits[:40], 64)
+    _check(c, np.ascontiguousarray(logits[:17, :4097]), 64)
+    _check(c, np.ascontiguousarray(logits[:33, :5]), 5)
+    _check(c, np.ascontiguousarray(logits[:128, :1000]), 7)
+    import torch
+    dev = torch.from_numpy(logits).cuda()
+    first = [t.clone() for t in c.topk(dev, 10)]
+    for _ in range(5):
+        ids, scores = c.topk(dev, 10)
+        assert torch.equal(ids, first[0]) and torch.equal(scores, first[1])
     c.close()
 
 
