@@ -266,7 +266,6 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   c->topk_chunks_max = (g.vocab + 4095) / 4096;
   HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
   HIP_TRY(dev_alloc(&c->topk_ms, (size_t)c->max_rows * c->topk_chunks_max * 2));
-  HIP_TRY(dev_alloc(&c->topk_count, (size_t)c->max_rows, true));
   return hipSuccess;
 }
 
@@ -538,7 +537,7 @@ void dart_destroy(dart_ctx *c) {
                   c->wqkv.data, c->wo.data, c->wgu.data, c->wdown.data, c->wlm.data, c->g_in,
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
-                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms, c->topk_count,
+                  c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
                   c->xn_kv, c->kv_part, c->xpack, c->xpack2, c->wfc.data, c->embed, c->g_emb, c->feat32,
                   c->fc_part};
   for (void *p : bufs)

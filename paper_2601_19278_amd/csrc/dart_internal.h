@@ -157,7 +157,6 @@ struct dart_ctx {
   // top-k workspace
   uint64_t *topk_cand = nullptr;  // [rows][chunks][DART_MAX_TOPK]
   float *topk_ms = nullptr;       // [rows][chunks][2]
-  int32_t *topk_count = nullptr;  // [rows] chunks of the row published so far (0 between calls)
   int topk_chunks_max;
 };
 

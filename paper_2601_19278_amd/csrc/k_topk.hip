@@ -1,18 +1,17 @@
 // Per-position candidate extraction (paper Alg. 1 "Top-k_i tokens from l_i" and
 // s_logit = log(softmax(l)_{i,t} + eps), App. D): one read of each logit row yields the
-// k best tokens and the row's log-sum-exp together, in one launch.
+// k best tokens and the row's log-sum-exp together.
 //
-// Grid: vocab chunks x rows.  A workgroup holds a 4096-logit chunk in registers, 1024 per
-// wavefront.  Each wavefront computes its (max, sum exp) and selects its k largest entries;
-// wavefront 0 then reduces the 4 x k winners to the chunk's k, combines the four statistics
-// and publishes both.  The workgroup that publishes a row's last chunk (a counter per row,
-// reset by that same workgroup) merges the chunk statistics into the row's log-sum-exp and
-// selects the k largest of the chunk winners: no second launch, and the result does not
-// depend on which workgroup happens to be last.  With many rows (a batch) the grid is large
-// enough that waiting for stores and counters inside it costs more than a launch: then the
-// chunk kernel only writes its results and a second, one-wavefront-per-row kernel merges them.
-// That form also needs fewer registers (the merge holds up to 40 keys per lane), so more
-// workgroups are resident per compute unit.
+// Chunk kernel, grid: vocab chunks x rows.  A workgroup holds a 4096-logit chunk in registers,
+// 1024 per wavefront.  Each wavefront computes its (max, sum exp) and selects its k largest
+// entries; wavefront 0 then reduces the 4 x k winners to the chunk's k, combines the four
+// statistics and writes both, while the other wavefronts have already left and made room for
+// the next workgroup's loads.  Merge kernel, one wavefront per row: the chunk statistics give
+// the row's log-sum-exp (fixed order) and the k largest of the chunk winners are the row's.
+// A fused form (the workgroup that completes a row merges it, found through a device-scope
+// counter) was slower at every row count: the wait for the stores and the counter sits inside
+// every workgroup, and the merge's 40 keys per lane set the register count of the whole kernel
+// (96 against 48, five wavefronts per SIMD against eight).
 //
 // Selection inside a wavefront (wave_select): the k-th largest of the 64 lane maxima is a
 // lower bound T of the k-th largest value, found (to 16 bits) by a bitwise search with ballots;
@@ -147,36 +146,19 @@ __device__ __forceinline__ void wave_select_row(const uint32_t (&v)[N], int ne, 
   for (int r = m + lane; r < k; r += 64) emit(r, (uint64_t)0);
 }
 
-// Results that another workgroup (possibly on another XCD, behind another L2) reads in the same
-// launch are written and read with device-scope accesses: they go to the point of coherence
-// without a cache-wide write-back or invalidate, which a __threadfence() per workgroup would
-// cost.  Order: a publisher waits until its stores are acknowledged, then bumps the row's
-// counter; the workgroup that reads the final count issues its loads after that read.
-template <typename T>
-__device__ __forceinline__ void publish(T *p, T v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T>
-__device__ __forceinline__ T fetch(const T *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // The row's log-sum-exp from the chunk statistics (fixed order) and the k best of the chunk
-// winners, by one wavefront.  COHERENT: the inputs were written in this launch by other
-// workgroups (device-scope loads); otherwise by an earlier launch.
-template <bool COHERENT>
+// winners, by one wavefront.
 __device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps, const uint64_t *cand,
                                           const float *ms, uint64_t *buf, int32_t *__restrict__ ids,
                                           float *__restrict__ scores) {
   const int lane = threadIdx.x & 63;
-  auto ld = [](const auto *p) { return COHERENT ? fetch(p) : *p; };
   float rmx = -3.0e38f;
-  for (int c = lane; c < nchunks; c += 64) rmx = fmaxf(rmx, ld(&ms[((size_t)row * nchunks + c) * 2]));
+  for (int c = lane; c < nchunks; c += 64) rmx = fmaxf(rmx, ms[((size_t)row * nchunks + c) * 2]);
   rmx = wave_max_dpp(rmx);
   float rse = 0.f;
   for (int c = lane; c < nchunks; c += 64) {
     const size_t sl = (size_t)row * nchunks + c;
-    rse += ld(&ms[sl * 2 + 1]) * expf(ld(&ms[sl * 2]) - rmx);
+    rse += ms[sl * 2 + 1] * expf(ms[sl * 2] - rmx);
   }
   rse = wave_sum_dpp(rse);
   const float lse = rmx + logf(rse);
@@ -192,7 +174,7 @@ __device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps
 #pragma unroll
     for (int e = 0; e < TOPK_MERGE_REGS; ++e) {
       const int j = e * 64 + lane;
-      mine[e] = j < total ? ld(&csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k]) : 0;
+      mine[e] = j < total ? csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k] : 0;
     }
     wave_select(mine, k, buf, emit);
   } else {                                          // very large vocab x k: re-read from memory
@@ -200,7 +182,7 @@ __device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps
     for (int it = 0; it < k; ++it) {
       uint64_t best = 0;
       for (int j = lane; j < total; j += 64) {
-        const uint64_t kk = ld(&csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k]);
+        const uint64_t kk = csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k];
         if (kk < bound && kk > best) best = kk;
       }
       best = wave_max_u64(best);
@@ -210,13 +192,9 @@ __device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps
   }
 }
 
-// FUSED: the workgroup that completes a row merges it (one launch); otherwise the chunk results
-// are left for topk_merge_kernel.
-template <bool FUSED>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
-    const float *__restrict__ logits, int vocab, int k, int nchunks, float eps,
-    uint64_t *cand, float *ms, int32_t *row_count,
-    int32_t *__restrict__ ids, float *__restrict__ scores) {
+    const float *__restrict__ logits, int vocab, int k, int nchunks,
+    uint64_t *__restrict__ cand, float *__restrict__ ms) {
   __shared__ uint64_t wcand[TOPK_WAVES][DART_MAX_TOPK];
   __shared__ uint64_t sel[TOPK_WAVES][TOPK_CAP];
   __shared__ float wms[TOPK_WAVES][2];
@@ -248,8 +226,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
   }
   wave_select_row(v, ne, idx0, k, sel[wave], [&](int r, uint64_t best) { wcand[wave][r] = best; });
   __syncthreads();
-  // Wavefront 0 finishes the chunk alone; the others leave now, so that their slots go to the
-  // next workgroup's loads while wavefront 0 waits for its stores and the row counter.
+  // Wavefront 0 finishes the chunk alone; the others leave now.
   if (wave != 0) return;
   const size_t slot = (size_t)row * nchunks + chunk;
   // chunk statistics in wavefront order (deterministic), then the chunk's k best of 4 x k
@@ -262,31 +239,13 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(
   uint64_t mine[TOPK_WAVES];
 #pragma unroll
   for (int w = 0; w < TOPK_WAVES; ++w) mine[w] = lane < k ? wcand[w][lane] : 0;
-  if (!FUSED) {
-    if (lane == 0) {
-      ms[slot * 2] = cm;
-      ms[slot * 2 + 1] = cs;
-    }
-    wave_select(mine, k, sel[0], [&](int r, uint64_t best) {
-      cand[slot * DART_MAX_TOPK + r] = best;                // 0 when the chunk ran out
-    });
-    return;
-  }
   if (lane == 0) {
-    publish(&ms[slot * 2], cm);
-    publish(&ms[slot * 2 + 1], cs);
+    ms[slot * 2] = cm;
+    ms[slot * 2 + 1] = cs;
   }
   wave_select(mine, k, sel[0], [&](int r, uint64_t best) {
-    publish(&cand[slot * DART_MAX_TOPK + r], best);
+    cand[slot * DART_MAX_TOPK + r] = best;                  // 0 when the chunk ran out
   });
-  // results first (all lanes' stores acknowledged), then the row's arrival count
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  int arrived = 0;
-  if (lane == 0)
-    arrived = __hip_atomic_fetch_add(&row_count[row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (__builtin_amdgcn_readfirstlane(arrived) != nchunks - 1) return;
-  if (lane == 0) publish(&row_count[row], 0);      // ready for the next call
-  merge_row<true>(row, k, nchunks, eps, cand, ms, sel[0], ids, scores);
 }
 
 // grid = rows, one wavefront each
@@ -294,24 +253,16 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(int k, int nchunks, floa
                                                         const float *ms, int32_t *__restrict__ ids,
                                                         float *__restrict__ scores) {
   __shared__ uint64_t buf[TOPK_CAP];
-  merge_row<false>(blockIdx.x, k, nchunks, eps, cand, ms, buf, ids, scores);
+  merge_row(blockIdx.x, k, nchunks, eps, cand, ms, buf, ids, scores);
 }
-
-// Rows up to this many take the one-launch form.
-constexpr int TOPK_FUSED_ROWS = 16;
 
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st) {
   const int nchunks = (vocab + TOPK_CHUNK - 1) / TOPK_CHUNK;
-  if (rows <= TOPK_FUSED_ROWS) {
-    hipLaunchKernelGGL(topk_kernel<true>, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab,
-                       k, nchunks, eps, c->topk_cand, c->topk_ms, c->topk_count, ids, scores);
-  } else {
-    hipLaunchKernelGGL(topk_kernel<false>, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab,
-                       k, nchunks, eps, c->topk_cand, c->topk_ms, c->topk_count, ids, scores);
-    hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, nchunks, eps, c->topk_cand,
-                       c->topk_ms, ids, scores);
-  }
+  hipLaunchKernelGGL(topk_kernel, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab, k,
+                     nchunks, c->topk_cand, c->topk_ms);
+  hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, nchunks, eps, c->topk_cand,
+                     c->topk_ms, ids, scores);
   return hipGetLastError();
 }
 
