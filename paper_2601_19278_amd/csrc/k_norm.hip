@@ -174,7 +174,8 @@ __global__ __launch_bounds__(ROW_THREADS) void front_norm_kernel(
 // pack != null: yn is also written as the packed operand tiles of the multi-row projection
 // that consumes it (ntiles row tiles, ksteps k-steps); the grid then covers the padded rows
 // ntiles*16, and rows >= rows and inputs >= d are written as zeros.
-template <typename T>
+// NJ: column groups of 8 per thread (ceil(d / (8 * ROW_THREADS))).
+template <typename T, int NJ>
 __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
     const float *__restrict__ resid, const float *__restrict__ part, int chunks, size_t chunk_stride,
     int row_stride, const T *__restrict__ gain, int rows, int d, float eps, float *__restrict__ y,
@@ -187,45 +188,53 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
   }
   if (pack)
     for (int c = d + threadIdx.x * 8; c < ksteps * 32; c += ROW_THREADS * 8) pack_zero8(pack, ntiles, terms, r, c);
-  float v[ROW_MAXIT][8], g[ROW_MAXIT][8];
+  float v[NJ][8], g[NJ][8];
 #pragma unroll
-  for (int j = 0; j < ROW_MAXIT; ++j) {
+  for (int j = 0; j < NJ; ++j) {
     const int c = (j * ROW_THREADS + threadIdx.x) * 8;
     if (c < d) {
       load8(resid + (size_t)r * d + c, v[j]);
       load8(gain + c, g[j]);
     }
   }
-  // chunk partials: up to 8 loads in flight per column group, added in index order
-  constexpr int U = 8;
+  // chunk partials, added in index order.  The loads of a batch of chunks are issued for all
+  // of the thread's column groups before the first add: the kernel is one workgroup per row
+  // and its time is the number of such round trips.
+  constexpr int U = NJ <= 2 ? 8 : 4;
   for (int k0 = 0; k0 < chunks; k0 += U) {
+    float p[NJ][U][8];
 #pragma unroll
-    for (int j = 0; j < ROW_MAXIT; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int c = (j * ROW_THREADS + threadIdx.x) * 8;
       if (c < d) {
-        float p[U][8];
 #pragma unroll
         for (int u = 0; u < U; ++u)
           if (k0 + u < chunks)
-            load8(part + (size_t)(k0 + u) * chunk_stride + (size_t)r * row_stride + c, p[u]);
+            load8(part + (size_t)(k0 + u) * chunk_stride + (size_t)r * row_stride + c, p[j][u]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+      if (c < d) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
           if (k0 + u < chunks)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[j][e] += p[u][e];
+            for (int e = 0; e < 8; ++e) v[j][e] += p[j][u][e];
       }
     }
   }
   float ss = 0.f;
 #pragma unroll
-  for (int j = 0; j < ROW_MAXIT; ++j)
+  for (int j = 0; j < NJ; ++j)
     if ((j * ROW_THREADS + threadIdx.x) * 8 < d)
 #pragma unroll
       for (int e = 0; e < 8; ++e) ss += v[j][e] * v[j][e];
   ss = block_sum(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
-  for (int j = 0; j < ROW_MAXIT; ++j) {
+  for (int j = 0; j < NJ; ++j) {
     const int c = (j * ROW_THREADS + threadIdx.x) * 8;
     if (c < d) {
       store8(y + (size_t)r * d + c, v[j]);
@@ -321,14 +330,23 @@ hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, i
     gemm_bf16_pack_shape(rows, d, &ntiles, &ksteps);
     grid = ntiles * 16;
   }
-  if (dtype == DART_BF16)
-    hipLaunchKernelGGL(resid_norm_kernel<bf16_t>, dim3(grid), dim3(ROW_THREADS), 0, st, resid, part,
-                       chunks, chunk_stride, row_stride, (const bf16_t *)gain, rows, d, eps, y, yn,
-                       (uint4 *)pack, ntiles, ksteps, terms);
-  else
-    hipLaunchKernelGGL(resid_norm_kernel<float>, dim3(grid), dim3(ROW_THREADS), 0, st, resid, part,
-                       chunks, chunk_stride, row_stride, (const float *)gain, rows, d, eps, y, yn,
-                       (uint4 *)nullptr, 0, 0, 2);
+  const int nj = (d + 8 * ROW_THREADS - 1) / (8 * ROW_THREADS);
+  if (nj > ROW_MAXIT) return hipErrorInvalidValue;
+#define DART_RESID_NORM_GO(NJ_)                                                                     \
+  do {                                                                                              \
+    if (dtype == DART_BF16)                                                                         \
+      hipLaunchKernelGGL((resid_norm_kernel<bf16_t, NJ_>), dim3(grid), dim3(ROW_THREADS), 0, st,    \
+                         resid, part, chunks, chunk_stride, row_stride, (const bf16_t *)gain, rows, \
+                         d, eps, y, yn, (uint4 *)pack, ntiles, ksteps, terms);                      \
+    else                                                                                            \
+      hipLaunchKernelGGL((resid_norm_kernel<float, NJ_>), dim3(grid), dim3(ROW_THREADS), 0, st,     \
+                         resid, part, chunks, chunk_stride, row_stride, (const float *)gain, rows,  \
+                         d, eps, y, yn, (uint4 *)nullptr, 0, 0, 2);                                 \
+  } while (0)
+  if (nj == 1) DART_RESID_NORM_GO(1);
+  else if (nj == 2) DART_RESID_NORM_GO(2);
+  else DART_RESID_NORM_GO(4);
+#undef DART_RESID_NORM_GO
   return hipGetLastError();
 }
 

@@ -7,65 +7,87 @@
 
 namespace dart {
 
-// grid (pass rows, Hq + 2*Hkv heads), block = head_dim threads.
+// grid (pass rows, ceil((Hq + 2*Hkv) / 4)), block = 4 wavefronts, one head each.  Lane l < hd/2
+// holds elements l and l + hd/2 of its head, the two a rotary rotation mixes, so a head needs no
+// LDS and no barrier; the head's sum of squares is a wavefront reduction.
 // Pass row i is position pos of sequence b (SeqBatch); q is produced for query rows only and
 // stored at the compact index b*K + j; k and v of every row go to the sequence's K/V slot.
 // T: storage type of the norm gains; CT: element type of q and of the K/V buffers.
+constexpr int QKV_POST_HEADS = 4;
 template <typename T, typename CT>
-__global__ __launch_bounds__(128) void qkv_post_kernel(
+__global__ __launch_bounds__(64 * QKV_POST_HEADS) void qkv_post_kernel(
     SeqBatch sb, const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride,
     int col0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
     const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
     const float *__restrict__ sin_tab, CT *__restrict__ q_out, CT *__restrict__ kbuf,
     CT *__restrict__ vbuf, size_t slot_elems, int t_cap, int tiled) {
-  __shared__ float red[16];
-  __shared__ float sh[128];
-  const int i = blockIdx.x, hh = blockIdx.y, t = threadIdx.x;
+  const int i = blockIdx.x, hh = blockIdx.y * QKV_POST_HEADS + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, half = hd >> 1;
+  if (hh >= Hq + 2 * Hkv) return;                 // uniform per wavefront, like the exits below
   int b, pos, qi;
   seq_of_row(sb, i, b, pos, qi);
   const bool is_q = hh < Hq, is_k = !is_q && hh < Hq + Hkv;
-  if (is_q && qi < 0) return;                     // non-query rows need no q (uniform per block)
+  if (is_q && qi < 0) return;                     // non-query rows need no q
+  const bool act = lane < half;
   kbuf += (size_t)sb.slot[b] * slot_elems;
   vbuf += (size_t)sb.slot[b] * slot_elems;
-  const int col = hh * hd + t - col0;             // q heads, then k heads, then v heads
-  // chunk partials: up to 8 loads in flight, added in index order
-  float x = 0.f;
-  const float *src = qkv + (size_t)i * row_stride + col;
+  const int t0 = lane, t1 = lane + half;          // the lane's two elements of the head
+  // chunk partials: up to 8 chunks in flight, added in index order
+  float x0 = 0.f, x1 = 0.f;
+  const float *src = qkv + (size_t)i * row_stride + (hh * hd - col0);   // q, then k, then v heads
   for (int c0 = 0; c0 < chunks; c0 += 8) {
-    float p[8];
+    float p0[8], p1[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) p[u] = c0 + u < chunks ? src[(size_t)(c0 + u) * chunk_stride] : 0.f;
+    for (int u = 0; u < 8; ++u) {
+      const bool in = act && c0 + u < chunks;
+      p0[u] = in ? src[(size_t)(c0 + u) * chunk_stride + t0] : 0.f;
+      p1[u] = in ? src[(size_t)(c0 + u) * chunk_stride + t1] : 0.f;
+    }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (c0 + u < chunks) x += p[u];
+      if (c0 + u < chunks) {
+        x0 += p0[u];
+        x1 += p1[u];
+      }
   }
 
   if (!is_q && !is_k) {                           // value head: store as is
     const int g = hh - Hq - Hkv;
-    if (tiled)
-      vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t, hd)] = from_f32<CT>(x);
-    else
-      vbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(x);
+    if (!act) return;
+    if (tiled) {
+      vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t0, hd)] = from_f32<CT>(x0);
+      vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t1, hd)] = from_f32<CT>(x1);
+    } else {
+      vbuf[((size_t)g * t_cap + pos) * hd + t0] = from_f32<CT>(x0);
+      vbuf[((size_t)g * t_cap + pos) * hd + t1] = from_f32<CT>(x1);
+    }
     return;
   }
   if (qk_norm) {
-    const float ss = block_sum(x * x, red);
-    x = x * (1.0f / sqrtf(ss / (float)hd + eps)) * to_f32((is_q ? q_gain : k_gain)[t]);
+    const float ss = wave_sum_dpp(act ? x0 * x0 + x1 * x1 : 0.f);
+    const float rinv = 1.0f / sqrtf(ss / (float)hd + eps);
+    const T *gain = is_q ? q_gain : k_gain;
+    if (act) {
+      x0 = x0 * rinv * to_f32(gain[t0]);
+      x1 = x1 * rinv * to_f32(gain[t1]);
+    }
   }
-  sh[t] = x;
-  __syncthreads();
-  const int half = hd >> 1;
-  const int fi = t < half ? t : t - half;
-  const float c = cos_tab[(size_t)pos * half + fi], s = sin_tab[(size_t)pos * half + fi];
-  const float y = t < half ? x * c - sh[t + half] * s : x * c + sh[t - half] * s;
+  if (!act) return;
+  const float c = cos_tab[(size_t)pos * half + lane], s = sin_tab[(size_t)pos * half + lane];
+  const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
   if (is_q) {
-    q_out[((size_t)(b * sb.K + qi) * Hq + hh) * hd + t] = from_f32<CT>(y);
+    CT *dst = q_out + ((size_t)(b * sb.K + qi) * Hq + hh) * hd;
+    dst[t0] = from_f32<CT>(y0);
+    dst[t1] = from_f32<CT>(y1);
   } else {
     const int g = hh - Hq;
-    if (tiled)
-      kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t, hd)] = from_f32<CT>(y);
-    else
-      kbuf[((size_t)g * t_cap + pos) * hd + t] = from_f32<CT>(y);
+    if (tiled) {
+      kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t0, hd)] = from_f32<CT>(y0);
+      kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t1, hd)] = from_f32<CT>(y1);
+    } else {
+      kbuf[((size_t)g * t_cap + pos) * hd + t0] = from_f32<CT>(y0);
+      kbuf[((size_t)g * t_cap + pos) * hd + t1] = from_f32<CT>(y1);
+    }
   }
 }
 
@@ -74,7 +96,8 @@ hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *q
   const dart_config &g = c->cfg;
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
   const size_t slot_elems = (size_t)Hkv * c->t_cap * hd;
-  dim3 grid(sb.row_off[sb.B], Hq + 2 * Hkv), block(hd);
+  if (hd > 128 || (hd & 1)) return hipErrorInvalidValue;
+  dim3 grid(sb.row_off[sb.B], (Hq + 2 * Hkv + QKV_POST_HEADS - 1) / QKV_POST_HEADS), block(64 * QKV_POST_HEADS);
   if (g.dtype == DART_BF16) {
     hipLaunchKernelGGL((qkv_post_kernel<bf16_t, f16_t>), grid, block, 0, st, sb, qkv, chunks,
                        chunk_stride, row_stride, col0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
