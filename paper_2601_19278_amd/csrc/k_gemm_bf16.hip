@@ -339,11 +339,14 @@ hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipSt
 int g_gemm_wgs = 256;      // resident workgroups: one per compute unit
 
 // k-chunks of a matrix on this path: fixed per matrix so that a row's sums do not depend on
-// the call.  Matrices with few strips are cut along k until (strip ranges of about 16 strips)
-// x chunks fill the compute units; chunks are at least 16 k-steps long.
+// the call.  Matrices with few strips are cut along k until (strip ranges of 8 strips, one per
+// wavefront) x chunks fill the compute units; chunks are at least 16 k-steps long.  Narrow
+// ranges keep the chunk count, and with it the fp32 partial sums written here and read back by
+// the next kernel, small: at 128 rows a chunk of partials is a quarter of the O projection's
+// weights.
 int gemm_bf16_chunks(int Kd, int nstrips) {
   const int KT = Kd / 32;
-  const int groups = (nstrips + 2 * GEMM_WAVES - 1) / (2 * GEMM_WAVES);
+  const int groups = (nstrips + GEMM_WAVES - 1) / GEMM_WAVES;
   if (groups >= g_gemm_wgs / 2) return 1;
   int nch = g_gemm_wgs / groups;          // rounded down: one more unit than workgroups costs a second round
   nch = min(nch, max(1, KT / 16));
