@@ -110,6 +110,40 @@ __device__ __forceinline__ int wave_scan_add_dpp(int v) {
   return v;
 }
 
+// x of this lane and of lane ^ 16 (lane ^ 32), as the two values of every lane, on the VALU:
+// v_permlane16_swap exchanges the odd rows of 16 lanes of its first operand with the even rows
+// of its second, v_permlane32_swap the upper half of the first with the lower half of the
+// second; with both operands equal to x the two results hold x[lane & ~16] and x[lane | 16]
+// (x[lane & 31] and x[lane | 32]).  The __shfl_xor forms go through the LDS instead, behind
+// whatever else is queued there.
+__device__ __forceinline__ void xor16_pair(float x, float &a, float &b) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  a = __uint_as_float(r[0]);
+  b = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void xor32_pair(float x, float &a, float &b) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  a = __uint_as_float(r[0]);
+  b = __uint_as_float(r[1]);
+}
+// max / sum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the same value in all four)
+__device__ __forceinline__ float quad16_max(float x) {
+  float a, b;
+  xor16_pair(x, a, b);
+  x = fmaxf(a, b);
+  xor32_pair(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float quad16_sum(float x) {
+  float a, b;
+  xor16_pair(x, a, b);
+  x = a + b;
+  xor32_pair(x, a, b);
+  return a + b;
+}
+
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   const uint32_t hi = (uint32_t)(v >> 32);
   const uint32_t mh = wave_max_u32(hi);

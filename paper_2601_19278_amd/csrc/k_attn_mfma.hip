@@ -216,8 +216,7 @@ __global__ __launch_bounds__(64 * NW) void attn_split_mfma_kernel(
                 s[tt][r] = vis ? s[tt][r] * scale : -3.0e38f;
                 mloc = fmaxf(mloc, s[tt][r]);
               }
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 16, DART_WAVE));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, DART_WAVE));
+            mloc = quad16_max(mloc);
             const float mn = fmaxf(m[a], mloc);
             const float corr = __expf(m[a] - mn);
             float lsum = 0.f;
@@ -230,8 +229,7 @@ __global__ __launch_bounds__(64 * NW) void attn_split_mfma_kernel(
                 lsum += p;
                 pop.e[4 * tt + r] = (f16_t)p;
               }
-            lsum += __shfl_xor(lsum, 16, DART_WAVE);
-            lsum += __shfl_xor(lsum, 32, DART_WAVE);
+            lsum = quad16_sum(lsum);
             l[a] = l[a] * corr + lsum;
             m[a] = mn;
 #pragma unroll
