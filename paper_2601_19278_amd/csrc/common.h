@@ -36,25 +36,6 @@ template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) {
   return (f16_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, DART_WAVE);
-  return v;
-}
-
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, DART_WAVE));
-  return v;
-}
-
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int off) {
-  uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-  lo = __shfl_xor(lo, off, DART_WAVE);
-  hi = __shfl_xor(hi, off, DART_WAVE);
-  return ((uint64_t)hi << 32) | lo;
-}
-
 // Wavefront-wide max of an unsigned 32-bit value on the DPP data path (row shifts, then the
 // gfx9 row broadcasts), result returned to every lane.  Lanes without a DPP source read 0,
 // which is neutral for an unsigned max, and max is idempotent, so overlapping shifts are fine.
@@ -99,6 +80,8 @@ __device__ __forceinline__ float wave_max_dpp(float v) {
   v = fmaxf(v, dpp_f32<0x143, 0xc>(lo, v));
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
+__device__ __forceinline__ float wave_sum(float v) { return wave_sum_dpp(v); }
+__device__ __forceinline__ float wave_max(float v) { return wave_max_dpp(v); }   // values >= -3e38
 // Inclusive prefix sum over the lanes (lane i: sum of lanes 0..i).
 __device__ __forceinline__ int wave_scan_add_dpp(int v) {
   v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);
