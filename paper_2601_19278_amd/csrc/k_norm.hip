@@ -200,7 +200,7 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
   // chunk partials, added in index order.  The loads of a batch of chunks are issued for all
   // of the thread's column groups before the first add: the kernel is one workgroup per row
   // and its time is the number of such round trips.
-  constexpr int U = NJ <= 2 ? 8 : 4;
+  constexpr int U = NJ <= 2 ? 9 : 4;     // 9: the 17 chunks of a 17408-input projection in two batches
   for (int k0 = 0; k0 < chunks; k0 += U) {
     float p[NJ][U][8];
 #pragma unroll
