@@ -152,14 +152,33 @@ __device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps
                                           const float *ms, uint64_t *buf, int32_t *__restrict__ ids,
                                           float *__restrict__ scores) {
   const int lane = threadIdx.x & 63;
-  float rmx = -3.0e38f;
-  for (int c = lane; c < nchunks; c += 64) rmx = fmaxf(rmx, ms[((size_t)row * nchunks + c) * 2]);
-  rmx = wave_max_dpp(rmx);
-  float rse = 0.f;
-  for (int c = lane; c < nchunks; c += 64) {
-    const size_t sl = (size_t)row * nchunks + c;
-    rse += ms[sl * 2 + 1] * expf(ms[sl * 2] - rmx);
+  const uint64_t *csrc = cand + (size_t)row * nchunks * DART_MAX_TOPK;
+  // Candidates first (the longest wait): winner j of the row's nchunks * k, lane by lane, so that
+  // every lane holds a mixed handful (the selection's threshold is the k-th largest lane
+  // maximum).  j / k by a multiplication: floor(j * ceil(2^32 / k) / 2^32) is exact while
+  // j * (k - 1) < 2^32.
+  const int total = nchunks * k;
+  const bool in_regs = total <= 64 * TOPK_MERGE_REGS;
+  uint64_t mine[TOPK_MERGE_REGS];
+  if (in_regs) {
+    const uint32_t inv_k = (uint32_t)((((uint64_t)1 << 32) + k - 1) / k);
+#pragma unroll
+    for (int e = 0; e < TOPK_MERGE_REGS; ++e) {
+      const int j = e * 64 + lane;
+      const int c = k == 1 ? j : (int)__umulhi((uint32_t)j, inv_k);
+      mine[e] = j < total ? csrc[(size_t)c * DART_MAX_TOPK + (j - c * k)] : 0;
+    }
   }
+  // chunk statistics: read once (one chunk per lane up to 64 chunks), combined in lane order
+  const float2 *ms2 = reinterpret_cast<const float2 *>(ms) + (size_t)row * nchunks;
+  float rmx = -3.0e38f;
+  float2 own = make_float2(-3.0e38f, 0.f);
+  if (lane < nchunks) own = ms2[lane];
+  rmx = own.x;
+  for (int c = lane + 64; c < nchunks; c += 64) rmx = fmaxf(rmx, ms2[c].x);
+  rmx = wave_max_dpp(rmx);
+  float rse = lane < nchunks ? own.y * expf(own.x - rmx) : 0.f;
+  for (int c = lane + 64; c < nchunks; c += 64) rse += ms2[c].y * expf(ms2[c].x - rmx);
   rse = wave_sum_dpp(rse);
   const float lse = rmx + logf(rse);
   auto emit = [&](int it, uint64_t best) {
@@ -167,15 +186,7 @@ __device__ __forceinline__ void merge_row(int row, int k, int nchunks, float eps
     ids[(size_t)row * k + it] = (int32_t)(~(uint32_t)best);
     scores[(size_t)row * k + it] = fminf(0.f, logf(expf(logit - lse) + eps));
   };
-  const int total = nchunks * k;
-  const uint64_t *csrc = cand + (size_t)row * nchunks * DART_MAX_TOPK;
-  if (total <= 64 * TOPK_MERGE_REGS) {
-    uint64_t mine[TOPK_MERGE_REGS];
-#pragma unroll
-    for (int e = 0; e < TOPK_MERGE_REGS; ++e) {
-      const int j = e * 64 + lane;
-      mine[e] = j < total ? csrc[(size_t)(j / k) * DART_MAX_TOPK + j % k] : 0;
-    }
+  if (in_regs) {
     wave_select(mine, k, buf, emit);
   } else {                                          // very large vocab x k: re-read from memory
     uint64_t bound = ~(uint64_t)0;

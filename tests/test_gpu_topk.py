@@ -89,6 +89,19 @@ def test_128_rows_of_a_batched_step_and_heavy_ties():
     c.close()
 
 
+def test_vocabulary_with_more_chunks_than_merge_registers():
+    """More chunk winners (chunks x k) than the row merge holds in registers: it re-reads them."""
+    cfg = ds.scaled_config("C1", vocab=170000, K=4, batch=1)
+    c, _ = make_context(cfg, 52, max_K=4)
+    rng = np.random.default_rng(12)
+    logits = (rng.standard_normal((3, 170000)) * 2).astype(np.float32)
+    logits[2, 169990:] = 9.0                          # winners in the ragged last chunk, tied
+    _check(c, logits, 10)
+    _check(c, logits, 1)
+    _check(c, logits, 64)                             # 42 chunks x 64 > 2560: the re-read path
+    c.close()
+
+
 def test_error_statuses(ctx):
     import torch
     import paper_2601_19278_amd as dart
