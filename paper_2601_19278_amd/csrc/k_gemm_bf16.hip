@@ -42,6 +42,13 @@ template <int NCT, int TERMS>
 struct GemmStage {
   u32x4_t t[GEMM_KS][NCT * TERMS][64];
 };
+// LDS stages in the ring.  A stage is copied GEMM_STAGES - 1 stages before it is read: with one
+// stage of lookahead a stage cannot take less than the latency of its copy, which bounds the
+// passes with few strips per wavefront (8 KiB of weights per stage and workgroup instead of
+// 64) -- the k-chunked projections and the short last pass of the LM head.  The two-term
+// format keeps two stages (its tiles are twice as large and static LDS ends at 64 KiB).
+template <int TERMS>
+constexpr int gemm_stages() { return TERMS == 1 ? 4 : 2; }
 
 // The main loop keeps three kinds of memory traffic in flight at once: weight tiles for the
 // next two k-steps (global -> registers), the next stage of activation tiles (global -> LDS,
@@ -117,9 +124,9 @@ struct GemmArgs {
 // TERMS 2: bf16 weights, activations as bf16 hi + lo (two products per tile pair).
 // TERMS 1: fp16 weights and fp16 activations (one product).
 template <int NCT, int SP, int EPI, int TERMS>
-__device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERMS> *st0,
-                                          GemmStage<NCT, TERMS> *st1, int rb, int chunk, int k0,
-                                          int nk, int sfirst, int ns, int wave) {
+__device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERMS> *ring, int rb,
+                                          int chunk, int k0, int nk, int sfirst, int ns, int wave) {
+  constexpr int NS = gemm_stages<TERMS>(), LA = NS - 1;   // ring size, stages of lookahead
   const int lane = threadIdx.x & 63;
   const int kend = k0 + nk;                               // k-steps [k0, kend) of this chunk
   const int nkp = (nk + GEMM_KS - 1) / GEMM_KS * GEMM_KS;  // an odd tail reads the zero k-step
@@ -165,14 +172,21 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
   // wavefront (64 to 128 KiB per compute unit) whatever the number of strips, so that neither
   // the full passes nor the ones with few strips per wavefront are bound by memory latency.
   constexpr int PD = SP == 4 ? 4 : 8 / SP;
-  constexpr int UNR = PD < 4 ? 4 : PD;                    // k-steps per unrolled loop body
+  // k-steps per unrolled loop body: a multiple of the weight ring and of the stage ring, so
+  // that both kinds of slot are static
+  constexpr int UNR = NS == 4 ? 8 : (PD < 4 ? 4 : PD);
+  static_assert(UNR % PD == 0 && (UNR / GEMM_KS) % NS == 0, "static ring slots");
   u32x4_t aop[PD][SP];
-  // prologue: stage 0 and the weight tiles of the first PD k-steps, issued in the same
-  // pattern as the loop issues them (per stage: copies, then two k-steps of tiles; stage 0 is
-  // simply copied PD/2 times), so that the counted waits below hold from the first k-step on
+  // prologue: the first LA stages, then the weight tiles of the first PD k-steps, issued in
+  // the same pattern as the loop issues them (per stage: copies, then two k-steps of tiles;
+  // the copies of that pattern just repeat the last of the LA stages), so that the counted
+  // waits below hold from the first k-step on
+  const int klast = k0 + nkp - GEMM_KS;                   // first k-step of the last stage
+#pragma unroll
+  for (int j = 0; j < LA; ++j) stage_copy(min(k0 + j * GEMM_KS, klast), &ring[j]);
 #pragma unroll
   for (int p = 0; p < PD; ++p) {
-    if (p % GEMM_KS == 0) stage_copy(k0, st0);
+    if (p % GEMM_KS == 0) stage_copy(min(k0 + (LA - 1) * GEMM_KS, klast), &ring[LA - 1]);
 #pragma unroll
     for (int s = 0; s < SP; ++s) {
       aop[p][s] = u32x4_t{0, 0, 0, 0};
@@ -181,12 +195,14 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
   }
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
 
-  // One stage: GEMM_KS k-steps out of `cur` while the next stage is copied into `nxt`; J is the
-  // position of the stage's first k-step in the unrolled body (ring slots are static).
-  auto stage_body = [&](int t0, auto jtag, GemmStage<NCT, TERMS> *cur, GemmStage<NCT, TERMS> *nxt) {
+  // One stage: GEMM_KS k-steps out of ring slot `cur` while the stage LA stages ahead is copied
+  // into the slot that the previous stage has just left; J is the position of the stage's first
+  // k-step in the unrolled body (ring slots are static).
+  auto stage_body = [&](int t0, auto jtag) {
     constexpr int J = decltype(jtag)::value;
-    // next stage (clamped at the end: copied again, never used)
-    stage_copy(min(k0 + t0 + GEMM_KS, k0 + nkp - GEMM_KS), nxt);
+    GemmStage<NCT, TERMS> *cur = &ring[(J / GEMM_KS) % NS];
+    // (clamped at the end: the last stage is copied again, into a slot that is not read any more)
+    stage_copy(min(k0 + t0 + LA * GEMM_KS, klast), &ring[(J / GEMM_KS + LA) % NS]);
 #pragma unroll
     for (int u = 0; u < GEMM_KS; ++u) {
       const int slot = (J + u) % PD;
@@ -227,17 +243,20 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
       // products would need more registers than a wavefront has
       __builtin_amdgcn_sched_barrier(0);
     }
-    // outstanding, oldest first: ..., this stage's copies (TPW), then its GEMM_KS * SP refills:
-    // once at most that many remain, this wavefront's part of the next stage is in LDS and
-    // the barrier publishes it; the weight prefetch stays in flight
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
+    // The next stage was copied LA stage starts ago.  Issued since then, oldest first: the
+    // refills of LA stages (GEMM_KS * SP each) and the copies of the LA - 1 later stage starts
+    // (TPW each): once at most that many loads remain, this wavefront's part of the next stage
+    // is in LDS and the barrier publishes it; the weight prefetch and the copies of the stages
+    // after it stay in flight
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LA * GEMM_KS * SP + (LA - 1) * TPW)
+                 : "memory");
   };
   for (int t0 = 0; t0 < nkp; t0 += UNR) {
-    stage_body(t0, std::integral_constant<int, 0>{}, st0, st1);
-    if (t0 + 2 < nkp) stage_body(t0 + 2, std::integral_constant<int, 2>{}, st1, st0);
+    stage_body(t0, std::integral_constant<int, 0>{});
+    if (t0 + 2 < nkp) stage_body(t0 + 2, std::integral_constant<int, 2>{});
     if constexpr (UNR == 8) {
-      if (t0 + 4 < nkp) stage_body(t0 + 4, std::integral_constant<int, 4>{}, st0, st1);
-      if (t0 + 6 < nkp) stage_body(t0 + 6, std::integral_constant<int, 6>{}, st1, st0);
+      if (t0 + 4 < nkp) stage_body(t0 + 4, std::integral_constant<int, 4>{});
+      if (t0 + 6 < nkp) stage_body(t0 + 6, std::integral_constant<int, 6>{});
     }
   }
   // the clamped refills and the last stage copy are still in flight: let them land before the
@@ -290,7 +309,7 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
 
 template <int NCT, int EPI, int TERMS>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
-  __shared__ GemmStage<NCT, TERMS> stage0, stage1;
+  __shared__ GemmStage<NCT, TERMS> ring[gemm_stages<TERMS>()];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int gc_count = a.ngroups * a.nchunks;
   for (int unit = blockIdx.x; unit < a.units; unit += gridDim.x) {
@@ -312,9 +331,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int per = (P + GEMM_WAVES - 1) / GEMM_WAVES;          // strips per wavefront
       const int sfirst = min(base + wave * per, g1 - 1);
       const int ns = max(0, min(per, P - wave * per));
-      if (per > 2) gemm_pass<NCT, 4, EPI, TERMS>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
-      else if (per == 2) gemm_pass<NCT, 2, EPI, TERMS>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
-      else gemm_pass<NCT, 1, EPI, TERMS>(a, &stage0, &stage1, rb, chunk, k0, nk, sfirst, ns, wave);
+      if (per > 2) gemm_pass<NCT, 4, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
+      else if (per == 2) gemm_pass<NCT, 2, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
+      else gemm_pass<NCT, 1, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
     }
   }
 }
