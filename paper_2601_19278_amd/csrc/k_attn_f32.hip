@@ -58,64 +58,82 @@ __global__ __launch_bounds__(64) void attn_split_f32_kernel(
 // out[qv][:] = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s over the partials of the query's
 // (sequence, K/V head) pair: one per workgroup run that holds units of the pair (AttnWork) and
 // sub-range, out of the nsplit slots of the query vector.  A partial with l == 0 saw no visible
-// key.  One workgroup per query vector, one thread per output dim; the weights are computed
-// once in parallel and kept in LDS, and the partial rows are then read with independent loads.
+// key.  One wavefront per query vector (a lane holds output dims l and l + 64), no workgroup
+// barrier: the weights are computed once across the lanes and kept in LDS, the reductions run
+// on the DPP path, and the partial rows are then read with independent loads.
 constexpr int ATTN_MAX_SPLITS = 1024;   // 256 key chunks x 4 sub-ranges
 
 // pack != null: the result goes to the packed operand tiles of the multi-row O projection
 // (row = query row, input = head * hd + dim; ntiles row tiles) instead of out.
-__global__ __launch_bounds__(128) void attn_merge_kernel(SeqBatch sb, AttnWork work, int Hq, int group,
-                                                         int nsub,
-                                                         const float *__restrict__ o_part,
-                                                         const float *__restrict__ ml_part,
-                                                         int nsplit, int hd,
-                                                         float *__restrict__ out,
-                                                         uint4 *__restrict__ pack, int ntiles,
-                                                         int terms) {
-  __shared__ float red[16];
-  __shared__ float w[ATTN_MAX_SPLITS];
-  __shared__ __align__(16) float row_out[128];
-  const int qv = blockIdx.x, t = threadIdx.x;
+constexpr int MERGE_VECS = 4;           // query vectors per workgroup, one wavefront each
+__global__ __launch_bounds__(64 * MERGE_VECS) void attn_merge_kernel(
+    SeqBatch sb, AttnWork work, int Hq, int group, int nsub, const float *__restrict__ o_part,
+    const float *__restrict__ ml_part, int nsplit, int hd, int n_vecs, float *__restrict__ out,
+    uint4 *__restrict__ pack, int ntiles, int terms) {
+  __shared__ float w_all[MERGE_VECS][ATTN_MAX_SPLITS];
+  __shared__ __align__(16) float row_all[MERGE_VECS][128];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int qv = blockIdx.x * MERGE_VECS + wave;
+  if (qv >= n_vecs) return;                       // wave-uniform; no workgroup barrier below
+  float *w = w_all[wave], *row_out = row_all[wave];
   const int b = qv / (Hq * sb.K), g = qv % Hq / group;
   const int cb = work.cum[b + 1] - work.cum[b];
   const int pair0 = work.cum[b] * (Hq / group) + g * cb;        // first unit of the pair
   const int used = ((pair0 + cb - 1) / work.per - pair0 / work.per + 1) * nsub;
+  const float2 *ml2 = reinterpret_cast<const float2 *>(ml_part) + (size_t)qv * nsplit;
+  // weights of the partials: exp(m_s - max m) over the partials that saw a key (l_s > 0)
   float mx = -3.0e38f;
-  for (int s = t; s < used; s += blockDim.x) {
-    const size_t slot = (size_t)qv * nsplit + s;
-    if (ml_part[slot * 2 + 1] > 0.f) mx = fmaxf(mx, ml_part[slot * 2]);
+  for (int s = lane; s < used; s += 64) {
+    const float2 ml = ml2[s];
+    if (ml.y > 0.f) mx = fmaxf(mx, ml.x);
   }
-  mx = block_max(mx, red);
+  mx = wave_max(mx);
   float den = 0.f;
-  for (int s = t; s < used; s += blockDim.x) {
-    const size_t slot = (size_t)qv * nsplit + s;
-    const float l = ml_part[slot * 2 + 1];
-    const float ws = l > 0.f ? expf(ml_part[slot * 2] - mx) : 0.f;
+  for (int s = lane; s < used; s += 64) {
+    const float2 ml = ml2[s];
+    const float ws = ml.y > 0.f ? expf(ml.x - mx) : 0.f;
     w[s] = ws;
-    den += ws * l;
+    den += ws * ml.y;
   }
-  den = block_sum(den, red);          // its barriers also publish w[]
-  const float *src = o_part + (size_t)qv * nsplit * hd + min(t, hd - 1);
-  float num = 0.f;
+  den = wave_sum(den);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  // lane l adds up elements l and l + 64 of the partial outputs, in index order (deterministic)
+  const int t0 = min(lane, hd - 1), t1 = min(lane + 64, hd - 1);
+  const float *src = o_part + (size_t)qv * nsplit * hd;
+  float n0 = 0.f, n1 = 0.f;
   int s = 0;
   for (; s + 4 <= used; s += 4) {
-    const float a0 = src[(size_t)s * hd], a1 = src[(size_t)(s + 1) * hd];
-    const float a2 = src[(size_t)(s + 2) * hd], a3 = src[(size_t)(s + 3) * hd];
-    num += w[s] * a0;                 // fixed order: deterministic
-    num += w[s + 1] * a1;
-    num += w[s + 2] * a2;
-    num += w[s + 3] * a3;
+    float a[4], c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[i] = src[(size_t)(s + i) * hd + t0];
+      c[i] = src[(size_t)(s + i) * hd + t1];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      n0 += w[s + i] * a[i];
+      n1 += w[s + i] * c[i];
+    }
   }
-  for (; s < used; ++s) num += w[s] * src[(size_t)s * hd];
+  for (; s < used; ++s) {
+    n0 += w[s] * src[(size_t)s * hd + t0];
+    n1 += w[s] * src[(size_t)s * hd + t1];
+  }
   if (!pack) {
-    if (t < hd) out[(size_t)qv * hd + t] = num / den;
+    if (lane < hd) out[(size_t)qv * hd + lane] = n0 / den;
+    if (lane + 64 < hd) out[(size_t)qv * hd + lane + 64] = n1 / den;
     return;
   }
-  row_out[t] = num / den;
-  __syncthreads();
-  if (t < hd / 8) {
+  if (lane < hd) row_out[lane] = n0 / den;
+  if (lane + 64 < hd) row_out[lane + 64] = n1 / den;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  if (lane < hd / 8) {
     const int row = qv / Hq, h = qv % Hq;
-    pack_store8(pack, ntiles, terms, row, h * hd + 8 * t, &row_out[8 * t]);
+    pack_store8(pack, ntiles, terms, row, h * hd + 8 * lane, &row_out[8 * lane]);
   }
 }
 
@@ -182,8 +200,9 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, i
     gemm_bf16_pack_shape(sb.B * sb.K, Hq * hd, &ntiles, &ksteps);
     if (ksteps * 32 != Hq * hd) return hipErrorInvalidValue;
   }
-  hipLaunchKernelGGL(attn_merge_kernel, dim3(QVT), dim3(hd), 0, st, sb, work, Hq, Hq / Hkv, nsub,
-                     c->att_part, c->att_ml, nseg * nsub, hd, c->att_out, (uint4 *)pack, ntiles, terms);
+  hipLaunchKernelGGL(attn_merge_kernel, dim3((QVT + MERGE_VECS - 1) / MERGE_VECS), dim3(64 * MERGE_VECS),
+                     0, st, sb, work, Hq, Hq / Hkv, nsub, c->att_part, c->att_ml, nseg * nsub, hd, QVT,
+                     c->att_out, (uint4 *)pack, ntiles, terms);
   return hipGetLastError();
 }
 
