@@ -222,13 +222,10 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   // one pass carries the query rows of up to DART_SEQ_GROUP sequences
   c->ws_rows = std::max(R, std::min(g.max_batch, DART_SEQ_GROUP) * g.max_K);
   const size_t W = c->ws_rows;
-  // attention partials: per query vector, one per 128-key split and key sub-range; fewer query
-  // rows per sequence mean more sub-ranges, so size for the worst draft length
+  // attention partials: per query vector, at most one per 128-key split (the key sub-ranges of
+  // a split are merged inside the attention kernel)
   c->max_splits = c->t_cap / ATTN_KEY_CHUNK;
-  int att_rows = g.max_K;
-  if (g.dtype == DART_BF16)
-    for (int k = 1; k <= g.max_K; ++k)
-      att_rows = std::max(att_rows, k * attn_mfma_nsub(k, g.n_q_heads / g.n_kv_heads));
+  const int att_rows = g.max_K;
   const size_t att_slots = (size_t)std::min(g.max_batch, DART_SEQ_GROUP) * att_rows * g.n_q_heads *
                            c->max_splits;
   const size_t proj_elems = std::max(std::max((size_t)ch_o * d, (size_t)ch_down * d),

@@ -206,7 +206,6 @@ hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const flo
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                             hipStream_t st);
-int attn_mfma_nsub(int Kq, int group);        // key sub-ranges per split of the MFMA attention
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
 int gemv_bf16_split(int Kd, int nstrips);     // k-chunks that balance the workgroups (>= gemv_bf16_chunks)
 int gemv_bf16_row_tiles(int Kd, int nch);     // 16-row tiles one launch may carry per row block

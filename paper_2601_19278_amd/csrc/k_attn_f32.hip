@@ -139,7 +139,6 @@ __global__ __launch_bounds__(64 * MERGE_VECS) void attn_merge_kernel(
 
 hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, const AttnWork &work,
                                  int nseg, hipStream_t st);
-int attn_mfma_nsub(int Kq, int group);
 
 // Chunk units per attention workgroup of the bf16 path; 0 = chosen from the amount of work.
 int g_attn_seg = 0;
@@ -174,7 +173,7 @@ hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, i
     const int resident = hd == 128 ? 256 : 512;
     work.per = g_attn_seg > 0 ? g_attn_seg : max(1, (units + resident - 1) / resident);
     nseg = (cb_max + work.per - 2) / work.per + 1;        // most runs a pair can touch
-    nsub = attn_mfma_nsub(sb.K, Hq / Hkv);
+    nsub = 1;                                             // sub-ranges are merged in the kernel
     hipError_t e = launch_attention_bf16(c, sb, work, nseg, st);
     if (e != hipSuccess) return e;
   } else {

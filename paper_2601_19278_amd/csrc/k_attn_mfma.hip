@@ -242,14 +242,50 @@ __global__ __launch_bounds__(64 * NW) void attn_split_mfma_kernel(
       }
     }
     if (chunk == cb - 1 || u + 1 == u1) {
-      // the pair ends here, or the run does: one partial, numbered by the run within the pair
-      if (active) {
+      // The pair ends here, or the run does: one partial per query column, numbered by the run
+      // within the pair.  The NSUB wavefronts that hold the key sub-ranges of a query tile
+      // first merge their (max, sum, output) through the chunk buffer that has just been
+      // consumed (the next unit's copies go to the other one): half or a quarter of the bytes
+      // to store here and to read back in the merge kernel.  The condition is uniform over the
+      // workgroup, so the barriers are too; they order LDS traffic only.
+      if constexpr (NSUB > 1) {
+        constexpr int F = 4 * DT + 2;                              // floats per lane
+        static_assert(MTW == 1 && (NSUB - 1) * TW * F * 256 <= (NK + NV) * 1024, "fits one chunk buffer");
+        float *xb = reinterpret_cast<float *>(attn_lds + (size_t)((u - u0) & 1) * (NK + NV) * 64);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // everyone is done with the chunk
+        if (active && sub > 0) {
+          float *dst = xb + (size_t)((sub - 1) * TW + a0) * F * 64 + lane;
+#pragma unroll
+          for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[(4 * t + r) * 64] = acc[0][t][r];
+          dst[(4 * DT) * 64] = m[0];
+          dst[(4 * DT + 1) * 64] = l[0];
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (active && sub == 0) {
+#pragma unroll
+          for (int s2 = 1; s2 < NSUB; ++s2) {
+            const float *src = xb + (size_t)((s2 - 1) * TW + a0) * F * 64 + lane;
+            const float m2 = src[(4 * DT) * 64], l2 = src[(4 * DT + 1) * 64];
+            const float mn = fmaxf(m[0], m2);
+            const float c0 = __expf(m[0] - mn), c1 = __expf(m2 - mn);
+            l[0] = l[0] * c0 + l2 * c1;
+            m[0] = mn;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) acc[0][t][r] = acc[0][t][r] * c0 + src[(4 * t + r) * 64] * c1;
+          }
+        }
+      }
+      if (active && sub == 0) {
         const int pair0 = work.cum[b] * Hkv + g * cb;      // first unit of the pair
         const int seg = (int)blockIdx.x - pair0 / work.per;
 #pragma unroll
         for (int a = 0; a < MTW; ++a) {
           if (qrow[a] < 0) continue;
-          const size_t slot = qslot[a] * nsplit_total + (size_t)seg * NSUB + sub;
+          const size_t slot = qslot[a] * nsplit_total + (size_t)seg;
 #pragma unroll
           for (int t = 0; t < DT; ++t)
             *reinterpret_cast<float4 *>(o_part + slot * HD + 16 * t + 4 * gq) =
@@ -264,12 +300,6 @@ __global__ __launch_bounds__(64 * NW) void attn_split_mfma_kernel(
     }
     b = nb, g = ng, chunk = nchunk, cb = ncb;
   }
-}
-
-// Key sub-ranges per chunk for a given number of query tiles (see the kernel).
-int attn_mfma_nsub(int Kq, int group) {
-  const int tiles = (Kq * group + 15) / 16;
-  return tiles == 1 ? 4 : (tiles <= 4 ? 2 : 1);
 }
 
 template <int HD, int NW, int TW>
@@ -292,11 +322,11 @@ static hipError_t launch_one(const dart_ctx *c, const SeqBatch &sb, const AttnWo
   hipLaunchKernelGGL(kern, dim3((units + work.per - 1) / work.per), dim3(64 * NW), lds, st, sb, work,
                      (const f16_t *)c->qrot, (const f16_t *)c->kbuf, (const f16_t *)c->vbuf,
                      slot_elems, c->t_cap, tiles, g.n_q_heads, g.n_q_heads / g.n_kv_heads,
-                     1.0f / sqrtf((float)HD), nseg * (NW / TW), c->att_part, c->att_ml);
+                     1.0f / sqrtf((float)HD), nseg, c->att_part, c->att_ml);
   return hipGetLastError();
 }
 
-// work: the launch's unit list; nseg: partial slots per query vector and sub-range.
+// work: the launch's unit list; nseg: partial slots per query vector.
 hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, const AttnWork &work,
                                  int nseg, hipStream_t st) {
   const dart_config &g = c->cfg;
