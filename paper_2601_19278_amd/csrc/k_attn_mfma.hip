@@ -250,24 +250,25 @@ __global__ __launch_bounds__(64 * NW) void attn_split_mfma_kernel(
       // workgroup, so the barriers are too; they order LDS traffic only.
       if constexpr (NSUB > 1) {
         constexpr int F = 4 * DT + 2;                              // floats per lane
-        static_assert(MTW == 1 && (NSUB - 1) * TW * F * 256 <= (NK + NV) * 1024, "fits one chunk buffer");
-        float *xb = reinterpret_cast<float *>(attn_lds + (size_t)((u - u0) & 1) * (NK + NV) * 64);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // everyone is done with the chunk
-        if (active && sub > 0) {
-          float *dst = xb + (size_t)((sub - 1) * TW + a0) * F * 64 + lane;
+        static_assert(MTW == 1 && TW * F * 256 <= (NK + NV) * 1024, "fits one chunk buffer");
+        float *xb = reinterpret_cast<float *>(attn_lds + (size_t)((u - u0) & 1) * (NK + NV) * 64) +
+                    (size_t)a0 * F * 64 + lane;
+        // one sub-range at a time hands its state to the wavefront of sub-range 0
 #pragma unroll
-          for (int t = 0; t < DT; ++t)
+        for (int s2 = 1; s2 < NSUB; ++s2) {
+          // everyone is done with the chunk (first round) / the previous hand-over has been read
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          if (active && sub == s2) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) dst[(4 * t + r) * 64] = acc[0][t][r];
-          dst[(4 * DT) * 64] = m[0];
-          dst[(4 * DT + 1) * 64] = l[0];
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (active && sub == 0) {
+            for (int t = 0; t < DT; ++t)
 #pragma unroll
-          for (int s2 = 1; s2 < NSUB; ++s2) {
-            const float *src = xb + (size_t)((s2 - 1) * TW + a0) * F * 64 + lane;
-            const float m2 = src[(4 * DT) * 64], l2 = src[(4 * DT + 1) * 64];
+              for (int r = 0; r < 4; ++r) xb[(4 * t + r) * 64] = acc[0][t][r];
+            xb[(4 * DT) * 64] = m[0];
+            xb[(4 * DT + 1) * 64] = l[0];
+          }
+          asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          if (active && sub == 0) {
+            const float m2 = xb[(4 * DT) * 64], l2 = xb[(4 * DT + 1) * 64];
             const float mn = fmaxf(m[0], m2);
             const float c0 = __expf(m[0] - mn), c1 = __expf(m2 - mn);
             l[0] = l[0] * c0 + l2 * c1;
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(64 * NW) void attn_split_mfma_kernel(
 #pragma unroll
             for (int t = 0; t < DT; ++t)
 #pragma unroll
-              for (int r = 0; r < 4; ++r) acc[0][t][r] = acc[0][t][r] * c0 + src[(4 * t + r) * 64] * c1;
+              for (int r = 0; r < 4; ++r) acc[0][t][r] = acc[0][t][r] * c0 + xb[(4 * t + r) * 64] * c1;
           }
         }
       }
