@@ -260,7 +260,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   HIP_TRY(dev_alloc(&c->kv_part, (size_t)ch_qkv * c->kv_rows * 2 * c->kv_dim));
 
   c->max_rows = g.max_batch * g.max_K;
-  c->topk_chunks_max = (g.vocab + 4095) / 4096;
+  c->topk_chunks_max = topk_chunks(g.vocab);
   HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
   HIP_TRY(dev_alloc(&c->topk_ms, (size_t)c->max_rows * c->topk_chunks_max * 2));
   return hipSuccess;

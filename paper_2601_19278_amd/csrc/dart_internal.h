@@ -238,6 +238,7 @@ hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *q
 // Attention of the B*K query rows of the pass (compact order) over their sequences' K/V.
 hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, int terms, hipStream_t st);
 
+int topk_chunks(int vocab);                   // vocabulary chunks of the top-k kernels
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st);
 

@@ -267,6 +267,8 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(int k, int nchunks, floa
   merge_row(blockIdx.x, k, nchunks, eps, cand, ms, buf, ids, scores);
 }
 
+int topk_chunks(int vocab) { return (vocab + TOPK_CHUNK - 1) / TOPK_CHUNK; }
+
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st) {
   const int nchunks = (vocab + TOPK_CHUNK - 1) / TOPK_CHUNK;
