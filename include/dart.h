@@ -250,8 +250,9 @@ dart_status dart_tree_verify_greedy(int batch, const int32_t *tokens, const int3
 /* Diagnostic (tests only): copy a named fp32 workspace of the last forward call to host
  * memory after synchronising the device.  Names: "xn" (normed layer input), "resid", "qkv",
  * "att_out" (attention output), "y" (after attention residual), "yn", "hmid" (SwiGLU
- * product), "u" (after MLP residual).  Buffers hold 16 rows.  Returns the number of floats
- * copied (at most max_count) or -1 on error. */
+ * product), "u" (after MLP residual).  Buffers hold 16 rows and are those of the single-sequence
+ * calls: the batched calls hand most of these rows on as packed operand tiles and do not store
+ * them.  Returns the number of floats copied (at most max_count) or -1 on error. */
 int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_t max_count);
 
 /* Diagnostic (benchmark only): enqueue only the LM-head projection (the final step of

@@ -413,7 +413,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
                   gemm ? c->gch_o : 0, &chunks, st));
   // on the multi-row path the norm kernels write the next projection's operand tiles themselves
   HIP_TRY(launch_resid_norm(g.dtype, c->resid, c->proj, chunks, cs, g.d, c->g_post, QR, g.d,
-                            g.rms_eps, c->y, c->yn, gemm ? c->xpack : nullptr,
+                            g.rms_eps, c->y, gemm ? nullptr : c->yn, gemm ? c->xpack : nullptr,
                             gemm_bf16_terms(c->wgu), st));
   const float *yn_in = gemm ? nullptr : c->yn;
   cs = W * 2 * g.ffn;
@@ -440,7 +440,8 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
                     gemm ? c->gch_down : 0, &chunks, st));
   }
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
-                            c->u, c->yn, gemm ? c->xpack : nullptr, gemm_bf16_terms(c->wlm), st));
+                            gemm ? nullptr : c->u, gemm ? nullptr : c->yn, gemm ? c->xpack : nullptr,
+                            gemm_bf16_terms(c->wlm), st));
   HIP_TRY(project(c, c->wlm, 0, g.vocab, yn_in, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
   return hipSuccess;
 }

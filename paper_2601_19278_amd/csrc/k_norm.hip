@@ -171,6 +171,7 @@ __global__ __launch_bounds__(ROW_THREADS) void front_norm_kernel(
 
 // y = resid + sum_c part[c];  yn = RMSNorm(y) * gain.  part[c] row r starts at
 // part + c*chunk_stride + r*row_stride.  Chunk partials are added in index order.
+// y, yn: either may be null (not stored).
 // pack != null: yn is also written as the packed operand tiles of the multi-row projection
 // that consumes it (ntiles row tiles, ksteps k-steps); the grid then covers the padded rows
 // ntiles*16, and rows >= rows and inputs >= d are written as zeros.
@@ -237,10 +238,10 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_norm_kernel(
   for (int j = 0; j < NJ; ++j) {
     const int c = (j * ROW_THREADS + threadIdx.x) * 8;
     if (c < d) {
-      store8(y + (size_t)r * d + c, v[j]);
+      if (y) store8(y + (size_t)r * d + c, v[j]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[j][e] = v[j][e] * rstd * g[j][e];
-      store8(yn + (size_t)r * d + c, v[j]);
+      if (yn) store8(yn + (size_t)r * d + c, v[j]);
       if (pack) pack_store8(pack, ntiles, terms, r, c, v[j]);
     }
   }
