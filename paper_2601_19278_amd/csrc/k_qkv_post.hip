@@ -7,86 +7,109 @@
 
 namespace dart {
 
-// grid (pass rows, ceil((Hq + 2*Hkv) / 4)), block = 4 wavefronts, one head each.  Lane l < hd/2
-// holds elements l and l + hd/2 of its head, the two a rotary rotation mixes, so a head needs no
-// LDS and no barrier; the head's sum of squares is a wavefront reduction.
+// grid (pass rows, ceil((Hq + 2*Hkv) / 8)), block = 4 wavefronts, two heads each.  Lane l < hd/2
+// holds elements l and l + hd/2 of a head, the two a rotary rotation mixes, so a head needs no
+// LDS and no barrier; the head's sum of squares is a wavefront reduction.  The chunk partials
+// of both heads are requested before either is used.
 // Pass row i is position pos of sequence b (SeqBatch); q is produced for query rows only and
 // stored at the compact index b*K + j; k and v of every row go to the sequence's K/V slot.
 // T: storage type of the norm gains; CT: element type of q and of the K/V buffers.
-constexpr int QKV_POST_HEADS = 4;
+constexpr int QKV_POST_WAVES = 4, QKV_POST_HPW = 2;
+static_assert(QKV_POST_HPW == 2, "the early exit below names both heads");
 template <typename T, typename CT>
-__global__ __launch_bounds__(64 * QKV_POST_HEADS) void qkv_post_kernel(
+__global__ __launch_bounds__(64 * QKV_POST_WAVES) void qkv_post_kernel(
     SeqBatch sb, const float *__restrict__ qkv, int chunks, size_t chunk_stride, int row_stride,
     int col0, int Hq, int Hkv, int hd, int qk_norm, float eps, const T *__restrict__ q_gain,
     const T *__restrict__ k_gain, const float *__restrict__ cos_tab,
     const float *__restrict__ sin_tab, CT *__restrict__ q_out, CT *__restrict__ kbuf,
     CT *__restrict__ vbuf, size_t slot_elems, int t_cap, int tiled) {
-  const int i = blockIdx.x, hh = blockIdx.y * QKV_POST_HEADS + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63, half = hd >> 1;
-  if (hh >= Hq + 2 * Hkv) return;                 // uniform per wavefront, like the exits below
+  const int i = blockIdx.x;
+  const int h0 = (blockIdx.y * QKV_POST_WAVES + (threadIdx.x >> 6)) * QKV_POST_HPW;
+  const int lane = threadIdx.x & 63, half = hd >> 1, heads = Hq + 2 * Hkv;
+  if (h0 >= heads) return;                        // uniform per wavefront, like the skips below
   int b, pos, qi;
   seq_of_row(sb, i, b, pos, qi);
-  const bool is_q = hh < Hq, is_k = !is_q && hh < Hq + Hkv;
-  if (is_q && qi < 0) return;                     // non-query rows need no q
   const bool act = lane < half;
   kbuf += (size_t)sb.slot[b] * slot_elems;
   vbuf += (size_t)sb.slot[b] * slot_elems;
-  const int t0 = lane, t1 = lane + half;          // the lane's two elements of the head
-  // chunk partials: up to 8 chunks in flight, added in index order
-  float x0 = 0.f, x1 = 0.f;
-  const float *src = qkv + (size_t)i * row_stride + (hh * hd - col0);   // q, then k, then v heads
+  const int t0 = lane, t1 = lane + half;          // the lane's two elements of a head
+  // chunk partials: up to 8 chunks in flight per head, added in index order
+  float x0[QKV_POST_HPW], x1[QKV_POST_HPW];
+  bool live[QKV_POST_HPW];
+#pragma unroll
+  for (int j = 0; j < QKV_POST_HPW; ++j) {
+    const int hh = h0 + j;
+    // heads past the end, and q heads of rows that are not query rows, are skipped
+    live[j] = hh < heads && !(hh < Hq && qi < 0);
+    x0[j] = x1[j] = 0.f;
+  }
+  if (!live[0] && !live[QKV_POST_HPW - 1]) return;   // (two heads per wavefront)
   for (int c0 = 0; c0 < chunks; c0 += 8) {
-    float p0[8], p1[8];
+    float p0[QKV_POST_HPW][8], p1[QKV_POST_HPW][8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const bool in = act && c0 + u < chunks;
-      p0[u] = in ? src[(size_t)(c0 + u) * chunk_stride + t0] : 0.f;
-      p1[u] = in ? src[(size_t)(c0 + u) * chunk_stride + t1] : 0.f;
-    }
+    for (int j = 0; j < QKV_POST_HPW; ++j) {
+      const float *src = qkv + (size_t)i * row_stride + ((h0 + j) * hd - col0);   // q, then k, then v heads
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (c0 + u < chunks) {
-        x0 += p0[u];
-        x1 += p1[u];
+      for (int u = 0; u < 8; ++u) {
+        const bool in = live[j] && act && c0 + u < chunks;
+        p0[j][u] = in ? src[(size_t)(c0 + u) * chunk_stride + t0] : 0.f;
+        p1[j][u] = in ? src[(size_t)(c0 + u) * chunk_stride + t1] : 0.f;
       }
+    }
+#pragma unroll
+    for (int j = 0; j < QKV_POST_HPW; ++j)
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (c0 + u < chunks) {
+          x0[j] += p0[j][u];
+          x1[j] += p1[j][u];
+        }
   }
+  const float c = act ? cos_tab[(size_t)pos * half + lane] : 0.f, s = act ? sin_tab[(size_t)pos * half + lane] : 0.f;
 
-  if (!is_q && !is_k) {                           // value head: store as is
-    const int g = hh - Hq - Hkv;
-    if (!act) return;
-    if (tiled) {
-      vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t0, hd)] = from_f32<CT>(x0);
-      vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t1, hd)] = from_f32<CT>(x1);
-    } else {
-      vbuf[((size_t)g * t_cap + pos) * hd + t0] = from_f32<CT>(x0);
-      vbuf[((size_t)g * t_cap + pos) * hd + t1] = from_f32<CT>(x1);
+#pragma unroll
+  for (int j = 0; j < QKV_POST_HPW; ++j) {
+    if (!live[j]) continue;
+    const int hh = h0 + j;
+    const bool is_q = hh < Hq, is_k = !is_q && hh < Hq + Hkv;
+    float a0 = x0[j], a1 = x1[j];
+    if (!is_q && !is_k) {                         // value head: store as is
+      const int g = hh - Hq - Hkv;
+      if (act) {
+        if (tiled) {
+          vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t0, hd)] = from_f32<CT>(a0);
+          vbuf[(size_t)g * hd * t_cap + attn_vt_index(pos, t1, hd)] = from_f32<CT>(a1);
+        } else {
+          vbuf[((size_t)g * t_cap + pos) * hd + t0] = from_f32<CT>(a0);
+          vbuf[((size_t)g * t_cap + pos) * hd + t1] = from_f32<CT>(a1);
+        }
+      }
+      continue;
     }
-    return;
-  }
-  if (qk_norm) {
-    const float ss = wave_sum_dpp(act ? x0 * x0 + x1 * x1 : 0.f);
-    const float rinv = 1.0f / sqrtf(ss / (float)hd + eps);
-    const T *gain = is_q ? q_gain : k_gain;
-    if (act) {
-      x0 = x0 * rinv * to_f32(gain[t0]);
-      x1 = x1 * rinv * to_f32(gain[t1]);
+    if (qk_norm) {
+      const float ss = wave_sum_dpp(act ? a0 * a0 + a1 * a1 : 0.f);
+      const float rinv = 1.0f / sqrtf(ss / (float)hd + eps);
+      const T *gain = is_q ? q_gain : k_gain;
+      if (act) {
+        a0 = a0 * rinv * to_f32(gain[t0]);
+        a1 = a1 * rinv * to_f32(gain[t1]);
+      }
     }
-  }
-  if (!act) return;
-  const float c = cos_tab[(size_t)pos * half + lane], s = sin_tab[(size_t)pos * half + lane];
-  const float y0 = x0 * c - x1 * s, y1 = x1 * c + x0 * s;
-  if (is_q) {
-    CT *dst = q_out + ((size_t)(b * sb.K + qi) * Hq + hh) * hd;
-    dst[t0] = from_f32<CT>(y0);
-    dst[t1] = from_f32<CT>(y1);
-  } else {
-    const int g = hh - Hq;
-    if (tiled) {
-      kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t0, hd)] = from_f32<CT>(y0);
-      kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t1, hd)] = from_f32<CT>(y1);
+    if (!act) continue;
+    const float y0 = a0 * c - a1 * s, y1 = a1 * c + a0 * s;
+    if (is_q) {
+      CT *dst = q_out + ((size_t)(b * sb.K + qi) * Hq + hh) * hd;
+      dst[t0] = from_f32<CT>(y0);
+      dst[t1] = from_f32<CT>(y1);
     } else {
-      kbuf[((size_t)g * t_cap + pos) * hd + t0] = from_f32<CT>(y0);
-      kbuf[((size_t)g * t_cap + pos) * hd + t1] = from_f32<CT>(y1);
+      const int g = hh - Hq;
+      if (tiled) {
+        kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t0, hd)] = from_f32<CT>(y0);
+        kbuf[(size_t)g * hd * t_cap + attn_k_index(pos, t1, hd)] = from_f32<CT>(y1);
+      } else {
+        kbuf[((size_t)g * t_cap + pos) * hd + t0] = from_f32<CT>(y0);
+        kbuf[((size_t)g * t_cap + pos) * hd + t1] = from_f32<CT>(y1);
+      }
     }
   }
 }
@@ -97,7 +120,8 @@ hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *q
   const int Hq = g.n_q_heads, Hkv = g.n_kv_heads, hd = g.head_dim;
   const size_t slot_elems = (size_t)Hkv * c->t_cap * hd;
   if (hd > 128 || (hd & 1)) return hipErrorInvalidValue;
-  dim3 grid(sb.row_off[sb.B], (Hq + 2 * Hkv + QKV_POST_HEADS - 1) / QKV_POST_HEADS), block(64 * QKV_POST_HEADS);
+  constexpr int per_block = QKV_POST_WAVES * QKV_POST_HPW;
+  dim3 grid(sb.row_off[sb.B], (Hq + 2 * Hkv + per_block - 1) / per_block), block(64 * QKV_POST_WAVES);
   if (g.dtype == DART_BF16) {
     hipLaunchKernelGGL((qkv_post_kernel<bf16_t, f16_t>), grid, block, 0, st, sb, qkv, chunks,
                        chunk_stride, row_stride, col0, Hq, Hkv, hd, g.qk_norm, g.rms_eps,
