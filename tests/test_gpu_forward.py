@@ -135,6 +135,10 @@ def test_batched_ragged_sequences():
     (2, 3, dict(d=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1024, vocab=40000, ctx=70,
                 qk_norm=False)),
     (20, 2, dict(d=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=512, vocab=2048, ctx=40)),
+    # long ragged contexts with one and two query tiles: several chunk units per attention
+    # workgroup, pairs that end inside a run, four and two key sub-ranges merged in the workgroup
+    (16, 4, dict(d=256, n_q_heads=2, n_kv_heads=2, head_dim=128, ffn=512, vocab=1024, ctx=2300)),
+    (12, 8, dict(d=256, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=512, vocab=1024, ctx=3000)),
 ])
 def test_batched_multi_row_kernel_matches_oracle_cold_and_warm(batch, K, over):
     """The batched entry point runs every projection on the multi-row MFMA kernel: 48 and 128
