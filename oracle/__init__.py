@@ -12,8 +12,10 @@ they meet only at the seeded input generators.
 
 Parity status: every function here is pinned by CPU tests to something other
 than itself (library routines on special cases, closed forms, brute force on
-tiny inputs, a hand-derived worked example).  The one exception is the beam cut
-of Alg. 1 at finite beam width, which is a heuristic defined only by its steps:
-`tree_prune` with finite `beam_w` is pinned through invariants and through the
-cases where the beam never cuts, and is otherwise "parity unpinned".
+tiny inputs, a hand-derived worked example).  The beam cut of Alg. 1 at finite
+beam width is a heuristic defined only by its steps; `tree_prune` with finite
+`beam_w` is pinned by brute force on tiny inputs (every path of the full tree
+scored by the enumerator, Alg. 1 then read as sets: children of the previous
+beam, all into T, the w best kept), by the hand-derived tie-break example and by
+invariants.  At sizes where all paths cannot be enumerated it has no other pin.
 """

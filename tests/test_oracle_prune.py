@@ -171,6 +171,30 @@ def test_wide_beam_equals_best_first_search(seed):
     assert sorted(otp.tree_paths(tree)) == sorted(popped)
 
 
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("w", [1, 2, 4, 7])
+def test_finite_beam_equals_its_set_definition_over_all_paths(seed, w):
+    """Brute force for a beam that does cut: score every path of the full k-ary tree (the
+    enumerator, itself pinned by the best-first search), then read Alg. 1 as sets -- the
+    expansions of a level are the children of the previous level's beam, all of them enter T,
+    the beam is the w best of them, and the tree is the theta best of T."""
+    K, k = 4, 3
+    pc, ng = _case(200 + seed, K=K, k=k)
+    wide = PruneParams(k=k, beam_w=k ** (K - 1), budget=2)
+    every = otp.enumerate_tree(pc.ids, pc.scores, pc.ctx_tail, ng, wide)
+    assert _no_ties(every)
+    for theta in (3, 11, 30):
+        beam, T = {()}, []
+        for L in range(K):
+            level = [(p, sc) for p, sc in every if len(p) == L + 1 and p[:-1] in beam]
+            T += level
+            beam = {p for p, _ in sorted(level, key=lambda ps: -float(ps[1]))[:w]}
+        best = sorted(T, key=lambda ps: -float(ps[1]))[:theta]
+        tree = otp.tree_prune(pc.ids, pc.scores, pc.ctx_tail, ng,
+                              PruneParams(k=k, beam_w=w, budget=theta + 1))
+        assert sorted(otp.tree_paths(tree)) == sorted(best)
+
+
 # ------------------------------------------------------------------ special cases
 def test_k1_gives_the_argmax_chain():
     pc, ng = _case(7, K=5, k=3)
