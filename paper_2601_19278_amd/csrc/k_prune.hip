@@ -498,7 +498,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         // only the expansions above the floor.  The list as merged two levels ago is the one
         // this wavefront may read; its floor is lower than the current one, which is safe.
         int n_keep = n_lvl;
-        if (n_best == theta) {
+        if (theta > 0 && n_best == theta) {
           const uint32_t floor_sc = sh.best_sc[bcur][theta - 1];
           n_keep = min(n_lvl, (int)(__popcll(__ballot(sc[0] > floor_sc)) + __popcll(__ballot(sc[1] > floor_sc)) +
                                     __popcll(__ballot(sc[2] > floor_sc)) + __popcll(__ballot(sc[3] > floor_sc))));

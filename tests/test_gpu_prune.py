@@ -120,7 +120,7 @@ def test_all_scores_tie():
     case = ds.make_prune_case(7300, vocab=1000, K=K, k=k, n_gram=2, S=4)
     case = ds.PruneCase(case.ids, np.zeros_like(case.scores), case.ctx_tail, case.table)
     model = NgramModel(2, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
-    for budget in (2, 5, 14, 40):
+    for budget in (1, 2, 5, 14, 40):
         params = otp.PruneParams(k=k, beam_w=2, budget=budget, w_ng=0.0)
         tokens, parents, mask, n_nodes = _gpu_prune([case], params)
         _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
