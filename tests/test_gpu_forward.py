@@ -98,6 +98,22 @@ def test_shorter_draft_and_longer_capacity():
     ctx.close()
 
 
+def test_longest_context_the_library_accepts():
+    """max_ctx + max_K = 32768 (256 key chunks per K/V head): cold call, warm call, oracle."""
+    cfg = ds.scaled_config("C2", d=256, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=512,
+                           vocab=1024, ctx=32760, K=8)
+    ctx, W = make_context(cfg, 2150)
+    hidden = ds.make_hidden(cfg, 2151)
+    h_dev = hidden_to_device(cfg, hidden)
+    n = cfg.ctx
+    cold = ctx.draft_forward(h_dev, n, cfg.K, n_cached=0).cpu().numpy()
+    ok, msg = logits_close(cold, odf.draft_forward(cfg, W, hidden, cfg.K), **BF16_TOL)
+    assert ok, msg
+    warm = ctx.draft_forward(h_dev, n, cfg.K, n_cached=n - 3).cpu().numpy()
+    np.testing.assert_array_equal(warm, cold)
+    ctx.close()
+
+
 def test_growing_context_like_decoding():
     """Successive calls with a growing prefix reuse cached rows (accepted-token appends)."""
     cfg = SMALL_BF16["tiny64"]
