@@ -53,7 +53,9 @@ enum {
   DART_MAX_TOPK = 64,       /* candidates per position */
   DART_MAX_BEAM = 64,       /* beam width w */
   DART_MAX_BUDGET = 128,    /* tree nodes including the root */
-  DART_MAX_LEVEL_NODES = 4096  /* beam_w * k, the expansions of one level */
+  DART_MAX_LEVEL_NODES = 4096, /* beam_w * k, the expansions of one level */
+  DART_TOPK_STATIC_CELLS = 4864 /* dart_topk_static: rows * ceil(vocab / 4096) at most (128 rows of a
+                                   151936-token vocabulary) */
 };
 
 /* Shapes of the draft layer: one pre-norm decoder layer "aligned with the target
@@ -182,6 +184,21 @@ dart_status dart_draft_forward_features_batched(dart_ctx *ctx, int batch,
  * SHAPE (vocab > cfg.vocab, rows too large), HIP. */
 dart_status dart_topk(dart_ctx *ctx, const float *logits, int rows, int vocab, int k, float eps,
                       int32_t *ids_out, float *scores_out, void *stream);
+
+/* dart_topk without a context and without any allocation, for callers that cannot allocate
+ * device memory (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): same arguments, kernels and results as dart_topk, but the workspace of the chunk
+ * kernel is a fixed array inside the library image (2.5 MiB per GPU, resident until the process
+ * ends) instead of a buffer owned by a dart_ctx.  The call enqueues two kernels on `stream` and
+ * calls no allocating routine; the array's device address is looked up once per device, on the
+ * first call made with that device current.
+ *   rows * ceil(vocab / 4096) <= DART_TOPK_STATIC_CELLS, else SHAPE (nothing launched).
+ * All calls on one GPU share the array: calls that overlap on one GPU (different streams or
+ * threads) race; calls on one stream, or otherwise ordered, are safe.  Nothing needs clearing
+ * between calls (every cell read is written first by the same call).
+ * Errors: ARG (NULL, k < 1, k > min(vocab, DART_MAX_TOPK), rows < 1), SHAPE, HIP. */
+dart_status dart_topk_static(const float *logits, int rows, int vocab, int k, float eps,
+                             int32_t *ids_out, float *scores_out, void *stream);
 
 /* Build the device N-gram table from raw counts (App. C): context = previous
  * n_gram-1 tokens -> up to succ_per_key successors.  HOST inputs:

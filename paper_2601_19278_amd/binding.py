@@ -13,7 +13,7 @@ _LIB = None
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
     "dart_draft_forward_features", "dart_draft_forward_features_batched",
-    "dart_draft_forward_batched", "dart_topk", "dart_ngram_create", "dart_ngram_destroy",
+    "dart_draft_forward_batched", "dart_topk", "dart_topk_static", "dart_ngram_create", "dart_ngram_destroy",
     "dart_tree_prune", "dart_tree_verify_greedy", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
 )
 
@@ -89,6 +89,7 @@ def load_library() -> C.CDLL:
                                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                                         i32, vp, vp]
     lib.dart_topk.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp]
+    lib.dart_topk_static.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
     lib.dart_ngram_create.argtypes = [i32, i64, i32, vp, vp, vp, f32, C.POINTER(vp)]
     lib.dart_ngram_destroy.argtypes = [vp]
     lib.dart_ngram_destroy.restype = None
@@ -254,6 +255,21 @@ class DraftContext:
         if n < 0:
             raise RuntimeError(f"dart_debug_read({name}) failed")
         return buf[: rows * cols].reshape(rows, cols).copy()
+
+
+def topk_static(logits, k: int, eps: float = 1e-9, stream=None, out=None):
+    """dart_topk_static: dart_topk on the library's built-in workspace (no context, no allocation
+    inside the call; pass `out` = (ids, scores) to keep the caller side allocation-free too)."""
+    torch = _torch()
+    lib = load_library()
+    rows, vocab = logits.shape
+    if out is None:
+        out = (torch.empty((rows, k), dtype=torch.int32, device=logits.device),
+               torch.empty((rows, k), dtype=torch.float32, device=logits.device))
+    ids, scores = out
+    _check(lib.dart_topk_static(logits.data_ptr(), rows, vocab, k, eps, ids.data_ptr(),
+                                scores.data_ptr(), _stream_ptr(stream)), "dart_topk_static")
+    return ids, scores
 
 
 def tree_verify_greedy(tokens, parents, n_nodes, ctx_len=None, target_next=None, path_cap: int = 17,

@@ -21,6 +21,8 @@
 // back to the k sequential extractions.
 // Ordering key: (logit descending, token id ascending), as one 64-bit integer
 // (order-preserving float map << 32 | ~id), unique per entry, so the result is deterministic.
+#include <mutex>
+
 #include "common.h"
 #include "dart_internal.h"
 
@@ -269,14 +271,76 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(int k, int nchunks, floa
 
 int topk_chunks(int vocab) { return (vocab + TOPK_CHUNK - 1) / TOPK_CHUNK; }
 
-hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
-                       int32_t *ids, float *scores, hipStream_t st) {
+// cand: [rows][chunks][DART_MAX_TOPK] keys, ms: [rows][chunks][2] floats of workspace.
+static hipError_t launch_topk_on(uint64_t *cand, float *ms, const float *logits, int rows, int vocab,
+                                 int k, float eps, int32_t *ids, float *scores, hipStream_t st) {
   const int nchunks = (vocab + TOPK_CHUNK - 1) / TOPK_CHUNK;
   hipLaunchKernelGGL(topk_kernel, dim3(nchunks, rows), dim3(TOPK_THREADS), 0, st, logits, vocab, k,
-                     nchunks, c->topk_cand, c->topk_ms);
-  hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, nchunks, eps, c->topk_cand,
-                     c->topk_ms, ids, scores);
+                     nchunks, cand, ms);
+  hipLaunchKernelGGL(topk_merge_kernel, dim3(rows), dim3(64), 0, st, k, nchunks, eps, cand, ms, ids,
+                     scores);
   return hipGetLastError();
 }
 
+hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
+                       int32_t *ids, float *scores, hipStream_t st) {
+  return launch_topk_on(c->topk_cand, c->topk_ms, logits, rows, vocab, k, eps, ids, scores, st);
+}
+
 }  // namespace dart
+
+// ---- dart_topk_static: the same two kernels on a workspace that is part of the library image ----
+//
+// Workspace of the chunk kernel for up to DART_TOPK_STATIC_CELLS (row, vocabulary chunk) pairs:
+// the chunk winners, then the chunk statistics.  One copy per GPU, held until the process ends.
+namespace {
+
+constexpr size_t STATIC_CAND_BYTES = (size_t)DART_TOPK_STATIC_CELLS * DART_MAX_TOPK * sizeof(uint64_t);
+constexpr size_t STATIC_MS_BYTES = (size_t)DART_TOPK_STATIC_CELLS * 2 * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[STATIC_CAND_BYTES + STATIC_MS_BYTES];
+
+// Device address of `scratch` on each GPU (the array's name is only a host-side handle; every
+// device holds its own copy at its own address), resolved on the first call per device.
+constexpr int STATIC_MAX_DEVICES = 64;
+void *g_scratch_ptr[STATIC_MAX_DEVICES];
+std::mutex g_scratch_lock;
+
+hipError_t scratch_on_current_device(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" dart_status dart_topk_static(const float *logits, int rows, int vocab, int k, float eps,
+                                        int32_t *ids_out, float *scores_out, void *stream) {
+  if (!logits || !ids_out || !scores_out) return DART_ERR_ARG;
+  if (rows < 1 || vocab < 1 || k < 1 || k > DART_MAX_TOPK || k > vocab) return DART_ERR_ARG;
+  const int64_t cells = (int64_t)rows * dart::topk_chunks(vocab);
+  if (cells > DART_TOPK_STATIC_CELLS) return DART_ERR_SHAPE;
+  void *base = nullptr;
+  if (scratch_on_current_device(&base) != hipSuccess) {
+    (void)hipGetLastError();
+    return DART_ERR_HIP;
+  }
+  // The chunk kernel writes every cell the merge kernel reads (all k winner slots and both
+  // statistics of every (row, chunk) pair of this call), so nothing of an earlier call's
+  // contents is read and nothing needs clearing.
+  uint64_t *cand = reinterpret_cast<uint64_t *>(base);
+  float *ms = reinterpret_cast<float *>(static_cast<unsigned char *>(base) + STATIC_CAND_BYTES);
+  hipError_t e = dart::launch_topk_on(cand, ms, logits, rows, vocab, k, eps, ids_out, scores_out,
+                                      (hipStream_t)stream);
+  return e == hipSuccess ? DART_OK : DART_ERR_HIP;
+}
