@@ -23,6 +23,17 @@
  *     the outputs are untouched.
  *   - A dart_ctx must not be used from two streams at once (calls share its
  *     workspaces and K/V buffers).
+ *   - Numeric range (bf16 contexts).  Weights are used as the exact bf16 values by the
+ *     single-sequence calls.  Intermediates that the library stores in 16 bits are fp16:
+ *     the rotated queries, the draft K/V buffers and the soft-max probabilities, and, in the
+ *     batched calls, every projection input and an fp16 copy of every weight matrix.  fp16
+ *     stores saturate at +-65504 instead of overflowing, and weights below 2^-14 in magnitude
+ *     become fp16 subnormals in that copy (absolute error <= 2^-25).  Results are within the
+ *     stated logit tolerance while |k|, |v|, |q| (after the optional q/k norm and the rotation),
+ *     the normed rows, the attention output and the SwiGLU products stay below 65504; with
+ *     qk_norm = 0 this bounds |Wk RMSNorm(z)| and |Wv RMSNorm(z)|, i.e. the weights' scale, not
+ *     the scale of the hidden states (every projection input is RMS-normalised).  Values beyond
+ *     the range saturate silently: finite, but wrong.
  */
 #ifndef DART_H
 #define DART_H
@@ -203,12 +214,14 @@ dart_status dart_topk_static(const float *logits, int rows, int vocab, int k, fl
 /* Build the device N-gram table from raw counts (App. C): context = previous
  * n_gram-1 tokens -> up to succ_per_key successors.  HOST inputs:
  *   keys        [n_keys][n_gram-1] int32, oldest token first, rows distinct
- *   succ_ids    [n_keys][succ_per_key] int32, distinct within a row
- *   succ_counts [n_keys][succ_per_key] int32, 0 marks an unused slot
+ *   succ_ids    [n_keys][succ_per_key] int32, >= 0 and distinct within a row wherever the
+ *               count is positive (ids of unused slots are ignored)
+ *   succ_counts [n_keys][succ_per_key] int32 >= 0, 0 marks an unused slot
  * Stored score of a successor: min(0, log(count / sum(row counts) + eps)) rounded
  * to fp32; an absent context or successor scores log(eps).  No back-off.
- * Errors: ARG (NULL, n_gram not 2 or 3, succ_per_key not in 1..64, negative ids),
- * OOM, HIP. */
+ * Errors: ARG (NULL, n_gram not 2 or 3, succ_per_key not in 1..64, a negative context token,
+ * a duplicate context, a negative count, a used successor with a negative id or repeated
+ * within its row, n_keys > 2^30), OOM, HIP. */
 dart_status dart_ngram_create(int n_gram, int64_t n_keys, int succ_per_key, const int32_t *keys,
                               const int32_t *succ_ids, const int32_t *succ_counts, float eps,
                               dart_ngram **out);
@@ -217,13 +230,17 @@ void dart_ngram_destroy(dart_ngram *t);
 /* Continuity-aware tree pruning (Alg. 1, App. D) for `batch` independent
  * sequences, one workgroup each.
  *   ids, scores  device [batch][K][k]: candidates per level, best first
- *                (dart_topk output with the same k)
+ *                (dart_topk output with the same k); ids distinct within a level and
+ *                scores <= 0 (log-probabilities), neither is checked on the device
  *   ctx_tail     device [batch][n_gram-1] int32: last real tokens, the root
  *                t_{n+1} last
  *   tokens_out   device [batch][budget] int32; node 0 = root, then level-major,
  *                within a level by (score desc, creation order); -1 beyond n_nodes
  *   parents_out  device [batch][budget] int32 index of the parent node (-1: root
- *                and unused slots); parents precede children
+ *                and unused slots); parents precede children.  With scores <= 0 and the
+ *                parameter ranges below, increments are <= 0 and the theta best nodes are
+ *                closed under "parent of"; a caller that passes positive scores may find
+ *                -2 here for a kept node whose parent was not kept
  *   mask_out     device [batch][budget][budget] uint8, mask[i][j] = 1 iff j == i
  *                or j is an ancestor of i (tree-attention mask); 0 elsewhere
  *   n_nodes_out  device [batch] int32 = 1 + min(budget-1, total expansions)
@@ -232,7 +249,8 @@ void dart_ngram_destroy(dart_ngram *t);
  * are reproducible bit for bit.  Ties: beam cut by (score desc, creation asc),
  * global cut by (score desc, level asc, creation asc).
  * Errors: ARG (NULL, K not in 1..DART_MAX_K, k, beam_w, budget out of range,
- * beam_w*k > DART_MAX_LEVEL_NODES, batch < 1), HIP. */
+ * beam_w*k > DART_MAX_LEVEL_NODES, batch < 1, w_ng < 0, logit_decay <= 0, or a non-finite
+ * w_ng, logit_decay or level_pow), HIP. */
 dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, int K,
                             const int32_t *ctx_tail, const dart_ngram *table,
                             const dart_prune_params *params, int32_t *tokens_out,
@@ -263,29 +281,6 @@ dart_status dart_tree_verify_greedy(int batch, const int32_t *tokens, const int3
                                     int32_t *position_ids, const int32_t *target_next,
                                     int path_cap, int32_t *accept_path, int32_t *n_accepted,
                                     int32_t *next_token, void *stream);
-
-/* Diagnostic (tests only): copy a named fp32 workspace of the last forward call to host
- * memory after synchronising the device.  Names: "xn" (normed layer input), "resid", "qkv",
- * "att_out" (attention output), "y" (after attention residual), "yn", "hmid" (SwiGLU
- * product), "u" (after MLP residual).  Buffers hold 16 rows and are those of the single-sequence
- * calls: the batched calls hand most of these rows on as packed operand tiles and do not store
- * them.  Returns the number of floats copied (at most max_count) or -1 on error. */
-int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_t max_count);
-
-/* Diagnostic (benchmark only): enqueue only the LM-head projection (the final step of
- * dart_draft_forward, Sec. 3.2) on the final-normed rows the last forward call left in the
- * workspace; logits_out device [rows][vocab] fp32.  multi_row = 0: the kernel of the
- * single-sequence call (rows <= 16); 1: the kernels of the batched call (bf16 contexts,
- * rows <= 16 * max_K): operand conversion pass + contraction; 2: the contraction alone, on the
- * operand tiles a preceding call with multi_row = 1 and the same rows left behind.  Used to
- * time those kernels in isolation. */
-dart_status dart_debug_lm_head(dart_ctx *ctx, int rows, int multi_row, float *logits_out,
-                               void *stream);
-
-/* Diagnostic (benchmark sweeps only): override a launch tunable of the kernels by name
- * ("gemv_wgs", "gemv_xcd", "gemv_depth", "gemv_nt", "gemv_nt_min_mb", "gemv_split", "gemm_wgs", "attn_seg").  Process-wide,
- * not thread-safe.  Returns 0, or -1 for an unknown name. */
-int dart_debug_set(const char *name, int value);
 
 #ifdef __cplusplus
 }

@@ -14,8 +14,10 @@ EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
     "dart_draft_forward_features", "dart_draft_forward_features_batched",
     "dart_draft_forward_batched", "dart_topk", "dart_topk_static", "dart_ngram_create", "dart_ngram_destroy",
-    "dart_tree_prune", "dart_tree_verify_greedy", "dart_debug_read", "dart_debug_lm_head", "dart_debug_set",
+    "dart_tree_prune", "dart_tree_verify_greedy",
 )
+# include/dart_debug.h: diagnostics for this repository's tests and benchmark, not product API
+DEBUG_SYMBOLS = ("dart_debug_read", "dart_debug_lm_head")
 
 DART_F32, DART_BF16 = 0, 1
 
@@ -99,7 +101,8 @@ def load_library() -> C.CDLL:
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
     lib.dart_debug_lm_head.argtypes = [vp, i32, i32, vp, vp]
-    lib.dart_debug_set.argtypes = [C.c_char_p, i32]
+    if hasattr(lib, "dart_debug_set"):          # tuning builds (-DDART_TUNING) only
+        lib.dart_debug_set.argtypes = [C.c_char_p, i32]
     _LIB = lib
     return lib
 

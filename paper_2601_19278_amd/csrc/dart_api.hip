@@ -1,9 +1,11 @@
 // C ABI of the DART drafting step: context creation (weight upload and re-tiling),
 // orchestration of the draft forward, top-k, N-gram table build and tree pruning.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -17,6 +19,27 @@ using namespace dart;
     hipError_t e_ = (expr);              \
     if (e_ != hipSuccess) return e_;     \
   } while (0)
+
+namespace dart {
+
+hipError_t raise_dynamic_lds_once(const void *func, int bytes) {
+  struct Done {
+    const void *func;
+    int device;
+  };
+  static std::mutex lock;
+  static std::vector<Done> done;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> hold(lock);
+  for (const Done &d : done)
+    if (d.func == func && d.device == dev) return hipSuccess;
+  HIP_TRY(hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  done.push_back(Done{func, dev});
+  return hipSuccess;
+}
+
+}  // namespace dart
 
 namespace {
 
@@ -663,18 +686,47 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
   const size_t cells = (size_t)std::max<int64_t>(n_keys, 1) * S;
   std::vector<int32_t> ids(cells, -1);
   std::vector<float> logp(cells, miss);
-  for (int64_t r = 0; r < n_keys; ++r) {
-    int64_t total = 0;
-    for (int j = 0; j < S; ++j) {
-      if (succ_counts[r * S + j] < 0) return DART_ERR_ARG;
-      total += succ_counts[r * S + j];
+  // Rows are independent: scored (and validated) on a few host threads.  A used successor must
+  // have a non-negative id, and the used ids of a row must be distinct: the pruning kernel lets
+  // one thread per (successor, candidate) match write a score cell, so a duplicate would make
+  // two threads write one cell with different values.
+  std::vector<int> bad(8, 0);
+  auto score_rows = [&](int64_t r0, int64_t r1, int *bad_flag) {
+    int32_t seen[64];
+    for (int64_t r = r0; r < r1; ++r) {
+      int64_t total = 0;
+      int used = 0;
+      for (int j = 0; j < S; ++j) {
+        const int32_t cnt = succ_counts[r * S + j];
+        if (cnt < 0 || (cnt > 0 && succ_ids[r * S + j] < 0)) {
+          *bad_flag = 1;
+          return;
+        }
+        total += cnt;
+        if (cnt > 0) seen[used++] = succ_ids[r * S + j];
+      }
+      std::sort(seen, seen + used);
+      for (int j = 1; j < used; ++j)
+        if (seen[j] == seen[j - 1]) {
+          *bad_flag = 1;
+          return;
+        }
+      for (int j = 0; j < S; ++j) {
+        const int32_t cnt = succ_counts[r * S + j];
+        if (cnt <= 0) continue;
+        ids[r * S + j] = succ_ids[r * S + j];
+        logp[r * S + j] = std::fmin(0.0f, (float)std::log((double)cnt / (double)total + eps_d));
+      }
     }
-    for (int j = 0; j < S; ++j) {
-      const int32_t cnt = succ_counts[r * S + j];
-      if (cnt <= 0) continue;
-      ids[r * S + j] = succ_ids[r * S + j];
-      logp[r * S + j] = std::fmin(0.0f, (float)std::log((double)cnt / (double)total + eps_d));
-    }
+  };
+  {
+    const int nthr = n_keys >= 4096 ? 8 : 1;
+    std::vector<std::thread> pool;
+    for (int i = 0; i < nthr; ++i)
+      pool.emplace_back(score_rows, n_keys * i / nthr, n_keys * (i + 1) / nthr, &bad[i]);
+    for (auto &th : pool) th.join();
+    for (int i = 0; i < nthr; ++i)
+      if (bad[i]) return DART_ERR_ARG;
   }
   dart_ngram *t = new (std::nothrow) dart_ngram();
   if (!t) return DART_ERR_OOM;
@@ -716,6 +768,11 @@ dart_status dart_tree_prune(int batch, const int32_t *ids, const float *scores, 
   if (p->k < 1 || p->k > DART_MAX_TOPK || p->beam_w < 1 || p->beam_w > DART_MAX_BEAM ||
       p->budget < 1 || p->budget > DART_MAX_BUDGET || p->beam_w * p->k > DART_MAX_LEVEL_NODES)
     return DART_ERR_ARG;
+  // Alg. 1's "top-theta of T" is a tree only if scores never rise along a path: increments must
+  // be <= 0, i.e. non-negative weights on scores that are <= 0 (as dart_topk and the table emit)
+  if (!(p->w_ng >= 0.0f) || !(p->logit_decay > 0.0f) || !std::isfinite(p->w_ng) ||
+      !std::isfinite(p->logit_decay) || !std::isfinite(p->level_pow))
+    return DART_ERR_ARG;
   PruneLevelWeights lw;
   for (int L = 0; L < DART_MAX_K; ++L) {
     lw.w_logit[L] = (float)std::pow((double)p->logit_decay, (double)L);
@@ -739,7 +796,8 @@ dart_status dart_tree_verify_greedy(int batch, const int32_t *tokens, const int3
                                      (hipStream_t)stream));
 }
 
-// Diagnostic: set a kernel tunable by name (benchmark sweeps).  Returns 0 if the name is known.
+#ifdef DART_TUNING
+// Tuning builds only: set a kernel tunable by name (sweeps).  Returns 0 if the name is known.
 int dart_debug_set(const char *name, int value) {
   if (!name) return -1;
   if (!strcmp(name, "gemv_wgs")) g_gemv_wgs = value;
@@ -754,6 +812,7 @@ int dart_debug_set(const char *name, int value) {
   else return -1;
   return 0;
 }
+#endif
 
 // Diagnostic: run only the LM-head projection again on the final-normed rows the last forward
 // call left in the workspace (used to time that kernel in isolation).
@@ -776,7 +835,7 @@ int64_t dart_debug_read(dart_ctx *c, const char *name, float *host_out, int64_t 
   const int R = DART_SKINNY_ROWS;
   const float *src = nullptr;
   int64_t count = 0;
-  if (!strcmp(name, "xn")) src = c->xn, count = (int64_t)R * c->cfg.d;
+  if (!strcmp(name, "xn")) src = c->xn, count = (int64_t)R * c->in_dim;
   else if (!strcmp(name, "resid")) src = c->resid, count = (int64_t)R * c->cfg.d;
   else if (!strcmp(name, "qkv")) src = c->qkv, count = (int64_t)R * c->qkv_dim;
   else if (!strcmp(name, "att_out")) src = c->att_out, count = (int64_t)R * c->q_dim;

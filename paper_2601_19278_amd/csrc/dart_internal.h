@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "../../include/dart.h"
+#include "../../include/dart_debug.h"
 
 #define DART_SKINNY_ROWS 16   // rows one skinny-GEMM pass carries (one MFMA column block)
 #define ATTN_KEY_CHUNK 128    // keys one attention workgroup walks (split-KV granularity)
@@ -172,8 +173,19 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
   return x;
 }
 
-// Launch tunables (defaults fixed after measurement; dart_debug_set overrides them).
-extern int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs, g_attn_seg;
+// Launch tunables: constants fixed after measurement.  Only a build with -DDART_TUNING (sweeps
+// on a developer's box) makes them variables and exports dart_debug_set to change them; the
+// product library has no mutable process-wide state on the hot path.
+#ifdef DART_TUNING
+#define DART_TUNABLE
+#else
+#define DART_TUNABLE const
+#endif
+extern DART_TUNABLE int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs, g_attn_seg;
+
+// Raise a kernel's dynamic-LDS limit: a per-device property of the function, set the first time
+// the function is launched on each device (thread-safe; a race only repeats the idempotent call).
+hipError_t raise_dynamic_lds_once(const void *func, int bytes);
 
 // All launchers only enqueue work on `st` and return the launch status.
 

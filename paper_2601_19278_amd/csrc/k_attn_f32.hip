@@ -141,7 +141,7 @@ hipError_t launch_attention_bf16(const dart_ctx *c, const SeqBatch &sb, const At
                                  int nseg, hipStream_t st);
 
 // Chunk units per attention workgroup of the bf16 path; 0 = chosen from the amount of work.
-int g_attn_seg = 0;
+DART_TUNABLE int g_attn_seg = 0;
 
 void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps);
 

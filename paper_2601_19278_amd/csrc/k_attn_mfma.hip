@@ -311,14 +311,8 @@ static hipError_t launch_one(const dart_ctx *c, const SeqBatch &sb, const AttnWo
   auto kern = attn_split_mfma_kernel<HD, NW, TW>;
   const size_t chunk_bytes = (size_t)2 * ATTN_KEY_CHUNK * HD * sizeof(f16_t);   // K and V^T
   const size_t lds = chunk_bytes * (work.per > 1 ? 2 : 1);
-  static bool raised = false;        // per instantiation; the limit is a property of the function
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(2 * chunk_bytes));
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  hipError_t e = raise_dynamic_lds_once(reinterpret_cast<const void *>(kern), (int)(2 * chunk_bytes));
+  if (e != hipSuccess) return e;
   const int units = work.cum[sb.B] * g.n_kv_heads;
   hipLaunchKernelGGL(kern, dim3((units + work.per - 1) / work.per), dim3(64 * NW), lds, st, sb, work,
                      (const f16_t *)c->qrot, (const f16_t *)c->kbuf, (const f16_t *)c->vbuf,

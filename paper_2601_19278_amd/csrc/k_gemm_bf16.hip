@@ -9,12 +9,17 @@
 // Roles: weights are the MFMA A operand, read straight from global memory in the packed tile
 // layout (1 KiB per 16 outputs x 32 inputs, already in operand order) -- each tile is used by
 // exactly one wavefront, so staging it in LDS would buy nothing.  Activations are the B
-// operand.  pack_rows_kernel converts them once from fp32 to bf16 hi + lo parts
-// (x ~= hi + lo to 2^-17, weights stay the exact bf16 values) in operand order, 1 KiB tiles of
-// 16 rows x 32 inputs; the GEMM workgroup copies the tiles of its row block (up to 128 rows)
-// for two k-steps at a time from global memory straight into LDS (no registers involved) and
-// its 8 wavefronts share them, each applying them to its own strips of 16 outputs.  A
-// wavefront holds up to 4 strips x 8 row tiles of fp32 accumulators.
+// operand, read from a buffer of packed operand tiles (1 KiB per 16 rows x 32 inputs, in operand
+// order) in one of two formats: one fp16 tile per row tile against the fp16 copy of the weights
+// (contexts of the batched calls: one product per weight tile), or a bf16 hi tile and a bf16 lo
+// tile (x ~= hi + lo to 2^-17) against the exact bf16 weights (two products).  The tiles are
+// written by whichever kernel produces the rows -- the input norm, the attention merge, the
+// residual + norm kernels, the gate/up projection's SwiGLU epilogue -- and only rows that arrive
+// as plain fp32 (the FC input of the front end) go through pack_rows_kernel first.  The GEMM
+// workgroup copies the tiles of its row block (up to 128 rows) for two k-steps at a time from
+// global memory straight into LDS (no registers involved) and its 8 wavefronts share them,
+// each applying them to its own strips of 16 outputs.  A wavefront holds up to 4 strips x 8
+// row tiles of fp32 accumulators.
 //
 // Work units: (row block of 16*NCT rows, contiguous strip range, k-chunk).  Strip ranges are
 // a balanced partition, so a launch with one range per compute unit has no tail; a range
@@ -355,7 +360,7 @@ hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipSt
   return hipGetLastError();
 }
 
-int g_gemm_wgs = 256;      // resident workgroups: one per compute unit
+DART_TUNABLE int g_gemm_wgs = 256;      // resident workgroups: one per compute unit
 
 // k-chunks of a matrix on this path: fixed per matrix so that a row's sums do not depend on
 // the call.  Matrices with few strips are cut along k until (strip ranges of 8 strips, one per

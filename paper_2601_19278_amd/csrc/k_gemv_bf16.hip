@@ -36,15 +36,15 @@ int gemv_bf16_chunks(int Kd) {
   return (KT + GEMV_WAVES * GEMV_KPW_MAX - 1) / (GEMV_WAVES * GEMV_KPW_MAX);
 }
 
-// Tunables (fixed after measurement; the benchmark harness may override them).
-int g_gemv_wgs = 184;      // resident workgroups.  Fewer than the 256 compute units on purpose: measured on
+// Tunables (fixed after measurement; variables only in a -DDART_TUNING build).
+DART_TUNABLE int g_gemv_wgs = 184;      // resident workgroups.  Fewer than the 256 compute units on purpose: measured on
                            // MI355X the weight stream peaks at 176-192 workgroups (LM head 6.6 TB/s against
                            // 6.2 TB/s with one per compute unit; 160 and fewer fall off again)
-int g_gemv_wgs_split = 224;  // the same for matrices whose k range is cut into chunks (QKV, O, MLP): best at 216-232
-int g_gemv_xcd = 2;        // strip-to-XCD assignment, see the kernel
-int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
-int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
-int g_gemv_nt_min_mb = 100;  // ... for matrices (strip ranges) of at least this many MiB: smaller ones
+DART_TUNABLE int g_gemv_wgs_split = 224;  // the same for matrices whose k range is cut into chunks (QKV, O, MLP): best at 216-232
+DART_TUNABLE int g_gemv_xcd = 2;        // strip-to-XCD assignment, see the kernel
+DART_TUNABLE int g_gemv_depth = 0;      // 0 = default rolling-buffer depth for the k-slice length
+DART_TUNABLE int g_gemv_nt = 1;         // weight tiles are read once: load them with the non-temporal hint
+DART_TUNABLE int g_gemv_nt_min_mb = 100;  // ... for matrices (strip ranges) of at least this many MiB: smaller ones
                              // (QKV, O) partly survive in the last-level cache from step to step (measured -3 us)
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
@@ -247,7 +247,7 @@ static void gemv_launch(bool nt, int mt, dim3 grid, hipStream_t st, const u32x4_
 // of 4 chunks of 17; matrices with more than ~12 strips per workgroup (the LM head) gain nothing.
 // Only chunk counts that keep every wavefront's k-slice an exact, supported length of at least
 // 4 k-steps are used.
-int g_gemv_split = 0;      // benchmark override: multiple of the minimum chunk count (0 = automatic)
+DART_TUNABLE int g_gemv_split = 0;      // tuning builds: multiple of the minimum chunk count (0 = automatic)
 
 static bool exact_kpw_supported(int kpw) {
   return kpw == 2 || kpw == 4 || kpw == 5 || kpw == 8 || kpw == 10 || kpw == 12 || kpw == 16 ||

@@ -876,14 +876,8 @@ hipError_t launch_prune(int batch, const int32_t *ids, const float *scores, int 
                         const int32_t *ctx_tail, const NgramTableDev &tab,
                         const dart_prune_params &p, const PruneLevelWeights &lw, int32_t *tokens,
                         int32_t *parents, uint8_t *mask, int32_t *n_nodes, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)prune_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)sizeof(PruneShared));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  hipError_t e = raise_dynamic_lds_once((const void *)prune_kernel, (int)sizeof(PruneShared));
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(prune_kernel, dim3(batch), dim3(PRUNE_THREADS), sizeof(PruneShared), st, ids,
                      scores, K, ctx_tail, tab, p.k, p.beam_w, p.budget, p.w_ng, lw, tokens, parents,
                      mask, n_nodes);

@@ -21,14 +21,24 @@ def dart():
     return pkg
 
 
-def test_header_symbols_are_exported(dart):
-    header = open(os.path.join(ROOT, "include", "dart.h")).read()
+def _declared(header_name, skip_ifdef=None):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(dart_[a-z_]+)\s*\(", header))
+    if skip_ifdef:
+        header = re.sub(r"#ifdef %s\b.*?#endif" % skip_ifdef, "", header, flags=re.S)
+    return set(re.findall(r"\b(dart_[a-z_]+)\s*\(", header))
+
+
+def test_header_symbols_are_exported(dart):
+    declared = _declared("dart.h")
     assert declared == set(dart.EXPORTED_SYMBOLS)
+    assert not any("debug" in name for name in declared)          # diagnostics live elsewhere
+    debug = _declared("dart_debug.h", skip_ifdef="DART_TUNING")
+    assert debug == set(dart.DEBUG_SYMBOLS)
     lib = dart.load_library()
-    for name in declared:
+    for name in declared | debug:
         assert hasattr(lib, name), name
+    assert not hasattr(lib, "dart_debug_set")        # product build: launch tunables are constants
     assert lib.dart_status_str(0) == b"ok"
     assert lib.dart_status_str(5) == b"invalid call sequence"
 
@@ -67,6 +77,22 @@ def test_ngram_and_prune_argument_checks(dart):
     assert lib.dart_ngram_create(3, 1, 2, None, None, None, 1e-9, C.byref(h)) == 1
     neg = np.array([[-1, 2]], np.int32)
     assert lib.dart_ngram_create(3, 1, 2, neg.ctypes.data, args[1], args[2], 1e-9, C.byref(h)) == 1
+    # a used successor with a negative id, a successor repeated within its row, a negative count
+    for bad_ids, bad_cnt in (([[3, -1]], [[1, 1]]), ([[3, 3]], [[1, 2]]), ([[3, 4]], [[1, -1]])):
+        bi, bc = np.array(bad_ids, np.int32), np.array(bad_cnt, np.int32)
+        assert lib.dart_ngram_create(3, 1, 2, args[0], bi.ctypes.data, bc.ctypes.data, 1e-9, C.byref(h)) == 1
+    dup = np.array([[1, 2], [1, 2]], np.int32)                               # the same context twice
+    two = np.array([[3, 4], [5, 6]], np.int32)
+    one = np.ones((2, 2), np.int32)
+    assert lib.dart_ngram_create(3, 2, 2, dup.ctypes.data, two.ctypes.data, one.ctypes.data, 1e-9, C.byref(h)) == 1
+    # pruning parameters outside the range in which Alg. 1's top-theta set is a tree
+    P = dart.binding._PruneParams
+    buf = np.zeros(64, np.int32)
+    ptr = buf.ctypes.data           # never dereferenced: the parameter check comes first
+    for w_ng, decay, pw in ((-0.5, 0.9, 0.7), (0.5, 0.0, 0.7), (0.5, -0.9, 0.7), (0.5, 0.9, float("nan")),
+                            (float("inf"), 0.9, 0.7), (0.5, float("nan"), 0.7)):
+        p = P(2, 2, 4, w_ng, decay, pw)
+        assert lib.dart_tree_prune(1, ptr, ptr, 2, ptr, ptr, C.byref(p), ptr, ptr, ptr, ptr, None) == 1
     assert lib.dart_tree_prune(1, None, None, 4, None, None, None, None, None, None, None, None) == 1
     assert lib.dart_topk(None, None, 1, 1, 1, 1e-9, None, None, None) == 1
     assert lib.dart_draft_forward(None, 0, None, 1, 0, 1, None, None) == 1
