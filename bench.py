@@ -23,10 +23,65 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per LM-head launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# a plain 1 GiB copy (profiles/lm_head_C4_hbm_counters.txt, profiles/gemm_lm_head_C5_counters.txt);
-# re-measure after kernel changes.
-MEASURED_LM_HEAD_TRAFFIC = {"C4": 1589.6e6, "C5": 1685.5e6}
+
+
+def profiled_traffic(key: str) -> dict:
+    """HBM bytes per LM-head launch from the committed rocprofv3 counter summaries.
+
+    The summaries under profiles/ (FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy) carry one
+    line `traffic_key: <kernel variant and grid> | bytes=<N>` per measured launch.  The figure is
+    reported only when that key equals the kernel variant and grid the library launches in this
+    run; after a kernel or launch-shape change the line says so instead of quoting a stale number.
+    """
+    pdir = os.path.join(ROOT, "profiles")
+    for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not name.endswith(".txt"):
+            continue
+        for line in open(os.path.join(pdir, name)):
+            if line.startswith("traffic_key:") and "|" in line:
+                k, _, rest = line[len("traffic_key:"):].partition("|")
+                if k.strip() == key and "bytes=" in rest:
+                    return {"traffic": float(rest.split("bytes=")[1].split()[0]),
+                            "traffic_source": f"profiles/{name}", "traffic_stale": False}
+    return {"traffic": None, "traffic_source": None, "traffic_stale": True}
+
+
+def percentiles(xs) -> dict:
+    import numpy as np
+    a = np.asarray(xs, dtype=np.float64)
+    return {"median": round(float(np.median(a)), 2), "p10": round(float(np.percentile(a, 10)), 2),
+            "p90": round(float(np.percentile(a, 90)), 2), "mean": round(float(a.mean()), 2), "n": int(a.size)}
+
+
+def event_times_us(fn, iters: int, torch) -> list:
+    """GPU time of each of `iters` consecutive fn() calls in us (HIP events on the launch
+    stream between the calls; no host synchronisation inside the sequence)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(iters):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return [ev[i].elapsed_time(ev[i + 1]) * 1000.0 for i in range(iters)]
+
+
+def streaming_read_ceiling(torch, dart, dev, gib: int = 4) -> dict:
+    """Read rate of a plain non-temporal streaming-read kernel over `gib` GiB on this machine: the
+    practical ceiling next to the 8 TB/s data-sheet peak."""
+    buf = torch.empty(gib << 30, dtype=torch.uint8, device=dev)
+    buf.zero_()
+    best = None
+    for wgs in (1024, 2048, 4096):
+        dart.debug_stream_read(buf, wgs)
+        ts = event_times_us(lambda: dart.debug_stream_read(buf, wgs), 8, torch)
+        rate = buf.numel() / (sorted(ts)[len(ts) // 2] * 1e-6) / 1e9
+        if best is None or rate > best[0]:
+            best = (rate, wgs)
+    del buf
+    torch.cuda.empty_cache()
+    return {"ceiling_GBps": round(best[0], 1), "ceiling_kernel": f"stream_read_kernel, {gib} GiB, "
+            f"{best[1]} workgroups x 512 threads, 16 B per lane, non-temporal, median of 8"}
 
 
 def algorithmic_bytes(cfg, n_new: int) -> dict:
@@ -139,7 +194,9 @@ def bench_batched(cfg, args, seed) -> dict:
               "step_gpu_us": event_time_us(step, it, torch), "cold_forward_us": cold_us,
               "sum_ctx_len": int(sum(lens))}
     ctx.debug_lm_head(B * K, logits, multi_row=1)      # leaves the operand tiles of the 128 rows
-    lm_us = event_time_us(lambda: ctx.debug_lm_head(B * K, logits, multi_row=2), it, torch)
+    lm_times = event_times_us(lambda: ctx.debug_lm_head(B * K, logits, multi_row=2), it, torch)
+    lm_us = sum(lm_times) / len(lm_times)
+    step_times = event_times_us(step, it, torch)
     forward(warm)
     if args.copy_calibration:
         copy_calibration(torch, dev)
@@ -153,10 +210,17 @@ def bench_batched(cfg, args, seed) -> dict:
     roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel (LM head, 128 rows)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_LM_HEAD_TRAFFIC.get(cfg.name),
-                "kernel_us": round(lm_us, 2), "algorithmic_bytes": lm_bytes,
+                **profiled_traffic(ctx.debug_lm_head_key(B * K, multi_row=1)),
+                "kernel_us": round(lm_us, 2), "kernel_us_stats": percentiles(lm_times),
+                "kernel_variant": ctx.debug_lm_head_key(B * K, multi_row=1),
+                "algorithmic_bytes": lm_bytes,
                 "mfma_TFLOPs_algorithmic": round(2.0 * B * K * p["lm_head"] / (lm_us * 1e-6) / 1e12, 1)}
+    if not args.no_ceiling:
+        ceil = streaming_read_ceiling(torch, dart, dev)
+        roofline.update(ceil)
+        roofline["frac_of_ceiling"] = round(achieved / ceil["ceiling_GBps"], 4)
     stages["lm_head_us"] = lm_us
+    stages["step_gpu_us_stats"] = percentiles(step_times)
     stages["forward_GBps"] = fwd_bytes / (stages["forward_warm_us"] * 1e-6) / 1e9
     stages["forward_TFLOPs"] = 2.0 * B * K * p["total"] / (stages["forward_warm_us"] * 1e-6) / 1e12
     cpu = None
@@ -194,6 +258,24 @@ def bench_batched(cfg, args, seed) -> dict:
     }
 
 
+def c5_stage_block(args) -> dict:
+    """The batched preset (C5: 16 ragged sequences, 128 masked rows, Qwen3-32B shapes) timed in
+    the same run as the headline preset: its step, LM-head kernel and forward rates."""
+    import dart_synth as ds
+    sub_args = argparse.Namespace(**vars(args))
+    sub_args.no_cpu_baseline, sub_args.no_ceiling, sub_args.copy_calibration = True, True, False
+    sub_args.front_end = False
+    sub_args.steps, sub_args.warmup = max(10, min(30, args.steps)), max(3, min(5, args.warmup))
+    r = bench_batched(ds.get_config("C5"), sub_args, 5000)
+    st, rf = r["stages"], r["roofline"]
+    return {"workload": r["config"]["workload"], "step_us": r["value"], "steps": sub_args.steps,
+            "step_gpu_us_stats": st["step_gpu_us_stats"], "forward_warm_us": st["forward_warm_us"],
+            "topk_us": st["topk_us"], "prune_us": st["prune_us"], "lm_head_us": st["lm_head_us"],
+            "lm_head_GBps": rf["achieved"], "lm_head_frac": rf["frac"],
+            "lm_head_variant": rf["kernel_variant"], "forward_GBps": st["forward_GBps"],
+            "forward_TFLOPs": st["forward_TFLOPs"], "cold_forward_us": st["cold_forward_us"]}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -205,6 +287,10 @@ def main() -> int:
     ap.add_argument("--front-end", action="store_true",
                     help="start from the target's raw outputs: FC over 3 concatenated hidden states + "
                          "shifted token embeddings, 2d-wide attention input (single-sequence presets)")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the in-run 4 GiB streaming-read measurement (roofline.ceiling_GBps)")
+    ap.add_argument("--no-c5", action="store_true",
+                    help="skip the stages.c5 block (the batched preset timed after the headline one)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM bytes) for counter scaling")
     args = ap.parse_args()
@@ -297,7 +383,11 @@ def main() -> int:
         "step_gpu_us": event_time_us(step, it, torch),
         "cold_forward_us": cold_us,
     }
-    lm_us = event_time_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
+    lm_times = event_times_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
+    lm_us = sum(lm_times) / len(lm_times)
+    step_times = event_times_us(step, max(it, min(200, args.steps)), torch)
+    stages["step_gpu_us_stats"] = percentiles(step_times)
+    stages["forward_warm_us_stats"] = percentiles(event_times_us(lambda: forward(n - args.n_new), it, torch))
     forward(n - args.n_new)          # leave the buffers consistent
     ab = algorithmic_bytes(cfg, args.n_new)
     if fe:      # + FC weights, + the second half of the Q/K/V input columns (embedding rows: negligible)
@@ -307,8 +397,15 @@ def main() -> int:
     achieved = ab["lm_head_kernel"] / (lm_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemv_bf16_kernel (LM head)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_LM_HEAD_TRAFFIC.get(cfg.name), "kernel_us": round(lm_us, 2),
+                **(profiled_traffic(ctx.debug_lm_head_key(K)) if cfg.dtype == "bf16" else
+                   {"traffic": None}),
+                "kernel_us": round(lm_us, 2), "kernel_us_stats": percentiles(lm_times),
+                "kernel_variant": ctx.debug_lm_head_key(K) if cfg.dtype == "bf16" else "gemv_f32_kernel",
                 "algorithmic_bytes": ab["lm_head_kernel"]}
+    if not args.no_ceiling:
+        ceil = streaming_read_ceiling(torch, dart, dev)
+        roofline.update(ceil)
+        roofline["frac_of_ceiling"] = round(achieved / ceil["ceiling_GBps"], 4)
     stages["lm_head_us"] = lm_us
     stages["forward_GBps"] = ab["forward"] / (stages["forward_warm_us"] * 1e-6) / 1e9
 
@@ -351,6 +448,13 @@ def main() -> int:
                    for a, b in stages.items()},
         "input_gen_s": round(t_gen, 1),
     }
+    if cfg.name == "C4" and not args.no_c5 and not fe:
+        # the batched preset in the same run; the headline context is released first
+        ctx.close()
+        table.close()
+        del h_dev, logits
+        torch.cuda.empty_cache()
+        out["stages"]["c5"] = c5_stage_block(args)
     print(json.dumps(out))
     return 0
 

@@ -121,7 +121,7 @@ const char *dart_status_str(dart_status s);
 
 /* Build a context on the current HIP device.  Errors: ARG (NULL, non-positive
  * sizes, max_K > DART_MAX_K, head_dim not 64 or 128, n_q_heads not a multiple of
- * n_kv_heads, bf16 with d, Hq*hd or ffn not a multiple of 32, or d > 5120; fp32 with d not a
+ * n_kv_heads, bf16 with d, Hq*hd or ffn not a multiple of 32; fp32 with d not a
  * multiple of 8 or ffn not a multiple of 4; d > 16384; max_ctx + max_K > 32768; more than 8 query heads per K/V head), OOM, HIP. */
 dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx **out);
 void dart_destroy(dart_ctx *ctx);

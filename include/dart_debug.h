@@ -30,6 +30,21 @@ int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_
 dart_status dart_debug_lm_head(dart_ctx *ctx, int rows, int multi_row, float *logits_out,
                                void *stream);
 
+/* Diagnostic (benchmark only): the name and launch shape of the kernel that
+ * dart_debug_lm_head(ctx, rows, multi_row != 0, ...) launches for the LM head, as text
+ * ("gemv_bf16_kernel<20,20,0,true,true> grid=184x512"), written to buf (at most len bytes
+ * including the terminator).  Counter summaries under profiles/ are keyed by this string.
+ * Returns the length written, or -1 on error. */
+int dart_debug_lm_head_key(dart_ctx *ctx, int rows, int multi_row, char *buf, int len);
+
+/* Diagnostic (benchmark only): a plain streaming read of `bytes` bytes of device memory at
+ * `buf` (16-byte aligned) by `workgroups` workgroups of 512 threads, 16 bytes per lane per
+ * load, with the non-temporal hint the weight streams use (non_temporal != 0) or as ordinary
+ * cached loads; nothing is written (`sink`, device, 4 bytes, may be NULL).  The read rate of
+ * this kernel is the practical ceiling the weight-streaming kernels are compared with. */
+dart_status dart_debug_stream_read(const void *buf, int64_t bytes, int workgroups, int non_temporal,
+                                   void *sink, void *stream);
+
 #ifdef DART_TUNING
 /* Tuning builds only (library compiled with -DDART_TUNING; the product build does not export
  * this symbol and its launch tunables are constants): override a launch tunable of the kernels by name

@@ -6,8 +6,8 @@ this package only marshals arguments.  PyTorch supplies device memory and stream
 There is no CPU fallback: if the library has not been built, loading raises.
 """
 from .binding import (DartError, DraftContext, NgramTable, PruneParams, library_path,
-                      load_library, bf16_bits_to_tensor, tree_verify_greedy, topk_static,
+                      load_library, bf16_bits_to_tensor, tree_verify_greedy, topk_static, debug_stream_read,
                       EXPORTED_SYMBOLS, DEBUG_SYMBOLS)
 
 __all__ = ["DartError", "DraftContext", "NgramTable", "PruneParams", "library_path",
-           "load_library", "bf16_bits_to_tensor", "tree_verify_greedy", "topk_static", "EXPORTED_SYMBOLS", "DEBUG_SYMBOLS"]
+           "load_library", "bf16_bits_to_tensor", "tree_verify_greedy", "topk_static", "debug_stream_read", "EXPORTED_SYMBOLS", "DEBUG_SYMBOLS"]

@@ -17,7 +17,8 @@ EXPORTED_SYMBOLS = (
     "dart_tree_prune", "dart_tree_verify_greedy",
 )
 # include/dart_debug.h: diagnostics for this repository's tests and benchmark, not product API
-DEBUG_SYMBOLS = ("dart_debug_read", "dart_debug_lm_head")
+DEBUG_SYMBOLS = ("dart_debug_read", "dart_debug_lm_head", "dart_debug_lm_head_key",
+                 "dart_debug_stream_read")
 
 DART_F32, DART_BF16 = 0, 1
 
@@ -101,6 +102,8 @@ def load_library() -> C.CDLL:
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
     lib.dart_debug_lm_head.argtypes = [vp, i32, i32, vp, vp]
+    lib.dart_debug_lm_head_key.argtypes = [vp, i32, i32, C.c_char_p, i32]
+    lib.dart_debug_stream_read.argtypes = [vp, i64, i32, i32, vp, vp]
     if hasattr(lib, "dart_debug_set"):          # tuning builds (-DDART_TUNING) only
         lib.dart_debug_set.argtypes = [C.c_char_p, i32]
     _LIB = lib
@@ -252,12 +255,26 @@ class DraftContext:
                                             _stream_ptr(stream)), "dart_debug_lm_head")
         return out
 
+    def debug_lm_head_key(self, rows: int, multi_row: int = 0) -> str:
+        buf = C.create_string_buffer(256)
+        n = self._lib.dart_debug_lm_head_key(self._h, rows, int(multi_row), buf, 256)
+        if n < 0:
+            raise RuntimeError("dart_debug_lm_head_key failed")
+        return buf.value.decode()
+
     def debug_read(self, name: str, rows: int, cols: int) -> np.ndarray:
         buf = np.empty(16 * cols, dtype=np.float32)
         n = self._lib.dart_debug_read(self._h, name.encode(), buf.ctypes.data, buf.size)
         if n < 0:
             raise RuntimeError(f"dart_debug_read({name}) failed")
         return buf[: rows * cols].reshape(rows, cols).copy()
+
+
+def debug_stream_read(buf, workgroups: int = 2048, stream=None, non_temporal: bool = True):
+    """dart_debug_stream_read over a CUDA tensor (diagnostic: the box's streaming-read rate)."""
+    lib = load_library()
+    _check(lib.dart_debug_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), workgroups,
+                                      int(non_temporal), None, _stream_ptr(stream)), "dart_debug_stream_read")
 
 
 def topk_static(logits, k: int, eps: float = 1e-9, stream=None, out=None):

@@ -282,6 +282,11 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   }
   HIP_TRY(dev_alloc(&c->kv_part, (size_t)ch_qkv * c->kv_rows * 2 * c->kv_dim));
 
+  if (g.dtype == DART_BF16 && gemv_bf16_chunks(d) > 1) {
+    c->split_lm = gemv_bf16_chunks(d);
+    c->lm_stride = (size_t)round_up(g.vocab, 16);
+    HIP_TRY(dev_alloc(&c->lm_part, (size_t)c->split_lm * R * c->lm_stride));
+  }
   c->max_rows = g.max_batch * g.max_K;
   c->topk_chunks_max = topk_chunks(g.vocab);
   HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
@@ -322,6 +327,26 @@ hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows
   for (int m0 = 0; m0 < M; m0 += R)
     HIP_TRY(launch_gemv_f32(W, row0, nrows, X + (size_t)m0 * W.Kd, std::min(R, M - m0),
                             out + (size_t)m0 * out_stride, out_stride, st));
+  return hipSuccess;
+}
+
+// LM head (Sec. 3.2) on the final-normed rows X (null on the multi-row path: operand tiles
+// already packed).  The skinny kernel writes the caller's logits directly when d fits one
+// k-chunk; a longer d goes through chunk partials and one more pass that adds them.
+hipError_t lm_head(const dart_ctx *c, const float *X, int rows, bool gemm, float *logits,
+                   hipStream_t st) {
+  const int V = c->cfg.vocab;
+  int chunks = 1;
+  if (gemm || c->split_lm == 1 || c->cfg.dtype != DART_BF16)
+    return project(c, c->wlm, 0, V, X, rows, logits, V, 0, 1, gemm ? 1 : 0, &chunks, st);
+  const size_t cs = (size_t)DART_SKINNY_ROWS * c->lm_stride;
+  for (int m0 = 0; m0 < rows; m0 += DART_SKINNY_ROWS) {
+    const int m = std::min(DART_SKINNY_ROWS, rows - m0);
+    HIP_TRY(launch_gemv_bf16(c->wlm, 0, (V + 15) / 16, X + (size_t)m0 * c->cfg.d, m, c->lm_part,
+                             (int)c->lm_stride, cs, c->split_lm, &chunks, st));
+    HIP_TRY(launch_sum_chunks(c->lm_part, chunks, cs, (int)c->lm_stride, m, V,
+                              logits + (size_t)m0 * V, V, st));
+  }
   return hipSuccess;
 }
 
@@ -465,8 +490,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
                             gemm ? nullptr : c->u, gemm ? nullptr : c->yn, gemm ? c->xpack : nullptr,
                             gemm_bf16_terms(c->wlm), st));
-  HIP_TRY(project(c, c->wlm, 0, g.vocab, yn_in, QR, logits, g.vocab, 0, 1, gemm ? 1 : 0, &chunks, st));
-  return hipSuccess;
+  return lm_head(c, yn_in, QR, gemm, logits, st);
 }
 
 dart_status check_forward_args(const dart_ctx *c, int seq, const void *hidden, int n, int n_cached,
@@ -515,7 +539,6 @@ dart_status dart_create(const dart_config *cfg, const dart_weights *w, dart_ctx 
   }
   if (g.dtype == DART_BF16) {
     if (g.d % 32 || q_dim % 32 || g.ffn % 32) return DART_ERR_ARG;
-    if (gemv_bf16_chunks(g.d) != 1) return DART_ERR_ARG;   // LM head writes caller memory in one pass
   } else if (g.d % 8 || g.ffn % 4) {
     return DART_ERR_ARG;
   }
@@ -559,7 +582,7 @@ void dart_destroy(dart_ctx *c) {
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
-                  c->xn_kv, c->kv_part, c->xpack, c->xpack2, c->wfc.data, c->embed, c->g_emb, c->feat32,
+                  c->xn_kv, c->kv_part, c->lm_part, c->xpack, c->xpack2, c->wfc.data, c->embed, c->g_emb, c->feat32,
                   c->fc_part};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
@@ -823,9 +846,20 @@ dart_status dart_debug_lm_head(dart_ctx *c, int rows, int multi_row, float *logi
   if (multi_row == 2)      // contraction only: the operand tiles of the last LM-head call are reused
     return from_hip(launch_gemm_bf16(c->wlm, 0, (c->cfg.vocab + 15) / 16, nullptr, rows, c->xpack,
                                      logits_out, c->cfg.vocab, 0, 1, 0, (hipStream_t)stream));
-  int chunks = 1;
-  return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, rows, logits_out, c->cfg.vocab, 0, 1,
-                          multi_row ? 1 : 0, &chunks, (hipStream_t)stream));
+  if (multi_row) {
+    int chunks = 1;
+    return from_hip(project(c, c->wlm, 0, c->cfg.vocab, c->yn, rows, logits_out, c->cfg.vocab, 0, 1, 1,
+                            &chunks, (hipStream_t)stream));
+  }
+  return from_hip(lm_head(c, c->yn, rows, false, logits_out, (hipStream_t)stream));
+}
+
+// Diagnostic: which kernel, in which launch shape, dart_debug_lm_head runs.
+int dart_debug_lm_head_key(dart_ctx *c, int rows, int multi_row, char *buf, int len) {
+  if (!c || !buf || len < 1 || rows < 1 || c->cfg.dtype != DART_BF16) return -1;
+  const int nstrips = (c->cfg.vocab + 15) / 16;
+  if (multi_row) return gemm_bf16_describe(c->wlm, nstrips, rows, 1, 0, buf, len);
+  return gemv_bf16_describe(c->wlm, nstrips, rows, gemv_bf16_chunks(c->cfg.d), buf, len);
 }
 
 // Diagnostic: copy a named fp32 workspace of the last forward to host memory (synchronises).

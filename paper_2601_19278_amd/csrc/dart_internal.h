@@ -145,6 +145,11 @@ struct dart_ctx {
   float *att_out = nullptr;       // [ws_rows][q_dim]
   float *proj = nullptr;          // projection partial sums, [chunks][ws_rows][N] of the largest
   float *y = nullptr, *yn = nullptr, *hmid = nullptr, *u = nullptr;
+  // LM head of the single-sequence calls when d is too long for one k-chunk of the skinny
+  // kernel: chunk partials [split_lm][16][lm_stride], summed into the caller's logits
+  int split_lm = 1;
+  size_t lm_stride = 0;
+  float *lm_part = nullptr;
   // K/V-only passes (prefix rows that are not query rows): up to kv_rows rows per pass
   int kv_rows = 16;
   float *xn_kv = nullptr;         // [kv_rows][d]
@@ -218,6 +223,9 @@ hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const flo
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
                             hipStream_t st);
+int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char *buf, int len);
+int gemm_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nchunks, int epi, char *buf,
+                       int len);
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
 int gemv_bf16_split(int Kd, int nstrips);     // k-chunks that balance the workgroups (>= gemv_bf16_chunks)
 int gemv_bf16_row_tiles(int Kd, int nch);     // 16-row tiles one launch may carry per row block
@@ -239,6 +247,9 @@ hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipSt
 __host__ __device__ inline int gemm_chunk_begin(int KT, int nchunks, int c) {
   return c >= nchunks ? KT : (int)((int64_t)KT * c / nchunks) / 4 * 4;
 }
+
+hipError_t launch_sum_chunks(const float *part, int chunks, size_t chunk_stride, int row_stride,
+                             int rows, int n, float *out, int out_stride, hipStream_t st);
 
 hipError_t launch_swiglu(const float *gu, int chunks, size_t chunk_stride, int rows, int ffn,
                          int interleaved, float *h, hipStream_t st);

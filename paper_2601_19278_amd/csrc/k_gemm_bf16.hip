@@ -26,6 +26,7 @@
 // longer than 32 strips takes several passes over k.  The sum of a row is one chain per
 // k-chunk in k order (hi product, then lo product, per 32-input step), independent of the
 // number of rows and of the strip grouping; chunk partials are added by the consumer.
+#include <cstdio>
 #include <type_traits>
 
 #include "common.h"
@@ -395,6 +396,30 @@ size_t gemm_bf16_pack_bytes(int M, int Kd) {      // of the larger (two-term) fo
 // the packed activations must be in the matching format (gemm_bf16_terms).
 int gemm_bf16_terms(const DeviceMatrix &W) { return W.data16 ? 1 : 2; }
 
+// Row tiling and grid of a launch (shared with the diagnostic description below).
+static void gemm_shape(int nstrips, int M, int nchunks, GemmArgs *a, int *nct_out) {
+  const int nct = gemm_nct(M);
+  a->row_blocks = (M + 16 * nct - 1) / (16 * nct);
+  a->ntiles = a->row_blocks * nct;
+  // strip ranges: as many as fill the machine, but at least one strip per wavefront
+  const int groups_max = (nstrips + GEMM_WAVES - 1) / GEMM_WAVES;
+  a->ngroups = max(1, min(groups_max, g_gemm_wgs / (nchunks * a->row_blocks)));
+  const int gc = a->ngroups * nchunks;
+  a->units = (gc + 7) / 8 * 8 * a->row_blocks;
+  *nct_out = nct;
+}
+
+// "gemm_bf16_kernel<NCT,EPI,TERMS> grid=<workgroups>x512" of the launch that launch_gemm_bf16
+// makes for these arguments (diagnostics: keys the counter summaries).
+int gemm_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nchunks, int epi, char *buf,
+                       int len) {
+  GemmArgs a;
+  int nct = 0;
+  gemm_shape(nstrips, M, nchunks, &a, &nct);
+  return snprintf(buf, len, "gemm_bf16_kernel<%d,%d,%d> grid=%dx%d", nct, epi, gemm_bf16_terms(W),
+                  a.units, GEMM_THREADS);
+}
+
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
                             int epi, hipStream_t st, void *out_pack) {
@@ -413,9 +438,8 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   a.nstrips = nstrips;
   a.n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
   a.out_stride = out_stride;
-  const int nct = gemm_nct(M);
-  a.row_blocks = (M + 16 * nct - 1) / (16 * nct);
-  a.ntiles = a.row_blocks * nct;
+  int nct = 0;
+  gemm_shape(nstrips, M, nchunks, &a, &nct);
   a.out_pack = (uint16_t *)out_pack;
   a.out_ntiles = a.ntiles;                // the next projection carries the same rows
   const int ksteps = (a.KT + 1) / 2 * 2;
@@ -426,11 +450,6 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  // strip ranges: as many as fill the machine, but at least one strip per wavefront
-  const int groups_max = (nstrips + GEMM_WAVES - 1) / GEMM_WAVES;
-  a.ngroups = max(1, min(groups_max, g_gemm_wgs / (nchunks * a.row_blocks)));
-  const int gc = a.ngroups * nchunks;
-  a.units = (gc + 7) / 8 * 8 * a.row_blocks;
   const dim3 grid(a.units), block(GEMM_THREADS);
 #define DART_GEMM_GO(NCT_)                                                                        \
   do {                                                                                            \

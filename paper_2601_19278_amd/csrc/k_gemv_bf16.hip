@@ -22,6 +22,8 @@
 // (deterministic), one barrier per strip.  When the k range is too long for the register
 // budget the range is cut into chunks handled by different workgroups, and the consumer
 // adds the chunk partials (also in fixed order).
+#include <cstdio>
+
 #include "common.h"
 #include "dart_internal.h"
 
@@ -278,6 +280,55 @@ int gemv_bf16_row_tiles(int Kd, int nch) {
   return kpw <= 5 && exact_kpw_supported(kpw) ? 4 : 1;
 }
 
+// Launch shape and kernel variant for strips of a matrix, M rows, nch k-chunks.
+struct GemvPlan {
+  int kpw_t, d_t;       // template k-slice length and rolling-buffer depth
+  bool exact, nt;
+  int mt, kpw, nchunks, wgs, row_blocks;
+};
+
+static hipError_t gemv_plan(const DeviceMatrix &W, int nstrips, int M, int nch, GemvPlan *p) {
+  const int KT = W.Kd / 32;
+  if (nch < gemv_bf16_chunks(W.Kd)) return hipErrorInvalidValue;
+  p->nchunks = nch;
+  p->kpw = (KT + GEMV_WAVES * nch - 1) / (GEMV_WAVES * nch);
+  p->exact = p->kpw * GEMV_WAVES * nch == KT;
+  p->mt = M <= 8 ? 0 : 1;
+  p->row_blocks = 1;
+  if (M > 16) {
+    if (gemv_bf16_row_tiles(W.Kd, nch) < 2) return hipErrorInvalidValue;   // <= 16 rows per launch
+    p->mt = M > 32 ? 4 : 2;
+    p->row_blocks = (M + 16 * p->mt - 1) / (16 * p->mt);
+  }
+  int wgs = (nch == 1 ? g_gemv_wgs : g_gemv_wgs_split) / (nch * p->row_blocks);
+  p->wgs = max(1, min(wgs, nstrips));
+  p->nt = g_gemv_nt && (int64_t)nstrips * KT / 1024 >= g_gemv_nt_min_mb;
+  const int depth = g_gemv_depth, kpw = p->kpw;
+  const bool m8 = p->mt == 0;
+  if (p->exact && exact_kpw_supported(kpw)) {
+    p->kpw_t = kpw;
+    p->d_t = kpw;
+    if (kpw == 20 && (depth == 10 || (depth == 0 && !m8))) p->d_t = 10;
+    else if (kpw == 20 && depth == 5) p->d_t = 5;
+    else if (kpw == 16 && depth == 8) p->d_t = 8;
+  } else {
+    p->exact = false;
+    p->kpw_t = kpw <= 4 ? 4 : (kpw <= 8 ? 8 : (kpw <= 12 ? 12 : (kpw <= 16 ? 16 : 20)));
+    p->d_t = p->kpw_t <= 8 ? p->kpw_t : p->kpw_t / 2;
+  }
+  return hipSuccess;
+}
+
+// "gemv_bf16_kernel<KPW,D,MT,NT,EXACT> grid=<workgroups>x512" of the launch that
+// launch_gemv_bf16 makes for these arguments (diagnostics: keys the counter summaries).
+int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char *buf, int len) {
+  GemvPlan p;
+  if (gemv_plan(W, nstrips, M, nch, &p) != hipSuccess) return -1;
+  return snprintf(buf, len, "gemv_bf16_kernel<%d,%d,%d,%s,%s> grid=%dx%d", p.kpw_t, p.d_t, p.mt,
+                  p.nt ? "true" : "false", p.exact ? "true" : "false",
+                  p.wgs * p.nchunks * p.row_blocks, GEMV_THREADS);
+}
+
 // Strips [strip0, strip0+nstrips) of the packed matrix; out[chunk][m][j], j < nstrips*16
 // (columns beyond W.n_real - strip0*16 are not written).  nch: k-chunks (at least
 // gemv_bf16_chunks(Kd); 1 when the output must be complete in a single chunk).  M may exceed 16
@@ -285,61 +336,26 @@ int gemv_bf16_row_tiles(int Kd, int nch) {
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int nch, int *chunks,
                             hipStream_t st) {
-  const int KT = W.Kd / 32;
-  const int nchunks = nch;
-  if (nchunks < gemv_bf16_chunks(W.Kd)) return hipErrorInvalidValue;
-  const int kpw = (KT + GEMV_WAVES * nchunks - 1) / (GEMV_WAVES * nchunks);
-  const bool exact = kpw * GEMV_WAVES * nchunks == KT;
+  GemvPlan p;
+  hipError_t e = gemv_plan(W, nstrips, M, nch, &p);
+  if (e != hipSuccess) return e;
+  const int KT = W.Kd / 32, nchunks = p.nchunks, kpw = p.kpw, mt = p.mt;
   if (chunks) *chunks = nchunks;
   const int n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
-  int mt = M <= 8 ? 0 : 1, row_blocks = 1;
-  if (M > 16) {
-    const int cap = gemv_bf16_row_tiles(W.Kd, nchunks);
-    if (cap < 2) return hipErrorInvalidValue;          // caller must pass <= 16 rows per launch
-    mt = M > 32 ? 4 : 2;
-    row_blocks = (M + 16 * mt - 1) / (16 * mt);
-  }
-  int wgs = (nchunks == 1 ? g_gemv_wgs : g_gemv_wgs_split) / (nchunks * row_blocks);
-  if (wgs > nstrips) wgs = nstrips;
-  if (wgs < 1) wgs = 1;
-  dim3 grid(wgs * nchunks, row_blocks);
+  dim3 grid(p.wgs * nchunks, p.row_blocks);
   const u32x4_t *wp = (const u32x4_t *)W.data;
-  const int depth = g_gemv_depth;
-  const bool m8 = mt == 0;
-  const bool nt = g_gemv_nt && (int64_t)nstrips * KT / 1024 >= g_gemv_nt_min_mb;
+  const bool nt = p.nt;
 #define DART_GEMV_ARGS nt, mt, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
-  if (exact && kpw == 20) {
-    if (depth == 10 || (depth == 0 && !m8)) gemv_launch<20, 10, true>(DART_GEMV_ARGS);
-    else if (depth == 5) gemv_launch<20, 5, true>(DART_GEMV_ARGS);
-    else gemv_launch<20, 20, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 17) {
-    gemv_launch<17, 17, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 16) {
-    if (depth == 8) gemv_launch<16, 8, true>(DART_GEMV_ARGS);
-    else gemv_launch<16, 16, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 12) {
-    gemv_launch<12, 12, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 10) {
-    gemv_launch<10, 10, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 8) {
-    gemv_launch<8, 8, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 5) {
-    gemv_launch<5, 5, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 4) {
-    gemv_launch<4, 4, true>(DART_GEMV_ARGS);
-  } else if (exact && kpw == 2) {
-    gemv_launch<2, 2, true>(DART_GEMV_ARGS);
-  } else if (kpw <= 4) {
-    gemv_launch<4, 4, false>(DART_GEMV_ARGS);
-  } else if (kpw <= 8) {
-    gemv_launch<8, 8, false>(DART_GEMV_ARGS);
-  } else if (kpw <= 12) {
-    gemv_launch<12, 6, false>(DART_GEMV_ARGS);
-  } else if (kpw <= 16) {
-    gemv_launch<16, 8, false>(DART_GEMV_ARGS);
-  } else {
-    gemv_launch<20, 10, false>(DART_GEMV_ARGS);
-  }
+#define DART_GEMV_CASE(KPW_, D_, EX_) \
+  if (p.kpw_t == KPW_ && p.d_t == D_ && p.exact == EX_) gemv_launch<KPW_, D_, EX_>(DART_GEMV_ARGS); else
+  DART_GEMV_CASE(20, 20, true) DART_GEMV_CASE(20, 10, true) DART_GEMV_CASE(20, 5, true)
+  DART_GEMV_CASE(17, 17, true) DART_GEMV_CASE(16, 16, true) DART_GEMV_CASE(16, 8, true)
+  DART_GEMV_CASE(12, 12, true) DART_GEMV_CASE(10, 10, true) DART_GEMV_CASE(8, 8, true)
+  DART_GEMV_CASE(5, 5, true) DART_GEMV_CASE(4, 4, true) DART_GEMV_CASE(2, 2, true)
+  DART_GEMV_CASE(4, 4, false) DART_GEMV_CASE(8, 8, false) DART_GEMV_CASE(12, 6, false)
+  DART_GEMV_CASE(16, 8, false) DART_GEMV_CASE(20, 10, false)
+  return hipErrorInvalidValue;
+#undef DART_GEMV_CASE
 #undef DART_GEMV_ARGS
   return hipGetLastError();
 }

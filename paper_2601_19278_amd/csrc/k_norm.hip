@@ -274,6 +274,25 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float *__restrict__ g
   h[(size_t)r * ffn + f] = g / (1.0f + expf(-g)) * u;
 }
 
+// out[r][j] = sum_c part[c][r][j] (chunk partials of a projection, added in index order).
+__global__ __launch_bounds__(256) void sum_chunks_kernel(const float *__restrict__ part, int chunks,
+                                                         size_t chunk_stride, int row_stride, int n,
+                                                         float *__restrict__ out, int out_stride) {
+  const int r = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n) return;
+  float v = 0.f;
+  for (int c = 0; c < chunks; ++c) v += part[c * chunk_stride + (size_t)r * row_stride + j];
+  out[(size_t)r * out_stride + j] = v;
+}
+
+hipError_t launch_sum_chunks(const float *part, int chunks, size_t chunk_stride, int row_stride,
+                             int rows, int n, float *out, int out_stride, hipStream_t st) {
+  hipLaunchKernelGGL(sum_chunks_kernel, dim3((n + 255) / 256, rows), dim3(256), 0, st, part, chunks,
+                     chunk_stride, row_stride, n, out, out_stride);
+  return hipGetLastError();
+}
+
 void gemm_bf16_pack_shape(int M, int Kd, int *ntiles, int *ksteps);
 
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,

@@ -23,6 +23,11 @@ SMALL_BF16 = {
     # ffn long enough that the down projection is cut into k-chunks; 5 heads per K/V head; K 16
     "chunked": ds.scaled_config("C2", d=256, n_q_heads=5, n_kv_heads=1, head_dim=128, ffn=5632,
                                 vocab=2048, ctx=130, K=16),
+    # d beyond one k-chunk of the skinny kernel: the LM head goes through chunk partials
+    "long_d": ds.scaled_config("C2", d=8192, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=1024,
+                               vocab=3000, ctx=100, K=8),
+    "long_d_16rows": ds.scaled_config("C2", d=6144, n_q_heads=2, n_kv_heads=2, head_dim=64, ffn=512,
+                                      vocab=1000, ctx=40, K=12),
     # no q/k norm, 8 heads per K/V head (several query-tile groups), K 12
     "wide_group": ds.scaled_config("C2", d=1024, n_q_heads=8, n_kv_heads=1, head_dim=128, ffn=1024,
                                    vocab=4096, ctx=257, K=12, qk_norm=False),
