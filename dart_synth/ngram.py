@@ -163,3 +163,111 @@ def make_prune_case(seed: int, *, vocab: int, K: int, k: int, n_gram: int, S: in
         succ_counts[row, :used] = base_counts[:used]
     return PruneCase(ids.astype(np.int32), scores, ctx_tail,
                      NgramCounts(n_gram, keys, succ_ids, succ_counts))
+
+
+def make_bulk_trigram_counts(n_keys: int, S: int, vocab: int, seed: int) -> NgramCounts:
+    """A trigram count table of `n_keys` contexts built arithmetically, for tables far larger
+    than the presets' (2^24 contexts and more) where rejection sampling of Zipf contexts and a
+    Python-side index would take minutes.
+
+    Context r is the pair (p // vocab, p % vocab) of p = (r * mult + off) mod vocab^2 with mult
+    coprime to vocab^2, so all contexts are distinct and `bulk_row_of` finds the row of a
+    context without an index.  Successor j of row r is (a_r + j * s_r) mod vocab with s_r coprime
+    to vocab (distinct within the row); counts follow ceil(1000 (j+1)^-1.1) as in the presets.
+    """
+    import math
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 606])))
+    V2 = vocab * vocab
+    assert n_keys <= V2 and V2 < (1 << 36) and n_keys <= (1 << 26)
+    mult, off = _bulk_params(vocab, seed)
+    strides = np.array([s for s in range(3, 4 * vocab // 5, 2) if math.gcd(s, vocab) == 1][:4096],
+                       dtype=np.int64)
+    keys = np.empty((n_keys, 2), dtype=np.int32)
+    succ_ids = np.empty((n_keys, S), dtype=np.int32)
+    j = np.arange(S, dtype=np.int32)[None, :]      # j * s_r < 64 * vocab: int32 arithmetic suffices
+    step = 1 << 20
+    for r0 in range(0, n_keys, step):
+        r = np.arange(r0, min(n_keys, r0 + step), dtype=np.int64)
+        p = (r * mult + off) % V2
+        keys[r0:r0 + r.size, 0] = p // vocab
+        keys[r0:r0 + r.size, 1] = p % vocab
+        a = ((r * 2654435761 + seed) % vocab).astype(np.int32)
+        s = strides[(r * 40503 + 17) % strides.size].astype(np.int32)
+        block = succ_ids[r0:r0 + r.size]
+        np.multiply(j, s[:, None], out=block)
+        block += a[:, None]
+        block %= np.int32(vocab)
+    succ_counts = np.broadcast_to(_counts_row(S), (n_keys, S)).copy()
+    del rng
+    return NgramCounts(3, keys, succ_ids, succ_counts)
+
+
+def _bulk_params(vocab: int, seed: int):
+    import math
+    V2 = vocab * vocab
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 607])))
+    while True:
+        mult = int(rng.integers(1 << 20, 1 << 34))
+        if math.gcd(mult, V2) == 1:
+            break
+    return mult, int(rng.integers(0, V2))
+
+
+def bulk_row_of(n_keys: int, vocab: int, seed: int, prev: int, tok: int) -> int:
+    """Row of context (prev, tok) in make_bulk_trigram_counts(n_keys, ., vocab, seed), or -1."""
+    V2 = vocab * vocab
+    mult, off = _bulk_params(vocab, seed)
+    r = ((prev * vocab + tok - off) * pow(mult, -1, V2)) % V2
+    return int(r) if r < n_keys else -1
+
+
+def plant_prune_case(table: NgramCounts, n_keys: int, vocab: int, table_seed: int, seed: int, *,
+                     K: int, k: int, p_key: float = 0.5, p_succ: float = 0.5) -> PruneCase:
+    """A prune-only case whose contexts really hit a bulk table: candidate lists are drawn, and
+    for about `p_key` of the contexts a beam entry can present (tail; (root, level-0 candidate);
+    (candidate of level L-2, candidate of level L-1)) a row of the table is rewritten IN PLACE to
+    that context with about `p_succ` of the next level's candidates among its successors.  A
+    context that the bulk table already holds keeps its row (found with bulk_row_of).  Returns the
+    case; `table` is modified."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 608])))
+    S = table.succ_ids.shape[1]
+    ids = np.stack([rng.choice(vocab, size=k, replace=False) for _ in range(K)]).astype(np.int32)
+    gaps = rng.exponential(0.7, size=(K, k)) + 1e-3
+    scores = (-np.cumsum(gaps, axis=1)).astype(np.float32)
+    ctx_tail = rng.integers(0, vocab, size=2).astype(np.int32)
+    root = int(ctx_tail[1])
+    used_rows, planted = set(), set()
+    for L in range(K):
+        if L == 0:
+            ctxs = [(int(ctx_tail[0]), root)]
+        elif L == 1:
+            ctxs = [(root, int(b)) for b in ids[0]]
+        else:
+            ctxs = [(int(a), int(b)) for a in ids[L - 2] for b in ids[L - 1]]
+        for c in ctxs:
+            if c in planted or rng.random() >= p_key:
+                continue
+            planted.add(c)
+            row = bulk_row_of(n_keys, vocab, table_seed, *c)
+            if row < 0:                       # not a bulk context: take over a row not yet used
+                row = int(rng.integers(0, n_keys))
+                while row in used_rows:
+                    row = int(rng.integers(0, n_keys))
+                # the row's old context disappears, the new one must not exist elsewhere: it does
+                # not, since bulk_row_of found none and planted contexts are distinct
+                table.keys[row] = c
+            if row in used_rows:
+                continue
+            used_rows.add(row)
+            chosen = [int(t) for t in ids[L] if rng.random() < p_succ]
+            have = set(chosen)
+            for t in table.succ_ids[row]:
+                if len(chosen) == S:
+                    break
+                if int(t) not in have:
+                    have.add(int(t))
+                    chosen.append(int(t))
+            chosen = np.array(chosen[:S], dtype=np.int32)
+            rng.shuffle(chosen)
+            table.succ_ids[row] = chosen
+    return PruneCase(ids, scores, ctx_tail, table)

@@ -80,7 +80,7 @@ def test_c1_chain_many_seeds_and_determinism():
     table.close()
 
 
-@pytest.mark.parametrize("name", ["C2", "C4"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
 def test_full_size_chain_with_preset_table(name):
     """Whole step at a bf16 preset with its 2^20-context trigram table (random-init logits give
     near-uniform candidates, so most lookups miss; hits are covered by the planted prune cases)."""
@@ -95,5 +95,50 @@ def test_full_size_chain_with_preset_table(name):
     tail = counts.keys[123].astype(np.int32)       # a stored context: level 0 looks up a real row
     got = _chain(cfg, ctx, table, hidden, tail)
     _check_stages(cfg, W, model, hidden, tail, got, dict(atol=2e-2, rtol=1e-2))
+    ctx.close()
+    table.close()
+
+
+def test_c5_batched_full_size_chain_with_preset_table():
+    """Preset C5 as one chained batched step: dart_draft_forward_batched over 16 ragged sequences
+    -> dart_topk over the 128 logit rows -> dart_tree_prune over the 16 sequences with the
+    2^20-context trigram table.  Top-k and pruning are checked for every row and every tree on
+    the inputs those stages saw; the forward against the oracle on the shortest, the median and
+    the longest sequence (a full fp64 forward of all 16 would take minutes)."""
+    import torch
+    import paper_2601_19278_amd as dart
+    from dart_synth.tensors import make_ragged_lengths
+    cfg = ds.get_config("C5")
+    B, K, k = cfg.batch, cfg.K, cfg.topk
+    ctx, W = make_context(cfg, 9600)
+    counts = ds.make_ngram_counts(cfg, 9601)
+    table = dart.NgramTable(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
+    model = NgramModel(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
+    lens = make_ragged_lengths(cfg, 9602).tolist()
+    hiddens = [ds.make_hidden(cfg, 9603 + b, n=lens[b]) for b in range(B)]
+    devs = [hidden_to_device(cfg, h) for h in hiddens]
+    tails = np.ascontiguousarray(counts.keys[1000:1000 + B].astype(np.int32))   # stored contexts
+    logits = ctx.draft_forward_batched(devs, lens, [0] * B, K)
+    ids, scores = ctx.topk(logits.view(B * K, cfg.vocab), k, 1e-9)
+    params = dart.PruneParams(k=k, beam_w=cfg.beam_w, budget=cfg.budget)
+    tree = table.tree_prune(ids.view(B, K, k), scores.view(B, K, k), torch.from_numpy(tails).cuda(), params)
+    torch.cuda.synchronize()
+    logits, ids, scores = logits.cpu().numpy(), ids.cpu().numpy(), scores.cpu().numpy()
+    tokens, parents, mask, n_nodes = [t.cpu().numpy() for t in tree]
+    tol = dict(atol=2e-2, rtol=1e-2)
+    order = np.argsort(lens)
+    for b in (int(order[0]), int(order[B // 2]), int(order[-1])):
+        ok, msg = logits_close(logits[b], odf.draft_forward(cfg, W, hiddens[b], K), **tol)
+        assert ok, f"sequence {b} (n={lens[b]}): {msg}"
+    ref_ids, ref_scores = otk.topk_rows(logits.reshape(B * K, cfg.vocab), k, 1e-9)
+    np.testing.assert_array_equal(ids, ref_ids)
+    np.testing.assert_allclose(scores, ref_scores, rtol=0, atol=1e-5)
+    for b in range(B):
+        ref = otp.tree_prune(ids.reshape(B, K, k)[b], scores.reshape(B, K, k)[b], tails[b], model,
+                             otp.PruneParams(k=k, beam_w=cfg.beam_w, budget=cfg.budget))
+        assert int(n_nodes[b]) == ref.n_nodes, b
+        np.testing.assert_array_equal(tokens[b], ref.tokens)
+        np.testing.assert_array_equal(parents[b], ref.parents)
+        np.testing.assert_array_equal(mask[b], ref.mask)
     ctx.close()
     table.close()

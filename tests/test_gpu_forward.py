@@ -187,6 +187,34 @@ def test_batched_multi_row_kernel_matches_oracle_cold_and_warm(batch, K, over):
     ctx.close()
 
 
+def test_large_magnitude_hidden_states_without_qk_norm():
+    """Hidden states 1024 times larger than the presets' (and 1/1024 of them), q/k norm off: every
+    projection input is RMS-normalised, so the fp16 intermediates of the bf16 path (rotated q, the
+    K/V buffers, the packed operands of the batched call) stay in range and the logits stay within
+    tolerance, on both entry points."""
+    cfg = ds.scaled_config("C2", d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1536,
+                           vocab=4096, ctx=150, K=8, qk_norm=False, batch=3)
+    ctx, W = make_context(cfg, 2600)
+    for scale in (1024.0, 1.0 / 1024.0):
+        lens = [150, 40, 97]
+        hiddens = [ds.f32_to_bf16_bits(ds.bf16_bits_to_f32(ds.make_hidden(cfg, 2601 + b, n=lens[b])) * scale)
+                   for b in range(3)]
+        devs = [hidden_to_device(cfg, h) for h in hiddens]
+        refs = [odf.draft_forward(cfg, W, h, cfg.K) for h in hiddens]
+        for b in range(3):
+            ctx.reset(b)
+        single = ctx.draft_forward(devs[0], lens[0], cfg.K).cpu().numpy()
+        ok, msg = logits_close(single, refs[0], **BF16_TOL)
+        assert ok, (scale, msg)
+        for b in range(3):
+            ctx.reset(b)
+        out = ctx.draft_forward_batched(devs, lens, [0, 0, 0], cfg.K).cpu().numpy()
+        for b in range(3):
+            ok, msg = logits_close(out[b], refs[b], **BF16_TOL)
+            assert ok, (scale, b, msg)
+    ctx.close()
+
+
 def test_error_statuses():
     import torch
     import paper_2601_19278_amd as dart

@@ -176,3 +176,63 @@ def test_repeat_runs_are_bit_identical_and_errors():
         with pytest.raises(dart.DartError) as ei:
             _gpu_prune([case], bad)
         assert ei.value.status == 1
+
+
+def test_large_table_2_pow_24_contexts_with_planted_hits():
+    """A trigram table of 2^24 contexts x 64 successors (8 GiB of successor rows plus a 512 MiB hash
+    index in HBM), sixteen times the presets': trees bit-exact against the oracle on candidates whose contexts
+    really hit.  The table is built arithmetically (dart_synth.make_bulk_trigram_counts) and
+    rows are rewritten in place to the contexts the candidate lists can present.  The oracle's
+    model is built from the rows of exactly those possible contexts -- Alg. 1 can query no
+    other context, and a Python index over all 2^24 rows would take minutes."""
+    import time
+    import torch
+    import paper_2601_19278_amd as dart
+    V, S, K, k, B = 151936, 64, 8, 10, 4
+    n_keys = 1 << 24
+    t0 = time.time()
+    tab = ds.make_bulk_trigram_counts(n_keys, S, V, 4242)
+    cases = [ds.plant_prune_case(tab, n_keys, V, 4242, 4300 + b, K=K, k=k) for b in range(B)]
+    t1 = time.time()
+    table = dart.NgramTable(3, tab.keys, tab.succ_ids, tab.succ_counts, 1e-9)
+    t2 = time.time()
+    packed = tab.keys[:, 0].astype(np.int64) * V + tab.keys[:, 1]
+    params = dart.PruneParams(k=k, beam_w=20, budget=60)
+    ids = torch.from_numpy(np.stack([c.ids for c in cases])).cuda()
+    scores = torch.from_numpy(np.stack([c.scores for c in cases])).cuda()
+    tails = torch.from_numpy(np.stack([c.ctx_tail for c in cases])).cuda()
+    tokens, parents, mask, n_nodes = [t.cpu().numpy() for t in table.tree_prune(ids, scores, tails, params)]
+    hits = 0
+    for b, case in enumerate(cases):
+        possible = {(int(case.ctx_tail[0]), int(case.ctx_tail[1]))}
+        possible |= {(int(case.ctx_tail[1]), int(t)) for t in case.ids[0]}
+        for L in range(2, K):
+            possible |= {(int(a), int(t)) for a in case.ids[L - 2] for t in case.ids[L - 1]}
+        sel = np.isin(packed, np.array([a * V + t for a, t in possible], dtype=np.int64))
+        hits += int(sel.sum())
+        model = NgramModel(3, tab.keys[sel], tab.succ_ids[sel], tab.succ_counts[sel], 1e-9)
+        ref = otp.tree_prune(case.ids, case.scores, case.ctx_tail, model,
+                             otp.PruneParams(k=k, beam_w=20, budget=60))
+        assert int(n_nodes[b]) == ref.n_nodes
+        np.testing.assert_array_equal(tokens[b], ref.tokens)
+        np.testing.assert_array_equal(parents[b], ref.parents)
+        np.testing.assert_array_equal(mask[b], ref.mask)
+        # the N-gram term matters here: without the table the tree differs
+        empty = NgramModel(3, tab.keys[:0], tab.succ_ids[:0], tab.succ_counts[:0], 1e-9)
+        blind = otp.tree_prune(case.ids, case.scores, case.ctx_tail, empty,
+                               otp.PruneParams(k=k, beam_w=20, budget=60))
+        assert not np.array_equal(blind.tokens, ref.tokens)
+    assert hits >= B * 200                      # about half of the 611 possible contexts per case
+    # latency of the call against the table size (reported, not asserted)
+    out = table.tree_prune(ids, scores, tails, params)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(50):
+        table.tree_prune(ids, scores, tails, params, out=out)
+    ev[1].record()
+    torch.cuda.synchronize()
+    print(f"\n[large table] 2^24 contexts x {S} successors: host build {t1 - t0:.1f} s, "
+          f"dart_ngram_create {t2 - t1:.1f} s, {hits} contexts hit over {B} trees, "
+          f"dart_tree_prune (batch {B}) {ev[0].elapsed_time(ev[1]) * 20:.1f} us per call")
+    table.close()
