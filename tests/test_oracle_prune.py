@@ -65,6 +65,114 @@ def test_hand_derived_example(variant, w_ng):
     assert kept == {p for p, (_, keep) in expected.items() if keep}
 
 
+# ------------------------------------------------------------------ back-off (optional reading)
+def _backoff_hand_case(with_backoff):
+    A, B, C, D, P, R, X = 1, 2, 3, 4, 7, 0, 9
+    ids = np.array([[A, B], [C, D]], dtype=np.int32)
+    scores = np.log(np.array([[0.6, 0.3], [0.5, 0.2]])).astype(np.float32)
+    keys = np.array([[P, R], [R, B]], dtype=np.int32)
+    succ = np.array([[A, B, X], [C, D, -1]], dtype=np.int32)
+    cnt = np.array([[2, 1, 1], [1, 9, 0]], dtype=np.int32)
+    lower = NgramModel(2, np.array([[A]], np.int32), np.array([[C, X]], np.int32),
+                       np.array([[4, 1]], np.int32), 1e-9, discount=0.4) if with_backoff else None
+    names = {(A,): "A", (B,): "B", (A, C): "AC", (A, D): "AD", (B, C): "BC", (B, D): "BD"}
+    return ids, scores, np.array([P, R], np.int32), NgramModel(3, keys, succ, cnt, 1e-9, backoff=lower), names
+
+
+@pytest.mark.parametrize("variant", ["tri_plain", "tri_backoff"])
+def test_hand_derived_backoff_example(variant):
+    expected = {}
+    for line in open(GOLDEN):
+        if line.startswith(variant + " "):
+            _, path, score, kept = line.split()
+            expected[path] = (float(score), kept == "1")
+    assert len(expected) == 6
+    ids, scores, tail, ng, names = _backoff_hand_case(variant == "tri_backoff")
+    full = otp.tree_prune(ids, scores, tail, ng, PruneParams(k=2, beam_w=4, budget=7))
+    got = {names[p]: float(s) for p, s in otp.tree_paths(full)}
+    for path, (score, _) in expected.items():
+        assert abs(got[path] - score) < 6e-5, (path, got[path], score)
+    top4 = otp.tree_prune(ids, scores, tail, ng, PruneParams(k=2, beam_w=4, budget=5))
+    assert {names[p] for p, _ in otp.tree_paths(top4)} == {p for p, (_, keep) in expected.items() if keep}
+
+
+def test_backoff_scores_and_precedence():
+    keys = np.array([[5, 6]], dtype=np.int32)
+    main_ids, main_cnt = np.array([[10, 11]], np.int32), np.array([[3, 1]], np.int32)
+    low = NgramModel(2, np.array([[6], [8]], np.int32), np.array([[10, 12], [13, -1]], np.int32),
+                     np.array([[1, 3], [5, 0]], np.int32), 1e-9, discount=0.25)
+    ng = NgramModel(3, keys, main_ids, main_cnt, 1e-9, backoff=low)
+    row = ng.lookup((5, 6))                       # stored: never backs off, although (6) exists below
+    np.testing.assert_allclose(row[10], math.log(0.75), rtol=1e-6)
+    assert 12 not in row and ng.score(row, 12) == ng.miss
+    row = ng.lookup((9, 6))                       # unseen: the context without its oldest token
+    np.testing.assert_allclose(row[10], math.log(0.25 * 0.25), rtol=1e-6)
+    np.testing.assert_allclose(row[12], math.log(0.25 * 0.75), rtol=1e-6)
+    row = ng.lookup((6, 8))                       # drops the OLDEST token: (8), not (6)
+    np.testing.assert_allclose(row[13], math.log(0.25), rtol=1e-6)
+    assert ng.lookup((1, 2)) is None              # unseen in both: log eps as before
+    plain = NgramModel(3, keys, main_ids, main_cnt, 1e-9)
+    assert plain.lookup((9, 6)) is None           # off by default
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_empty_trigram_table_with_undiscounted_backoff_is_the_bigram_model(seed):
+    """Every trigram lookup misses and falls to the bigram table with alpha = 1: the tree must be
+    the one a plain bigram model gives for the same candidates (the context loses its oldest
+    token, nothing else changes)."""
+    K, k = 4, 3
+    pc = ds.make_prune_case(300 + seed, vocab=64, K=K, k=k, n_gram=2, S=8, n_filler_keys=8)
+    bigram = NgramModel(2, pc.table.keys, pc.table.succ_ids, pc.table.succ_counts, 1e-9)
+    empty3 = NgramModel(3, np.zeros((0, 2), np.int32), np.zeros((0, 8), np.int32),
+                        np.zeros((0, 8), np.int32), 1e-9,
+                        backoff=NgramModel(2, pc.table.keys, pc.table.succ_ids, pc.table.succ_counts, 1e-9))
+    tail3 = np.array([17, int(pc.ctx_tail[0])], np.int32)
+    for w, budget in ((2, 9), (27, 30)):
+        params = PruneParams(k=k, beam_w=w, budget=budget)
+        a = otp.tree_prune(pc.ids, pc.scores, pc.ctx_tail, bigram, params)
+        b = otp.tree_prune(pc.ids, pc.scores, tail3, empty3, params)
+        np.testing.assert_array_equal(a.tokens, b.tokens)
+        np.testing.assert_array_equal(a.parents, b.parents)
+        np.testing.assert_array_equal(a.scores, b.scores)
+        assert a.n_nodes == b.n_nodes
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_backoff_keeps_the_invariants_and_is_idle_when_every_context_is_stored(seed):
+    K, k = 4, 3
+    pc, ng = _case(400 + seed, K=K, k=k, n_gram=3)
+    lowc = ds.make_prune_case(500 + seed, vocab=64, K=K, k=k, n_gram=2, S=8, n_filler_keys=40)
+    # bigram rows for the trigram case's own candidates, so that back-off really hits
+    low_keys = np.unique(np.concatenate([pc.ids[:-1].ravel(), pc.ctx_tail[-1:]]))[:, None].astype(np.int32)
+    low_ids = np.stack([np.resize(np.random.default_rng(seed + i).permutation(pc.ids[min(K - 1, 1 + i % (K - 1))]), 8)
+                        for i in range(low_keys.shape[0])]).astype(np.int32)
+    low_ids[:, k:] = -1
+    low_cnt = (low_ids >= 0).astype(np.int32) * np.arange(1, 9, dtype=np.int32)[None, :]
+    low = NgramModel(2, low_keys, low_ids, low_cnt, 1e-9, discount=0.4)
+    both = NgramModel(3, pc.table.keys, pc.table.succ_ids, pc.table.succ_counts, 1e-9, backoff=low)
+    params = PruneParams(k=k, beam_w=4, budget=20)
+    tree = otp.tree_prune(pc.ids, pc.scores, pc.ctx_tail, both, params)
+    _check_invariants(tree, pc, both, params, K)
+    plain = otp.tree_prune(pc.ids, pc.scores, pc.ctx_tail, ng, params)
+    assert not np.array_equal(tree.scores, plain.scores)      # back-off changed some score
+    # a main table that stores every context the candidates can present never consults it
+    ctxs = {tuple(int(t) for t in pc.ctx_tail)} | {(int(pc.ctx_tail[1]), int(t)) for t in pc.ids[0]}
+    for L in range(2, K):
+        ctxs |= {(int(a), int(t)) for a in pc.ids[L - 2] for t in pc.ids[L - 1]}
+    have = {tuple(int(t) for t in key) for key in pc.table.keys}
+    extra = sorted(ctxs - have)
+    keys2 = np.concatenate([pc.table.keys, np.array(extra, np.int32).reshape(-1, 2)])
+    ids2 = np.concatenate([pc.table.succ_ids, np.full((len(extra), 8), -1, np.int32)])
+    cnt2 = np.concatenate([pc.table.succ_counts, np.zeros((len(extra), 8), np.int32)])
+    ids2[len(pc.table.keys):, 0], cnt2[len(pc.table.keys):, 0] = 63, 1      # a successor no level proposes
+    full_plain = NgramModel(3, keys2, ids2, cnt2, 1e-9)
+    full_both = NgramModel(3, keys2, ids2, cnt2, 1e-9, backoff=low)
+    a = otp.tree_prune(pc.ids, pc.scores, pc.ctx_tail, full_plain, params)
+    b = otp.tree_prune(pc.ids, pc.scores, pc.ctx_tail, full_both, params)
+    np.testing.assert_array_equal(a.tokens, b.tokens)
+    np.testing.assert_array_equal(a.scores, b.scores)
+
+
 def test_combine_is_the_printed_formula_in_fp32_without_fma():
     p = PruneParams(k=1, beam_w=1, budget=2)
     s_logit, s_ng = f32(-1.2345678), f32(-7.654321)
