@@ -10,13 +10,13 @@ from .configs import DraftConfig, CONFIGS, get_config, scaled_config
 from .tensors import (f32_to_bf16_bits, bf16_bits_to_f32, make_weights,
                       make_hidden, make_frontend_weights, make_features, WEIGHT_NAMES)
 from .ngram import (make_ngram_counts, make_prune_case, make_bulk_trigram_counts, bulk_row_of,
-                    plant_prune_case, NgramCounts, PruneCase)
+                    plant_prune_case, make_backoff_counts, NgramCounts, PruneCase)
 
 __all__ = [
     "DraftConfig", "CONFIGS", "get_config", "scaled_config",
     "f32_to_bf16_bits", "bf16_bits_to_f32", "make_weights", "make_hidden",
     "make_frontend_weights", "make_features",
     "WEIGHT_NAMES", "make_ngram_counts", "make_prune_case", "make_bulk_trigram_counts",
-    "bulk_row_of", "plant_prune_case", "NgramCounts",
+    "bulk_row_of", "plant_prune_case", "make_backoff_counts", "NgramCounts",
     "PruneCase",
 ]

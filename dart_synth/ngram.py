@@ -271,3 +271,43 @@ def plant_prune_case(table: NgramCounts, n_keys: int, vocab: int, table_seed: in
             rng.shuffle(chosen)
             table.succ_ids[row] = chosen
     return PruneCase(ids, scores, ctx_tail, table)
+
+
+def make_backoff_counts(case: PruneCase, seed: int, *, vocab: int, S: int, p_key: float = 0.6,
+                        p_succ: float = 0.5, n_filler_keys: int = 64) -> NgramCounts:
+    """A bigram count table to go with a trigram prune case as its back-off: for about `p_key` of
+    the tokens that can be the newest token of a context (the root and the candidates of every
+    level but the last) a row is planted holding about `p_succ` of the next level's candidates
+    plus filler; `n_filler_keys` unrelated rows are added.  Same row format as the main table."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 707])))
+    K, k = case.ids.shape
+    rows = {}                                   # newest token -> level whose candidates follow it
+    rows_for = [(int(case.ctx_tail[-1]), 0)] + [(int(t), L + 1) for L in range(K - 1) for t in case.ids[L]]
+    for tok, L in rows_for:
+        if tok not in rows and rng.random() < p_key:
+            rows[tok] = L
+    while n_filler_keys > 0:
+        tok = int(rng.integers(0, vocab))
+        if tok not in rows:
+            rows[tok] = -1
+            n_filler_keys -= 1
+    n = len(rows)
+    keys = np.empty((n, 1), dtype=np.int32)
+    succ_ids = np.full((n, S), -1, dtype=np.int32)
+    succ_counts = np.zeros((n, S), dtype=np.int32)
+    base = _counts_row(S)
+    for r, (tok, L) in zip(rng.permutation(n), rows.items()):
+        keys[r, 0] = tok
+        used = int(rng.integers(1, S + 1)) if rng.random() < 0.3 else S
+        chosen = [int(t) for t in case.ids[L] if rng.random() < p_succ][:used] if L >= 0 else []
+        have = set(chosen)
+        while len(chosen) < used:
+            t = int(rng.integers(0, vocab))
+            if t not in have:
+                have.add(t)
+                chosen.append(t)
+        chosen = np.array(chosen, dtype=np.int32)
+        rng.shuffle(chosen)
+        succ_ids[r, :used] = chosen
+        succ_counts[r, :used] = base[:used]
+    return NgramCounts(2, keys, succ_ids, succ_counts)

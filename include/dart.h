@@ -218,7 +218,8 @@ dart_status dart_topk_static(const float *logits, int rows, int vocab, int k, fl
  *               count is positive (ids of unused slots are ignored)
  *   succ_counts [n_keys][succ_per_key] int32 >= 0, 0 marks an unused slot
  * Stored score of a successor: min(0, log(count / sum(row counts) + eps)) rounded
- * to fp32; an absent context or successor scores log(eps).  No back-off.
+ * to fp32; an absent context or successor scores log(eps).  No back-off unless
+ * dart_ngram_set_backoff attaches a lower-order table.
  * Errors: ARG (NULL, n_gram not 2 or 3, succ_per_key not in 1..64, a negative context token,
  * a duplicate context, a negative count, a used successor with a negative id or repeated
  * within its row, n_keys > 2^30), OOM, HIP. */
@@ -226,6 +227,20 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int succ_per_key, cons
                               const int32_t *succ_ids, const int32_t *succ_counts, float eps,
                               dart_ngram **out);
 void dart_ngram_destroy(dart_ngram *t);
+
+/* Optional one-level back-off (the paper's N-gram store is a trie, App. C.2, and is silent on
+ * contexts it has not seen; without this call they score log(eps)).  Attaches to a trigram
+ * table a bigram table of the same succ_per_key, built from HOST arrays laid out as for
+ * dart_ngram_create (keys [n_keys][1]): when dart_tree_prune finds no row for a context
+ * (t_-2, t_-1) it looks up (t_-1) here, and a successor found scores
+ * min(0, log(alpha * count / sum(row counts) + eps)), eps being the table's.  A stored context
+ * never backs off (its unseen successors keep log(eps)).  0 < alpha <= 1 is the discount of
+ * the shorter context.  A table attached earlier is replaced and freed; the call must not
+ * overlap with a dart_tree_prune that uses `table`.
+ * Errors: ARG (NULL table, table not a trigram table, alpha out of range, bad rows as in
+ * dart_ngram_create), OOM, HIP. */
+dart_status dart_ngram_set_backoff(dart_ngram *table, int64_t n_keys, const int32_t *keys,
+                                   const int32_t *succ_ids, const int32_t *succ_counts, float alpha);
 
 /* Continuity-aware tree pruning (Alg. 1, App. D) for `batch` independent
  * sequences, one workgroup each.

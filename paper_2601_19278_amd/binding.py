@@ -14,6 +14,7 @@ EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
     "dart_draft_forward_features", "dart_draft_forward_features_batched",
     "dart_draft_forward_batched", "dart_topk", "dart_topk_static", "dart_ngram_create", "dart_ngram_destroy",
+    "dart_ngram_set_backoff",
     "dart_tree_prune", "dart_tree_verify_greedy",
 )
 # include/dart_debug.h: diagnostics for this repository's tests and benchmark, not product API
@@ -94,6 +95,7 @@ def load_library() -> C.CDLL:
     lib.dart_topk.argtypes = [vp, vp, i32, i32, i32, f32, vp, vp, vp]
     lib.dart_topk_static.argtypes = [vp, i32, i32, i32, f32, vp, vp, vp]
     lib.dart_ngram_create.argtypes = [i32, i64, i32, vp, vp, vp, f32, C.POINTER(vp)]
+    lib.dart_ngram_set_backoff.argtypes = [vp, i64, vp, vp, vp, f32]
     lib.dart_ngram_destroy.argtypes = [vp]
     lib.dart_ngram_destroy.restype = None
     lib.dart_tree_prune.argtypes = [i32, vp, vp, i32, vp, vp, C.POINTER(_PruneParams), vp, vp, vp,
@@ -331,6 +333,16 @@ class NgramTable:
                                      succ_counts.ctypes.data, eps, C.byref(handle)),
                "dart_ngram_create")
         self._h, self._lib = handle, lib
+
+    def set_backoff(self, keys, succ_ids, succ_counts, alpha: float):
+        """dart_ngram_set_backoff: attach a bigram table (keys [n][1]) consulted for trigram
+        contexts this table lacks, with discount alpha."""
+        keys = np.ascontiguousarray(keys, dtype=np.int32)
+        succ_ids = np.ascontiguousarray(succ_ids, dtype=np.int32)
+        succ_counts = np.ascontiguousarray(succ_counts, dtype=np.int32)
+        _check(self._lib.dart_ngram_set_backoff(self._h, keys.shape[0], keys.ctypes.data,
+                                                succ_ids.ctypes.data, succ_counts.ctypes.data, alpha),
+               "dart_ngram_set_backoff")
 
     def close(self):
         if getattr(self, "_h", None):

@@ -676,18 +676,14 @@ dart_status dart_topk(dart_ctx *c, const float *logits, int rows, int vocab, int
                               (hipStream_t)stream));
 }
 
-dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *keys,
-                              const int32_t *succ_ids, const int32_t *succ_counts, float eps,
-                              dart_ngram **out) {
-  if (!out) return DART_ERR_ARG;
-  *out = nullptr;
-  if ((n_gram != 2 && n_gram != 3) || n_keys < 0 || S < 1 || S > 64) return DART_ERR_ARG;
-  if (n_keys > 0 && (!keys || !succ_ids || !succ_counts)) return DART_ERR_ARG;
-  if (n_keys > ((int64_t)1 << 30)) return DART_ERR_ARG;
-  const int ctx_len = n_gram - 1;
+// Host arrays of one hashed table -> device.  ctx_len tokens per context; stored score of a
+// successor = min(0, log(scale * count / sum(row counts) + eps)) in fp64, rounded once.
+static dart_status build_table(int ctx_len, int64_t n_keys, int S, const int32_t *keys,
+                               const int32_t *succ_ids, const int32_t *succ_counts, double eps_d,
+                               double scale, void **d_slots, void **d_ids, void **d_logp,
+                               uint64_t *slot_mask, float *miss_out) {
   for (int64_t i = 0; i < n_keys * ctx_len; ++i)
     if (keys[i] < 0) return DART_ERR_ARG;
-
   uint64_t n_slots = 16;
   while (n_slots < (uint64_t)n_keys * 2) n_slots <<= 1;
   std::vector<NgramSlot> slots(n_slots, NgramSlot{~(uint64_t)0, -1, 0});
@@ -703,8 +699,6 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
     slots[h].key = packed;
     slots[h].row = (int32_t)r;
   }
-  // s_ng = log(Pr + eps), Pr = count / sum of the row's counts (App. D); fp64 then one rounding
-  const double eps_d = (double)eps;
   const float miss = std::fmin(0.0f, (float)std::log(eps_d));
   const size_t cells = (size_t)std::max<int64_t>(n_keys, 1) * S;
   std::vector<int32_t> ids(cells, -1);
@@ -738,7 +732,7 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
         const int32_t cnt = succ_counts[r * S + j];
         if (cnt <= 0) continue;
         ids[r * S + j] = succ_ids[r * S + j];
-        logp[r * S + j] = std::fmin(0.0f, (float)std::log((double)cnt / (double)total + eps_d));
+        logp[r * S + j] = std::fmin(0.0f, (float)std::log(scale * (double)cnt / (double)total + eps_d));
       }
     }
   };
@@ -751,30 +745,78 @@ dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *
     for (int i = 0; i < nthr; ++i)
       if (bad[i]) return DART_ERR_ARG;
   }
-  dart_ngram *t = new (std::nothrow) dart_ngram();
-  if (!t) return DART_ERR_OOM;
-  hipError_t e = upload(slots.data(), n_slots * sizeof(NgramSlot), &t->slots);
-  if (e == hipSuccess) e = upload(ids.data(), cells * 4, &t->succ_ids);
-  if (e == hipSuccess) e = upload(logp.data(), cells * 4, &t->succ_logp);
+  hipError_t e = upload(slots.data(), n_slots * sizeof(NgramSlot), d_slots);
+  if (e == hipSuccess) e = upload(ids.data(), cells * 4, d_ids);
+  if (e == hipSuccess) e = upload(logp.data(), cells * 4, d_logp);
   if (e != hipSuccess) {
     (void)hipGetLastError();
-    dart_ngram_destroy(t);
+    for (void **q : {d_slots, d_ids, d_logp}) {
+      if (*q) (void)hipFree(*q);
+      *q = nullptr;
+    }
     return from_hip(e);
   }
+  *slot_mask = n_slots - 1;
+  *miss_out = miss;
+  return DART_OK;
+}
+
+dart_status dart_ngram_create(int n_gram, int64_t n_keys, int S, const int32_t *keys,
+                              const int32_t *succ_ids, const int32_t *succ_counts, float eps,
+                              dart_ngram **out) {
+  if (!out) return DART_ERR_ARG;
+  *out = nullptr;
+  if ((n_gram != 2 && n_gram != 3) || n_keys < 0 || S < 1 || S > 64) return DART_ERR_ARG;
+  if (n_keys > 0 && (!keys || !succ_ids || !succ_counts)) return DART_ERR_ARG;
+  if (n_keys > ((int64_t)1 << 30)) return DART_ERR_ARG;
+  dart_ngram *t = new (std::nothrow) dart_ngram();
+  if (!t) return DART_ERR_OOM;
+  std::memset(&t->dev, 0, sizeof t->dev);
+  // s_ng = log(Pr + eps), Pr = count / sum of the row's counts (App. D)
+  dart_status s = build_table(n_gram - 1, n_keys, S, keys, succ_ids, succ_counts, (double)eps, 1.0,
+                              &t->slots, &t->succ_ids, &t->succ_logp, &t->dev.slot_mask,
+                              &t->dev.logp_miss);
+  if (s != DART_OK) {
+    delete t;
+    return s;
+  }
+  t->eps = eps;
   t->dev.n_gram = n_gram;
   t->dev.S = S;
-  t->dev.slot_mask = n_slots - 1;
   t->dev.slots = (const NgramSlot *)t->slots;
   t->dev.succ_ids = (const int32_t *)t->succ_ids;
   t->dev.succ_logp = (const float *)t->succ_logp;
-  t->dev.logp_miss = miss;
   *out = t;
+  return DART_OK;
+}
+
+dart_status dart_ngram_set_backoff(dart_ngram *t, int64_t n_keys, const int32_t *keys,
+                                   const int32_t *succ_ids, const int32_t *succ_counts, float alpha) {
+  if (!t) return DART_ERR_ARG;
+  if (t->dev.n_gram != 3) return DART_ERR_ARG;            // the shorter context is one token
+  if (n_keys < 0 || n_keys > ((int64_t)1 << 30)) return DART_ERR_ARG;
+  if (n_keys > 0 && (!keys || !succ_ids || !succ_counts)) return DART_ERR_ARG;
+  if (!(alpha > 0.0f) || !(alpha <= 1.0f)) return DART_ERR_ARG;
+  void *slots = nullptr, *ids = nullptr, *logp = nullptr;
+  uint64_t mask = 0;
+  float miss = 0.f;
+  dart_status s = build_table(1, n_keys, t->dev.S, keys, succ_ids, succ_counts, (double)t->eps,
+                              (double)alpha, &slots, &ids, &logp, &mask, &miss);
+  if (s != DART_OK) return s;
+  // a table already attached is replaced; no kernel may be using it (see the header)
+  for (void *q : {t->bo_slots, t->bo_succ_ids, t->bo_succ_logp})
+    if (q) (void)hipFree(q);
+  t->bo_slots = slots, t->bo_succ_ids = ids, t->bo_succ_logp = logp;
+  t->dev.bo_slots = (const NgramSlot *)slots;
+  t->dev.bo_slot_mask = mask;
+  t->dev.bo_succ_ids = (const int32_t *)ids;
+  t->dev.bo_succ_logp = (const float *)logp;
   return DART_OK;
 }
 
 void dart_ngram_destroy(dart_ngram *t) {
   if (!t) return;
-  void *bufs[] = {t->slots, t->succ_ids, t->succ_logp};
+  void *bufs[] = {t->slots, t->succ_ids, t->succ_logp, t->bo_slots, t->bo_succ_ids, t->bo_succ_logp};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
   delete t;

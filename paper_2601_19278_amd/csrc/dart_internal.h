@@ -37,11 +37,21 @@ struct NgramTableDev {
   const int32_t *succ_ids;    // [n_keys][S], -1 = unused
   const float *succ_logp;     // [n_keys][S]
   float logp_miss;
+  // optional back-off table of order n_gram - 1 (same S; scores already carry the discount):
+  // consulted with the context's newest n_gram - 2 tokens when the full context has no row.
+  // Rows found there are reported with NGRAM_BACKOFF_ROW set.
+  const NgramSlot *bo_slots;  // null = no back-off
+  uint64_t bo_slot_mask;
+  const int32_t *bo_succ_ids;
+  const float *bo_succ_logp;
 };
+#define NGRAM_BACKOFF_ROW (1 << 30)   // row indices are < 2^30
 
 struct dart_ngram {
   NgramTableDev dev;
+  float eps = 0.f;
   void *slots = nullptr, *succ_ids = nullptr, *succ_logp = nullptr;
+  void *bo_slots = nullptr, *bo_succ_ids = nullptr, *bo_succ_logp = nullptr;
 };
 
 struct PruneLevelWeights {

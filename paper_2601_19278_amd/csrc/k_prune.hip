@@ -97,23 +97,51 @@ __device__ __forceinline__ uint4 slot_load(const NgramTableDev &tab, uint64_t h)
   return *reinterpret_cast<const uint4 *>(tab.slots + h);          // one 16-byte access
 }
 
-// Finish a lookup whose first slot `raw` (at index h) has already been fetched: row of the
-// packed context, or -1.  Linear probing; the table is at most half full and the probe
-// count is bounded by the table size, so the loop always ends.
-__device__ int32_t ngram_resolve(const NgramTableDev &tab, uint64_t packed, uint64_t h, uint4 raw) {
-  for (uint64_t probes = 0; probes <= tab.slot_mask; ++probes) {
+// Linear probing from slot h whose content `raw` has already been fetched: row of the packed
+// context, or -1.  A table is at most half full and the probe count is bounded by its size,
+// so the loop always ends.
+__device__ int32_t ngram_probe(const NgramSlot *slots, uint64_t mask, uint64_t packed, uint64_t h,
+                               uint4 raw) {
+  for (uint64_t probes = 0; probes <= mask; ++probes) {
     const uint64_t kk = ((uint64_t)raw.y << 32) | raw.x;
     if (kk == packed) return (int32_t)raw.z;
     if (kk == ~(uint64_t)0) return -1;
-    h = (h + 1) & tab.slot_mask;
-    raw = slot_load(tab, h);
+    h = (h + 1) & mask;
+    raw = *reinterpret_cast<const uint4 *>(slots + h);
   }
   return -1;
 }
 
-__device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed) {
+// Back-off (optional): the context without its oldest token, in the lower-order table.  Only a
+// trigram table can carry one, so the shorter context is the newest token alone.
+__device__ int32_t ngram_backoff_find(const NgramTableDev &tab, int tok) {
+  if (!tab.bo_slots) return -1;
+  const uint64_t packed = (uint64_t)(uint32_t)tok;
+  const uint64_t h = mix64(packed) & tab.bo_slot_mask;
+  const int32_t row = ngram_probe(tab.bo_slots, tab.bo_slot_mask, packed, h,
+                                  *reinterpret_cast<const uint4 *>(tab.bo_slots + h));
+  return row < 0 ? -1 : (row | NGRAM_BACKOFF_ROW);
+}
+
+// Finish a lookup of context (.., tok) whose first slot `raw` (at index h) has already been
+// fetched: its row, else its back-off row (flagged), else -1.
+__device__ int32_t ngram_resolve(const NgramTableDev &tab, uint64_t packed, uint64_t h, uint4 raw, int tok) {
+  const int32_t row = ngram_probe(tab.slots, tab.slot_mask, packed, h, raw);
+  return row >= 0 ? row : ngram_backoff_find(tab, tok);
+}
+
+__device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed, int tok) {
   const uint64_t h = mix64(packed) & tab.slot_mask;
-  return ngram_resolve(tab, packed, h, slot_load(tab, h));
+  return ngram_resolve(tab, packed, h, slot_load(tab, h), tok);
+}
+
+// Successor ids and scores of a row as a lookup reported it.
+__device__ __forceinline__ void ngram_row(const NgramTableDev &tab, int32_t row, const int32_t *&ids,
+                                          const float *&logp) {
+  const bool bo = (row & NGRAM_BACKOFF_ROW) != 0;
+  const size_t at = (size_t)(row & (NGRAM_BACKOFF_ROW - 1)) * tab.S;
+  ids = (bo ? tab.bo_succ_ids : tab.succ_ids) + at;
+  logp = (bo ? tab.bo_succ_logp : tab.succ_logp) + at;
 }
 
 __device__ __forceinline__ int key_level(uint64_t key) { return 15 - (int)((key >> 28) & 0xF); }
@@ -179,8 +207,11 @@ __device__ __forceinline__ void score_rows(PruneShared &sh, const NgramTableDev 
     const int b = idx / S, j = idx - b * S;
     const int row = sh.beam_row[b];
     if (row >= 0) {
-      const int32_t id = tab.succ_ids[(size_t)row * S + j];
-      const float lp = tab.succ_logp[(size_t)row * S + j];
+      const int32_t *rid;
+      const float *rlp;
+      ngram_row(tab, row, rid, rlp);
+      const int32_t id = rid[j];
+      const float lp = rlp[j];
       const int c = cand_find(sh, L, H, k, id);
       if (c >= 0) sh.ng[b * k + c] = lp;
     }
@@ -249,6 +280,7 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
   constexpr int Q = (PRUNE_NG_CTX + PRUNE_THREADS - 1) / PRUNE_THREADS;
   uint64_t packed[Q], hslot[Q];
   uint4 raw[Q];
+  int newest[Q];
 #pragma unroll
   for (int q = 0; q < Q; ++q) {
     const int g = t + q * PRUNE_THREADS;
@@ -272,6 +304,7 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
         prev = sh.cand_id[(L - 2) * k + idx / k], tok = sh.cand_id[(L - 1) * k + idx % k];
       }
       packed[q] = pack_context(ctx_len, prev, tok);
+      newest[q] = tok;
       hslot[q] = mix64(packed[q]) & tab.slot_mask;
       raw[q] = slot_load(tab, hslot[q]);
     }
@@ -280,7 +313,7 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
   for (int q = 0; q < Q; ++q) {
     const int g = t + q * PRUNE_THREADS;
     if (g < NC) {
-      const int row = ngram_resolve(tab, packed[q], hslot[q], raw[q]);
+      const int row = ngram_resolve(tab, packed[q], hslot[q], raw[q], newest[q]);
       sh.ctx_row[g] = row;
       if (row >= 0) {
         const int L = g == 0 ? 0
@@ -313,9 +346,11 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
         const int item = min(i0 + u * PRUNE_THREADS, total - 1);
         const int hi = (int)(((uint32_t)item * inv) >> 20), piece = item - hi * parts;
         hc[u] = sh.hit_ctx[hi];
-        const size_t at = (size_t)sh.ctx_row[hc[u] & 0xFFFF] * S + 4 * piece;
-        id4[u] = *reinterpret_cast<const int4 *>(tab.succ_ids + at);
-        lp4[u] = *reinterpret_cast<const float4 *>(tab.succ_logp + at);
+        const int32_t *rid;
+        const float *rlp;
+        ngram_row(tab, sh.ctx_row[hc[u] & 0xFFFF], rid, rlp);
+        id4[u] = *reinterpret_cast<const int4 *>(rid + 4 * piece);
+        lp4[u] = *reinterpret_cast<const float4 *>(rlp + 4 * piece);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -358,9 +393,11 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
     for (int item = t; item < n_hit * S; item += PRUNE_THREADS) {
       const int hcx = sh.hit_ctx[item / S];
       const int g = hcx & 0xFFFF, L = hcx >> 16;
-      const size_t at = (size_t)sh.ctx_row[g] * S + item % S;
-      const int32_t id = tab.succ_ids[at];
-      const float lp = tab.succ_logp[at];
+      const int32_t *rid;
+      const float *rlp;
+      ngram_row(tab, sh.ctx_row[g], rid, rlp);
+      const int32_t id = rid[item % S];
+      const float lp = rlp[item % S];
       const int c = cand_find(sh, L, H, k, id);
       if (c >= 0) sh.ng[g * k + c] = lp;
     }
@@ -401,7 +438,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     sh.beam_cre[0][0] = -1;                    // the root
     sh.beam_ci[0][0] = 0;
     sh.beam_pi[0][0] = 0;
-    if (!pre) sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev0, root));
+    if (!pre) sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev0, root), root);
   }
   int nb = 1, n_best = 0, cur = 0, bcur = 0;
   __syncthreads();
@@ -678,7 +715,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
       }
       // beam_row of this level was last read before the barriers above: safe to overwrite
       if (owner && !last && !pre && r < nb_next)
-        sh.beam_row[r] = ngram_resolve(tab, packed, hslot, raw);
+        sh.beam_row[r] = ngram_resolve(tab, packed, hslot, raw, tok);
     } else {
       // General path (up to 4096 expansions): bitonic sort of the keys in LDS.
       int P = 2, logP = 1;
@@ -719,7 +756,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           sh.beam_cre[nxt][t] = e;
           sh.beam_ci[nxt][t] = c;
           sh.beam_pi[nxt][t] = sh.beam_ci[cur][b];
-          if (!last && !pre) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk));
+          if (!last && !pre) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk), tk);
         }
         if (t < n_lvl) {
           sh.lvl_key[0][t] = kk;

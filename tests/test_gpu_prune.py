@@ -62,6 +62,67 @@ def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
         _compare(case, model, params, tokens[0], parents[0], mask[0], n_nodes[0])
 
 
+@pytest.mark.parametrize("K,k,w,budget,S,p_key", [
+    (8, 10, 20, 60, 64, 0.5),     # presets' shape: every possible context resolved up front
+    (8, 25, 20, 60, 64, 0.5),     # paper defaults: level-by-level lookups
+    (6, 30, 40, 128, 32, 0.3),    # more than 1024 expansions per level: the sorted path
+    (8, 8, 32, 128, 7, 0.0),      # no trigram row at all: every lookup backs off; odd row length
+    (3, 2, 1, 2, 8, 0.5),
+])
+def test_backoff_to_the_bigram_table_matches_oracle(K, k, w, budget, S, p_key):
+    """dart_ngram_set_backoff: trigram contexts the table lacks are looked up without their oldest
+    token in a discounted bigram table.  Trees bit-exact against the oracle's model with the same
+    back-off; the back-off must also matter (the tree differs from the plain table's)."""
+    import torch
+    import paper_2601_19278_amd as dart
+    params = otp.PruneParams(k=k, beam_w=w, budget=budget)
+    gp = dart.PruneParams(k=k, beam_w=w, budget=budget)
+    changed = 0
+    for seed in range(8):
+        case = ds.make_prune_case(7700 + seed, vocab=151936, K=K, k=k, n_gram=3, S=S, p_key=p_key)
+        low = ds.make_backoff_counts(case, 7750 + seed, vocab=151936, S=S)
+        alpha = (0.4, 1.0, 0.05)[seed % 3]
+        table = dart.NgramTable(3, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
+        ids, scores = torch.from_numpy(case.ids).cuda(), torch.from_numpy(case.scores).cuda()
+        tail = torch.from_numpy(case.ctx_tail).cuda()
+        plain = [t.cpu().numpy() for t in table.tree_prune(ids, scores, tail, gp)]
+        table.set_backoff(low.keys, low.succ_ids, low.succ_counts, alpha)
+        got = [t.cpu().numpy() for t in table.tree_prune(ids, scores, tail, gp)]
+        lower = NgramModel(2, low.keys, low.succ_ids, low.succ_counts, 1e-9, discount=alpha)
+        model = NgramModel(3, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9,
+                           backoff=lower)
+        _compare(case, model, params, *got)
+        _compare(case, NgramModel(3, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9),
+                 params, *plain)
+        changed += not np.array_equal(got[0], plain[0])
+        table.close()
+    assert changed >= (4 if K > 3 else 0)
+
+
+def test_backoff_argument_checks():
+    import paper_2601_19278_amd as dart
+    case = ds.make_prune_case(7790, vocab=1000, K=3, k=2, n_gram=3, S=8)
+    low = ds.make_backoff_counts(case, 7791, vocab=1000, S=8)
+    table = dart.NgramTable(3, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
+    for alpha in (0.0, -1.0, 1.5, float("nan")):
+        with pytest.raises(dart.DartError) as ei:
+            table.set_backoff(low.keys, low.succ_ids, low.succ_counts, alpha)
+        assert ei.value.status == 1
+    dup = low.succ_ids.copy()
+    dup[0, 1] = dup[0, 0]
+    with pytest.raises(dart.DartError):
+        table.set_backoff(low.keys, dup, np.ones_like(low.succ_counts), 0.4)
+    table.set_backoff(low.keys, low.succ_ids, low.succ_counts, 0.4)
+    table.set_backoff(low.keys, low.succ_ids, low.succ_counts, 0.5)         # replaces the first
+    table.close()
+    big = ds.make_prune_case(7792, vocab=1000, K=3, k=2, n_gram=2, S=8)
+    t2 = dart.NgramTable(2, big.table.keys, big.table.succ_ids, big.table.succ_counts, 1e-9)
+    with pytest.raises(dart.DartError) as ei:                                # bigram tables carry none
+        t2.set_backoff(low.keys, low.succ_ids, low.succ_counts, 0.4)
+    assert ei.value.status == 1
+    t2.close()
+
+
 def test_batch_of_sequences_shares_one_table():
     K, k = 8, 10
     params = otp.PruneParams(k=k, beam_w=20, budget=60)
