@@ -229,6 +229,10 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
     if (g.max_ctx > R && gemv_bf16_row_tiles(in_dim, c->split_qkv) >= 4 &&
         (!g.front_end || gemv_bf16_row_tiles(g.feat_dim, c->split_fc) >= 4))
       c->kv_rows = std::min(1024, round_up(g.max_ctx, 64));
+    // the many-row kernel that keeps the skinny kernel's sums takes the whole cold prefix in
+    // passes of up to 4096 rows (512 workgroup units: two per compute unit)
+    c->kv_ordered = !g.front_end && g.max_ctx > 32 && gemm_ordered_supported(c->wqkv, c->split_qkv);
+    if (c->kv_ordered) c->kv_rows = std::min(4096, round_up(g.max_ctx, 64));
     if (g.max_batch > 1) {     // the batched entry point runs on the multi-row kernel
       c->gch_qkv = gemm_bf16_chunks(in_dim, c->qkv_dim / 16);
       c->gch_o = gemm_bf16_chunks(c->q_dim, (d + 15) / 16);
@@ -384,6 +388,14 @@ hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid,
 hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int M = sb.row_off[sb.B];
+  if (!gemm && c->kv_ordered && M > 32) {
+    // single-sequence call, many rows: the input norm writes two-term operand tiles, the
+    // order-preserving many-row kernel gives the skinny kernel's K/V sums bit for bit
+    HIP_TRY(launch_norm_pack_rows(sb, c->mask_emb, c->g_in, g.d, g.rms_eps, c->xn_kv, c->xpack, st));
+    HIP_TRY(launch_gemm_ordered(c->wqkv, c->q_dim / 16, 2 * c->kv_dim / 16, M, c->xpack, c->kv_part,
+                                2 * c->kv_dim, c->split_qkv, st));
+    return launch_qkv_post(c, sb, c->kv_part, 1, 0, 2 * c->kv_dim, c->q_dim, st);
+  }
   HIP_TRY(input_stage(c, sb, c->xn_kv, nullptr, gemm, st));
   const size_t cs = (size_t)c->kv_rows * 2 * c->kv_dim;
   int chunks = 1;
@@ -873,6 +885,7 @@ int dart_debug_set(const char *name, int value) {
   else if (!strcmp(name, "gemv_nt_min_mb")) g_gemv_nt_min_mb = value;
   else if (!strcmp(name, "gemv_split")) g_gemv_split = value;
   else if (!strcmp(name, "gemm_wgs")) g_gemm_wgs = value < 1 ? 1 : value;
+  else if (!strcmp(name, "gemm_ord_map")) g_gemm_ord_map = value;
   else if (!strcmp(name, "attn_seg")) g_attn_seg = value < 0 ? 0 : (value > 64 ? 64 : value);
   else return -1;
   return 0;

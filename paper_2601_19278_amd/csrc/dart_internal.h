@@ -162,6 +162,7 @@ struct dart_ctx {
   float *lm_part = nullptr;
   // K/V-only passes (prefix rows that are not query rows): up to kv_rows rows per pass
   int kv_rows = 16;
+  bool kv_ordered = false;        // single-sequence K/V-only passes of many rows run on gemm_ordered_kernel
   float *xn_kv = nullptr;         // [kv_rows][d]
   float *kv_part = nullptr;       // [chunks][kv_rows][2*kv_dim]
   int split_qkv = 1, split_o = 1, split_gu = 1, split_down = 1;   // k-chunks per matrix (skinny kernel)
@@ -196,7 +197,7 @@ __host__ __device__ inline uint64_t mix64(uint64_t x) {
 #else
 #define DART_TUNABLE const
 #endif
-extern DART_TUNABLE int g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs, g_attn_seg;
+extern DART_TUNABLE int g_gemm_ord_map, g_gemv_xcd, g_gemv_wgs_split, g_gemv_wgs, g_gemv_depth, g_gemv_nt, g_gemv_nt_min_mb, g_gemv_split, g_gemm_wgs, g_attn_seg;
 
 // Raise a kernel's dynamic-LDS limit: a per-device property of the function, set the first time
 // the function is launched on each device (thread-safe; a race only repeats the idempotent call).
@@ -209,6 +210,9 @@ hipError_t raise_dynamic_lds_once(const void *func, int bytes);
 hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask_emb,
                                  const void *gain, int d, float eps, float *xn, float *resid,
                                  void *pack, int terms, hipStream_t st);
+
+hipError_t launch_norm_pack_rows(const SeqBatch &sb, const void *mask_emb, const void *gain, int d,
+                                 float eps, float *rstd, void *pack, hipStream_t st);
 
 // Front end, step 1: the feature rows of a pass as fp32 (mask rows: zeros).
 hipError_t launch_feature_rows(int dtype, const SeqBatch &sb, int feat_dim, float *out, hipStream_t st);
@@ -249,6 +253,10 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
                             int epi, hipStream_t st,
                             void *out_pack = nullptr);
 int gemm_bf16_chunks(int Kd, int nstrips);
+// Many rows with the skinny kernel's sums, bit for bit (the K/V build of a long prefix).
+bool gemm_ordered_supported(const DeviceMatrix &W, int nch);
+hipError_t launch_gemm_ordered(const DeviceMatrix &W, int strip0, int nstrips, int M, const void *pack,
+                               float *out, int out_stride, int nch, hipStream_t st);
 size_t gemm_bf16_pack_bytes(int M, int Kd);
 int gemm_bf16_terms(const DeviceMatrix &W);   // format of the packed activations W's launches expect
 hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipStream_t st);

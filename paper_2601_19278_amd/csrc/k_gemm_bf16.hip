@@ -344,6 +344,199 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   }
 }
 
+// ---- Many-row projection that reproduces the skinny kernel's sums bit for bit ----
+//
+// The K/V build of a long prefix (a cold call: thousands of rows against Wk, Wv; Sec. 3.2) must
+// leave in the K/V buffers exactly what a later warm call would compute for the same row with
+// the skinny kernel, since cached rows and new rows are mixed freely.  The skinny kernel's sum
+// for an output element is, per k-chunk, eight k-slices (one per wavefront) of `kpw` k-steps,
+// each slice one chain of hi products and one chain of lo products starting from zero; the
+// slices' hi sums and lo sums are added in slice order, then hi + lo, and the consumer adds the
+// chunks in order.  Here one wavefront owns an output tile for the whole k range and walks the
+// slices one after the other: slice accumulators (hi, lo) are flushed into chunk totals every
+// kpw k-steps, chunk totals into the final sum every 8 kpw k-steps, each in the same order of
+// additions.  The same MFMA with the same operands in the same chain gives the same bits, so
+// the result equals the skinny kernel's (tests compare cold and warm calls bit for bit).  No
+// partial sums leave the kernel.
+//
+// A workgroup takes 64 rows (4 row tiles) x 16 strips (2 per wavefront): 20 accumulator
+// registers per (strip, row tile) pair fit that shape; the activations (two-term packed tiles)
+// go through the same LDS ring as above, the weights stream from L2 (units that share strips
+// run on one XCD at the same time).
+template <int NCT, int SP>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_ordered_kernel(GemmArgs a, int kpw, int map) {
+  // ring of four LDS stages (16 KiB each at 4 row tiles): a stage is copied three stages before
+  // it is read, so a stage may take less time than the latency of its copy
+  constexpr int TERMS = 2, NS = 4, LA = NS - 1;
+  static_assert(sizeof(GemmStage<NCT, TERMS>) * NS <= 64 * 1024, "static LDS");
+  __shared__ GemmStage<NCT, TERMS> ring[NS];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  // unit -> (strip group, row block): all row blocks of a strip group run on one XCD (unit u
+  // runs on XCD u % 8), so that XCD's L2 serves the group's weights to every one of them
+  int group, rb;
+  {
+    const int u = blockIdx.x, x = u % 8, j = u / 8;
+    if (map == 1) {            // XCD x: row blocks x, x + 8, ..., the strip groups of one together
+      rb = x + 8 * (j / a.ngroups);
+      group = j % a.ngroups;
+    } else if (map == 0) {     // XCD x: strip groups x, x + 8, ..., the row blocks of one together
+      group = x + 8 * (j / a.row_blocks);
+      rb = j % a.row_blocks;
+    } else {
+      group = u / a.row_blocks;
+      rb = u % a.row_blocks;
+    }
+  }
+  if (group >= a.ngroups || rb >= a.row_blocks) return;
+  const int g0 = group * GEMM_WAVES * SP, g1 = min(a.nstrips, g0 + GEMM_WAVES * SP);
+  const int P = g1 - g0;
+  const int per = (P + GEMM_WAVES - 1) / GEMM_WAVES;              // strips per wavefront (<= SP)
+  const int sfirst = min(g0 + wave * per, g1 - 1);
+  const int ns = max(0, min(per, P - wave * per));
+  const int KT = a.KT;                                             // even, = nchunks * 8 * kpw
+
+  const u32x4_t *wrow[SP];
+#pragma unroll
+  for (int s = 0; s < SP; ++s) {
+    const int strip = a.strip0 + sfirst + (s < ns ? s : 0);
+    wrow[s] = a.Wp + (size_t)strip * KT * 64;
+  }
+  auto tile_off = [&](int kstep) { return (uint32_t)(min(kstep, KT - 1) * 64 + lane) * 16u; };
+  constexpr int NT = GEMM_KS * NCT * TERMS;
+  static_assert(NT % GEMM_WAVES == 0, "uniform copies per wavefront");
+  constexpr int TPW = NT / GEMM_WAVES;
+  const u32x4_t *xbase = a.Xp + (size_t)rb * NCT * 64 * TERMS;
+  const uint32_t xstep = (uint32_t)a.ntiles * 1024u * TERMS;
+  auto stage_copy = [&](int kstage, GemmStage<NCT, TERMS> *dst) {
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+      const int tile = wave + GEMM_WAVES * i;
+      const int u = tile / (NCT * TERMS), c2 = tile % (NCT * TERMS);
+      copy_tile_to_lds_async((uint32_t)(uintptr_t)(lptr_t)&dst->t[u][c2][0],
+                             (uint32_t)(kstage + u) * xstep + (uint32_t)(c2 * 64 + lane) * 16u, xbase);
+    }
+  };
+
+  // slice accumulators, chunk totals, final sums
+  f32x4_t ahi[SP][NCT], alo[SP][NCT], thi[SP][NCT], tlo[SP][NCT], sum[SP][NCT];
+  const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < SP; ++s)
+#pragma unroll
+    for (int c = 0; c < NCT; ++c) ahi[s][c] = alo[s][c] = thi[s][c] = tlo[s][c] = sum[s][c] = zero;
+
+  constexpr int PD = 8 / SP;                 // weight ring depth in k-steps
+  constexpr int UNR = 8;                     // k-steps per unrolled body (multiple of PD and of the stage ring)
+  static_assert(UNR % PD == 0 && (UNR / GEMM_KS) % NS == 0, "static ring slots");
+  u32x4_t aop[PD][SP];
+  const int klast = KT - GEMM_KS;
+  // prologue: the first LA stages, then the weight tiles of the first PD k-steps in the pattern
+  // the loop issues them (the copies of that pattern just repeat the last of the LA stages), so
+  // that the counted waits hold from the first k-step on
+#pragma unroll
+  for (int j = 0; j < LA; ++j) stage_copy(min(j * GEMM_KS, klast), &ring[j]);
+#pragma unroll
+  for (int p = 0; p < PD; ++p) {
+    if (p % GEMM_KS == 0) stage_copy(min((LA - 1) * GEMM_KS, klast), &ring[LA - 1]);
+#pragma unroll
+    for (int s = 0; s < SP; ++s) {
+      aop[p][s] = u32x4_t{0, 0, 0, 0};
+      load_tile_async(aop[p][s], tile_off(p), wrow[s]);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(GEMM_KS * SP) : "memory");
+
+  int in_slice = 0, in_chunk = 0;            // k-steps done of the current slice / slices of the chunk
+  auto stage_body = [&](int t0, auto jtag) {
+    constexpr int J = decltype(jtag)::value;
+    GemmStage<NCT, TERMS> *cur = &ring[(J / GEMM_KS) % NS];
+    stage_copy(min(t0 + LA * GEMM_KS, klast), &ring[(J / GEMM_KS + LA) % NS]);
+#pragma unroll
+    for (int u = 0; u < GEMM_KS; ++u) {
+      const int slot = (J + u) % PD;
+      wait_tiles<(PD - 1) * SP + (PD / 2) * TPW, SP>(aop[slot]);
+#pragma unroll
+      for (int hl = 0; hl < TERMS; ++hl) {
+        u32x4_t b[NCT];
+#pragma unroll
+        for (int c = 0; c < NCT; ++c) b[c] = cur->t[u][TERMS * c + hl][lane];
+#pragma unroll
+        for (int s = 0; s < SP; ++s)
+#pragma unroll
+          for (int c = 0; c < NCT; ++c) {
+            f32x4_t &acc = hl == 0 ? ahi[s][c] : alo[s][c];
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, aop[slot][s]),
+                                                          __builtin_bit_cast(bf16x8_t, b[c]), acc, 0, 0, 0);
+          }
+      }
+      const uint32_t off = tile_off(t0 + u + PD);
+#pragma unroll
+      for (int s = 0; s < SP; ++s) load_tile_async(aop[slot][s], off, wrow[s]);
+      // end of a k-slice: its sums join the chunk totals (hi and lo apart, slice order); end of
+      // a k-chunk: hi + lo joins the final sum (chunk order).  Uniform branches, no memory.
+      if (++in_slice == kpw) {
+        in_slice = 0;
+#pragma unroll
+        for (int s = 0; s < SP; ++s)
+#pragma unroll
+          for (int c = 0; c < NCT; ++c) {
+            thi[s][c] += ahi[s][c];
+            tlo[s][c] += alo[s][c];
+            ahi[s][c] = zero;
+            alo[s][c] = zero;
+          }
+        if (++in_chunk == GEMM_WAVES) {
+          in_chunk = 0;
+#pragma unroll
+          for (int s = 0; s < SP; ++s)
+#pragma unroll
+            for (int c = 0; c < NCT; ++c) {
+              sum[s][c] += thi[s][c] + tlo[s][c];
+              thi[s][c] = zero;
+              tlo[s][c] = zero;
+            }
+        }
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LA * GEMM_KS * SP + (LA - 1) * TPW)
+                 : "memory");
+  };
+  for (int t0 = 0; t0 < KT; t0 += UNR) {
+    stage_body(t0, std::integral_constant<int, 0>{});
+    if (t0 + 2 < KT) stage_body(t0 + 2, std::integral_constant<int, 2>{});
+    if constexpr (UNR == 8) {
+      if (t0 + 4 < KT) stage_body(t0 + 4, std::integral_constant<int, 4>{});
+      if (t0 + 6 < KT) stage_body(t0 + 6, std::integral_constant<int, 6>{});
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  const int j = lane & 15, i4 = (lane >> 4) * 4;
+  const int m0 = rb * 16 * NCT;
+#pragma unroll
+  for (int s = 0; s < SP; ++s) {
+    if (s < ns) {
+      const int col = (sfirst + s) * 16 + i4;
+#pragma unroll
+      for (int c = 0; c < NCT; ++c) {
+        const int m = m0 + 16 * c + j;
+        if (m < a.M) {
+          const f32x4_t v = sum[s][c];
+          float *dst = a.out + (size_t)m * a.out_stride + col;
+          if (col + 3 < a.n_cols && (a.out_stride & 3) == 0) {
+            *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (col + r < a.n_cols) dst[r] = v[r];
+          }
+        }
+      }
+    }
+  }
+}
+
 // fp16 copy of a matrix of packed bf16 tiles (same tile layout: both are 16-bit operands of a
 // 16x16x32 MFMA).  bf16 -> fp16 is exact for 2^-14 <= |w| < 65520; smaller weights round to
 // fp16 subnormals (absolute error <= 2^-25), larger ones saturate.
@@ -362,6 +555,7 @@ hipError_t launch_tiles_to_f16(const void *src, void *dst, size_t n_elems, hipSt
 }
 
 DART_TUNABLE int g_gemm_wgs = 256;      // resident workgroups: one per compute unit
+DART_TUNABLE int g_gemm_ord_map = 1;    // unit-to-XCD map of gemm_ordered_kernel, see there
 
 // k-chunks of a matrix on this path: fixed per matrix so that a row's sums do not depend on
 // the call.  Matrices with few strips are cut along k until (strip ranges of 8 strips, one per
@@ -466,6 +660,45 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   else if (nct == 4) DART_GEMM_GO(4);
   else DART_GEMM_GO(8);
 #undef DART_GEMM_GO
+  return hipGetLastError();
+}
+
+// Can the order-preserving many-row kernel serve this matrix cut into nch k-chunks of the skinny
+// kernel?  It needs whole k-slices (KT = nch * 8 * kpw) and an even number of k-steps.
+bool gemm_ordered_supported(const DeviceMatrix &W, int nch) {
+  const int KT = W.Kd / 32;
+  return nch >= 1 && KT % 2 == 0 && KT % (GEMM_WAVES * nch) == 0 && KT >= 8;
+}
+
+// out[m][j] (row stride out_stride) = the skinny kernel's result for strips [strip0, strip0+nstrips)
+// of W with nch k-chunks, chunk partials already added; pack: two-term operand tiles of the M rows
+// (gemm_bf16_pack_shape(M, Kd) row tiles, written by the input norm).
+hipError_t launch_gemm_ordered(const DeviceMatrix &W, int strip0, int nstrips, int M, const void *pack,
+                               float *out, int out_stride, int nch, hipStream_t st) {
+  if (M < 1 || nstrips < 1 || !gemm_ordered_supported(W, nch)) return hipErrorInvalidValue;
+  constexpr int NCT = 4, SP = 2;
+  GemmArgs a{};
+  a.Wp = (const u32x4_t *)W.data;
+  a.Xp = (const u32x4_t *)pack;
+  a.out = out;
+  a.M = M;
+  a.KT = W.Kd / 32;
+  a.strip0 = strip0;
+  a.nstrips = nstrips;
+  a.n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
+  a.out_stride = out_stride;
+  int ntiles = 0, ksteps = 0;
+  gemm_bf16_pack_shape(M, W.Kd, &ntiles, &ksteps);
+  if (ntiles % NCT != 0) return hipErrorInvalidValue;
+  a.ntiles = ntiles;
+  a.row_blocks = (M + 16 * NCT - 1) / (16 * NCT);
+  a.ngroups = (nstrips + GEMM_WAVES * SP - 1) / (GEMM_WAVES * SP);
+  int map = g_gemm_ord_map;
+  if (map == 1) a.units = 8 * ((a.row_blocks + 7) / 8) * a.ngroups;
+  else if (map == 0) a.units = 8 * ((a.ngroups + 7) / 8) * a.row_blocks;
+  else a.units = a.ngroups * a.row_blocks;
+  const int kpw = a.KT / (GEMM_WAVES * nch);
+  hipLaunchKernelGGL((gemm_ordered_kernel<NCT, SP>), dim3(a.units), dim3(GEMM_THREADS), 0, st, a, kpw, map);
   return hipGetLastError();
 }
 

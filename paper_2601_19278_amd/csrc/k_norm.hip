@@ -84,6 +84,86 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_gather_kernel(
   }
 }
 
+// The input norm of many rows (the K/V build of a long prefix) in two steps, so that the packed
+// operand tiles are written as whole 1 KiB tiles: row_rstd_kernel computes 1/rms of every pass
+// row exactly as rmsnorm_gather_kernel does (same thread-to-column map, same reduction order:
+// the two must agree bit for bit, since rows normed by either end up in one K/V buffer), and
+// pack_norm_tiles_kernel forms (x * rstd) * gain per element -- again the same arithmetic -- and
+// writes the two-term tiles, one tile pair per wavefront store.
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void row_rstd_kernel(SeqBatch sb, const T *__restrict__ mask_emb,
+                                                              int d, float eps, float *__restrict__ rstd) {
+  __shared__ float red[16];
+  const int i = blockIdx.x;
+  int b, pos, qi;
+  seq_of_row(sb, i, b, pos, qi);
+  const int n = sb.n[b];
+  const T *src = pos < n ? (const T *)sb.hidden[b] + (size_t)pos * d : mask_emb + (size_t)(pos - n) * d;
+  float v[ROW_MAXIT][8];
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j) {
+    const int c = (j * ROW_THREADS + threadIdx.x) * 8;
+    if (c < d) load8(src + c, v[j]);
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < ROW_MAXIT; ++j)
+    if ((j * ROW_THREADS + threadIdx.x) * 8 < d)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += v[j][e] * v[j][e];
+  ss = block_sum(ss, red);
+  if (threadIdx.x == 0) rstd[i] = 1.0f / sqrtf(ss / (float)d + eps);
+}
+
+// grid (row tiles, ceil(k-steps / 16)), 8 wavefronts, each two adjacent k-steps of its row tile:
+// lane (gq, col) owns inputs 32 t + 8 gq .. + 7 of row 16 tile + col, the lane's 16 bytes of the
+// hi tile and of the lo tile.  Rows beyond the pass and k-steps beyond d are written as zeros.
+template <typename T>
+__global__ __launch_bounds__(ROW_THREADS) void pack_norm_tiles_kernel(
+    SeqBatch sb, const T *__restrict__ mask_emb, const T *__restrict__ gain,
+    const float *__restrict__ rstd, int d, int ntiles, int ksteps, uint4 *__restrict__ pack) {
+  const int tile = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = tile * 16 + (lane & 15), gq = lane >> 4;
+  const bool row_ok = r < sb.row_off[sb.B];
+  const T *src = nullptr;
+  float rs = 0.f;
+  if (row_ok) {
+    int b, pos, qi;
+    seq_of_row(sb, r, b, pos, qi);
+    const int n = sb.n[b];
+    src = pos < n ? (const T *)sb.hidden[b] + (size_t)pos * d : mask_emb + (size_t)(pos - n) * d;
+    rs = rstd[r];
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int t = (blockIdx.y * 8 + wave) * 2 + u;
+    if (t >= ksteps) continue;
+    const int c = t * 32 + 8 * gq;
+    uint4 *dst = pack + ((size_t)t * ntiles + tile) * 128 + lane;      // two-term format
+    if (row_ok && c < d) {
+      float v[8], g[8];
+      load8(src + c, v);
+      load8(gain + c, g);
+      uint32_t h[4], l[4];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = v[e] * rs * g[e];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bf16_t h0 = f32_to_bf16(v[2 * e]), h1 = f32_to_bf16(v[2 * e + 1]);
+        const bf16_t l0 = f32_to_bf16(v[2 * e] - bf16_to_f32(h0));
+        const bf16_t l1 = f32_to_bf16(v[2 * e + 1] - bf16_to_f32(h1));
+        h[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        l[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+      }
+      dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
+      dst[64] = make_uint4(l[0], l[1], l[2], l[3]);
+    } else {
+      dst[0] = make_uint4(0, 0, 0, 0);
+      dst[64] = make_uint4(0, 0, 0, 0);
+    }
+  }
+}
+
 // Front end (Sec. 3.2): the concatenated target hidden states of the pass rows as fp32, the
 // input format of the FC projection.  Mask rows have no features: zeros (their FC output is
 // not used).  One workgroup per row.
@@ -313,6 +393,22 @@ hipError_t launch_rmsnorm_gather(int dtype, const SeqBatch &sb, const void *mask
     hipLaunchKernelGGL(rmsnorm_gather_kernel<float>, dim3(grid), dim3(ROW_THREADS), 0, st, sb,
                        (const float *)mask_emb, (const float *)gain, d, eps, xn, resid,
                        (uint4 *)nullptr, 0, 0, 2);
+  return hipGetLastError();
+}
+
+// Normed rows of a K/V-only pass as two-term operand tiles (bf16 storage only); rstd: scratch of
+// one float per pass row.
+hipError_t launch_norm_pack_rows(const SeqBatch &sb, const void *mask_emb, const void *gain, int d,
+                                 float eps, float *rstd, void *pack, hipStream_t st) {
+  const int M = sb.row_off[sb.B];
+  if ((d & 7) || d > 8 * ROW_THREADS * ROW_MAXIT) return hipErrorInvalidValue;
+  int ntiles = 0, ksteps = 0;
+  gemm_bf16_pack_shape(M, d, &ntiles, &ksteps);
+  hipLaunchKernelGGL(row_rstd_kernel<bf16_t>, dim3(M), dim3(ROW_THREADS), 0, st, sb,
+                     (const bf16_t *)mask_emb, d, eps, rstd);
+  hipLaunchKernelGGL(pack_norm_tiles_kernel<bf16_t>, dim3(ntiles, (ksteps + 15) / 16), dim3(ROW_THREADS), 0,
+                     st, sb, (const bf16_t *)mask_emb, (const bf16_t *)gain, rstd, d, ntiles, ksteps,
+                     (uint4 *)pack);
   return hipGetLastError();
 }
 
