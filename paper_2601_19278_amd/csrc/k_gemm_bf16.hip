@@ -18,12 +18,12 @@
 // as plain fp32 (the FC input of the front end) go through pack_rows_kernel first.  The GEMM
 // workgroup copies the tiles of its row block (up to 128 rows) for two k-steps at a time from
 // global memory straight into LDS (no registers involved) and its 8 wavefronts share them,
-// each applying them to its own strips of 16 outputs.  A wavefront holds up to 4 strips x 8
+// each applying them to its own strips of 16 outputs.  A wavefront holds up to 5 strips x 8
 // row tiles of fp32 accumulators.
 //
 // Work units: (row block of 16*NCT rows, contiguous strip range, k-chunk).  Strip ranges are
 // a balanced partition, so a launch with one range per compute unit has no tail; a range
-// longer than 32 strips takes several passes over k.  The sum of a row is one chain per
+// longer than 40 strips takes several passes over k.  The sum of a row is one chain per
 // k-chunk in k order (hi product, then lo product, per 32-input step), independent of the
 // number of rows and of the strip grouping; chunk partials are added by the consumer.
 #include <cstdio>
@@ -36,7 +36,7 @@ namespace dart {
 
 constexpr int GEMM_WAVES = 8;
 constexpr int GEMM_THREADS = GEMM_WAVES * 64;
-constexpr int GEMM_SMAX = 4;        // strips per wavefront per pass
+constexpr int GEMM_SMAX = 5;        // strips per wavefront per pass
 constexpr int GEMM_KS = 2;          // k-steps (of 32 inputs) per LDS stage = per loop body
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
@@ -83,7 +83,9 @@ __device__ __forceinline__ void copy_tile_to_lds_async(uint32_t lds_base, uint32
 // this wait makes valid (the operands tie their first use to the wait).
 template <int N, int SP>
 __device__ __forceinline__ void wait_tiles(u32x4_t (&t)[SP]) {
-  if constexpr (SP == 4)
+  if constexpr (SP == 5)
+    asm volatile("s_waitcnt vmcnt(%5)" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]) : "n"(N));
+  else if constexpr (SP == 4)
     asm volatile("s_waitcnt vmcnt(%4)" : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]) : "n"(N));
   else if constexpr (SP == 2)
     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(t[0]), "+v"(t[1]) : "n"(N));
@@ -177,7 +179,11 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
   // k-step t + PD) right after the products that consumed it.  8 to 16 KiB are in flight per
   // wavefront (64 to 128 KiB per compute unit) whatever the number of strips, so that neither
   // the full passes nor the ones with few strips per wavefront are bound by memory latency.
-  constexpr int PD = SP == 4 ? 4 : 8 / SP;
+  // Five strips per wavefront (one pass over k for up to 40 strips per workgroup: the LM head's
+  // 37-38 at 256 workgroups, which otherwise pays the staging of all operand tiles a second
+  // time for 5-6 left-over strips) leave registers for a ring of two k-steps (10 KiB in flight)
+  // and for two operand tiles at a time.
+  constexpr int PD = SP == 5 ? 2 : (SP == 4 ? 4 : 8 / SP);
   // k-steps per unrolled loop body: a multiple of the weight ring and of the stage ring, so
   // that both kinds of slot are static
   constexpr int UNR = NS == 4 ? 8 : (PD < 4 ? 4 : PD);
@@ -217,7 +223,7 @@ __device__ __forceinline__ void gemm_pass(const GemmArgs &a, GemmStage<NCT, TERM
       wait_tiles<(PD - 1) * SP + (PD / 2) * TPW, SP>(aop[slot]);
       // operand tiles are read NB at a time (registers), hi then lo of each row tile: every
       // accumulator still adds its hi product, then its lo product, k-step by k-step
-      constexpr int NB = NCT < 4 ? NCT : 4;
+      constexpr int NB = SP == 5 ? 2 : (NCT < 4 ? NCT : 4);
 #pragma unroll
       for (int cb = 0; cb < NCT; cb += NB) {
 #pragma unroll
@@ -337,7 +343,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int per = (P + GEMM_WAVES - 1) / GEMM_WAVES;          // strips per wavefront
       const int sfirst = min(base + wave * per, g1 - 1);
       const int ns = max(0, min(per, P - wave * per));
-      if (per > 2) gemm_pass<NCT, 4, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
+      if (per > 4) gemm_pass<NCT, 5, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
+      else if (per > 2) gemm_pass<NCT, 4, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
       else if (per == 2) gemm_pass<NCT, 2, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
       else gemm_pass<NCT, 1, EPI, TERMS>(a, ring, rb, chunk, k0, nk, sfirst, ns, wave);
     }
@@ -610,8 +617,10 @@ int gemm_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nchunks, i
   GemmArgs a;
   int nct = 0;
   gemm_shape(nstrips, M, nchunks, &a, &nct);
-  return snprintf(buf, len, "gemm_bf16_kernel<%d,%d,%d> grid=%dx%d", nct, epi, gemm_bf16_terms(W),
-                  a.units, GEMM_THREADS);
+  const int per_range = (nstrips + a.ngroups - 1) / a.ngroups;      // strips of the longest range
+  const int passes = (per_range + GEMM_WAVES * GEMM_SMAX - 1) / (GEMM_WAVES * GEMM_SMAX);
+  return snprintf(buf, len, "gemm_bf16_kernel<%d,%d,%d> grid=%dx%d strips/wg=%d passes=%d", nct, epi,
+                  gemm_bf16_terms(W), a.units, GEMM_THREADS, per_range, passes);
 }
 
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
