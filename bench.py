@@ -3,9 +3,12 @@
 
 A "step" is one pass of the whole hot path over one synthetic input at Qwen3-14B shapes
 (preset C4: d 5120, 40/8 heads x 128, FFN 17408, vocab 151936, context 4096, K = 8):
-dart_draft_forward (warm: the prefix K/V of all but the last `--n-new` rows are cached, as
-in steady-state decoding where ~4 tokens are accepted per iteration) -> dart_topk (k = 10)
--> dart_tree_prune (w = 20, budget 60, 2^20-key trigram table).  Inputs are resident in HBM
+dart_draft_forward_topk (warm: the prefix K/V of all but the last `--n-new` rows are cached, as
+in steady-state decoding where ~4 tokens are accepted per iteration; the LM head selects the
+k = 10 candidates per row itself, so the forward and the top-k are one call and the logits are
+never stored) -> dart_tree_prune (w = 20, budget 60, 2^20-key trigram table).  The same step
+through dart_draft_forward -> dart_topk -> dart_tree_prune is timed beside it
+(stages.step_two_call_gpu_us).  Inputs are resident in HBM
 before the timed region.  Prints ONE JSON line.
 
 `--workload C5` times the batched preset instead (Qwen3-32B shapes, 16 ragged sequences, 128
@@ -84,15 +87,17 @@ def streaming_read_ceiling(torch, dart, dev, gib: int = 4) -> dict:
             f"{best[1]} workgroups x 512 threads, 16 B per lane, non-temporal, median of 8"}
 
 
-def algorithmic_bytes(cfg, n_new: int) -> dict:
+def algorithmic_bytes(cfg, n_new: int, logits_stored: bool = True) -> dict:
     """Bytes the step must move once: every weight (2 B) + the draft K/V rows read by attention
-    (+ the fp32 logits written by the LM head, counted with the LM head)."""
+    (+ the fp32 logits written by the LM head, counted with the LM head, unless the LM head
+    selects the candidates itself and stores no logits)."""
     p = cfg.n_params()
     T = cfg.ctx + cfg.K - 1
     kv = 2 * cfg.n_kv_heads * T * cfg.head_dim * 2
-    lm = p["lm_head"] * 2 + cfg.K * cfg.vocab * 4
+    out = cfg.K * cfg.vocab * 4 if logits_stored else 0
+    lm = p["lm_head"] * 2 + out
     return {"weights": p["total"] * 2, "kv": kv, "lm_head_kernel": lm,
-            "forward": p["total"] * 2 + kv + cfg.K * cfg.vocab * 4}
+            "forward": p["total"] * 2 + kv + out}
 
 
 def event_time_us(fn, iters: int, torch) -> float:
@@ -349,10 +354,24 @@ def main() -> int:
     def prune():
         table.tree_prune(tk[0][None], tk[1][None], tail, params, out=tree)
 
-    def step():
+    # bf16 contexts without the front end: the LM head selects the candidates itself and the
+    # logits never travel through HBM (dart_draft_forward_topk); otherwise the two calls
+    fused = cfg.dtype == "bf16" and not fe
+
+    def forward_topk():
+        ctx.draft_forward_topk(h_dev, n, K, k, 1e-9, n_cached=n - args.n_new, out=tk)
+
+    def step_two_call():
         forward(n - args.n_new)
         topk()
         prune()
+
+    def step():
+        if fused:
+            forward_topk()
+            prune()
+        else:
+            step_two_call()
 
     # cold calls (no cached K/V): the first one also pays one-time kernel loading, so the
     # second and third are timed; they leave the cache filled for the warm steps
@@ -383,13 +402,21 @@ def main() -> int:
         "step_gpu_us": event_time_us(step, it, torch),
         "cold_forward_us": cold_us,
     }
-    lm_times = event_times_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
+    if fused:
+        stages["forward_topk_us"] = event_time_us(forward_topk, it, torch)
+        stages["step_two_call_gpu_us"] = event_time_us(step_two_call, it, torch)
+        stages["lm_head_plain_us"] = event_time_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
+        lm_times = event_times_us(lambda: ctx.debug_lm_head_select(K, k), it, torch)
+        lm_key = ctx.debug_lm_head_key(K, multi_row=3)
+    else:
+        lm_times = event_times_us(lambda: ctx.debug_lm_head(K, logits), it, torch)
+        lm_key = ctx.debug_lm_head_key(K) if cfg.dtype == "bf16" else "gemv_f32_kernel"
     lm_us = sum(lm_times) / len(lm_times)
     step_times = event_times_us(step, max(it, min(200, args.steps)), torch)
     stages["step_gpu_us_stats"] = percentiles(step_times)
     stages["forward_warm_us_stats"] = percentiles(event_times_us(lambda: forward(n - args.n_new), it, torch))
     forward(n - args.n_new)          # leave the buffers consistent
-    ab = algorithmic_bytes(cfg, args.n_new)
+    ab = algorithmic_bytes(cfg, args.n_new, logits_stored=not fused)
     if fe:      # + FC weights, + the second half of the Q/K/V input columns (embedding rows: negligible)
         extra = 2 * (3 * cfg.d * cfg.d + cfg.d * (cfg.q_dim + 2 * cfg.kv_dim))
         ab["weights"] += extra
@@ -397,17 +424,18 @@ def main() -> int:
     achieved = ab["lm_head_kernel"] / (lm_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "gemv_bf16_kernel (LM head)", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                **(profiled_traffic(ctx.debug_lm_head_key(K)) if cfg.dtype == "bf16" else
-                   {"traffic": None}),
+                **(profiled_traffic(lm_key) if cfg.dtype == "bf16" else {"traffic": None}),
                 "kernel_us": round(lm_us, 2), "kernel_us_stats": percentiles(lm_times),
-                "kernel_variant": ctx.debug_lm_head_key(K) if cfg.dtype == "bf16" else "gemv_f32_kernel",
+                "kernel_variant": lm_key,
                 "algorithmic_bytes": ab["lm_head_kernel"]}
     if not args.no_ceiling:
         ceil = streaming_read_ceiling(torch, dart, dev)
         roofline.update(ceil)
         roofline["frac_of_ceiling"] = round(achieved / ceil["ceiling_GBps"], 4)
     stages["lm_head_us"] = lm_us
-    stages["forward_GBps"] = ab["forward"] / (stages["forward_warm_us"] * 1e-6) / 1e9
+    # dart_draft_forward stores the logits: its bytes include them whichever route the step takes
+    fwd_bytes = ab["forward"] + (0 if not fused else cfg.K * cfg.vocab * 4)
+    stages["forward_GBps"] = fwd_bytes / (stages["forward_warm_us"] * 1e-6) / 1e9
 
     if args.copy_calibration:
         copy_calibration(torch, dev)

@@ -145,6 +145,20 @@ dart_status dart_reset(dart_ctx *ctx, int seq);
 dart_status dart_draft_forward(dart_ctx *ctx, int seq, const void *hidden, int ctx_len,
                                int n_cached, int K, float *logits_out, void *stream);
 
+/* dart_draft_forward followed by dart_topk on its K rows, as one call: on bf16 contexts with
+ * K <= 8 the LM-head workgroups select the k best logits and the (max, sum exp) of the vocabulary
+ * strips they compute while those are still on chip, and only the short row merge runs afterwards
+ * -- the candidate extraction of Alg. 1 ("Top-k_i tokens from l_i", App. D "s_logit") without a
+ * second pass over the K x vocab logits.  Other contexts run the two steps one after the other.
+ *   logits_out  device [K][vocab] fp32, or NULL when the caller only needs the candidates
+ *   ids_out     device [K][k] int32, scores_out device [K][k] fp32: exactly what
+ *               dart_topk(logits, K, vocab, k, eps) returns for the logits this call computes
+ *               (ids and order identical; scores to the rounding of the row's log-sum-exp)
+ * Errors: as dart_draft_forward and dart_topk (ARG also for NULL ids_out / scores_out). */
+dart_status dart_draft_forward_topk(dart_ctx *ctx, int seq, const void *hidden, int ctx_len,
+                                    int n_cached, int K, int k, float eps, float *logits_out,
+                                    int32_t *ids_out, float *scores_out, void *stream);
+
 /* Draft forward from the target model's raw outputs (contexts created with front_end = 1;
  * Sec. 3.2, Fig. 3): for every new prefix position, g = FC(features) and e = embedding of the
  * token that follows it (the shifted embeddings e_{2:n+1}); z = [g ; e] is the layer's 2d-wide

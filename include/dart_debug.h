@@ -30,8 +30,18 @@ int64_t dart_debug_read(dart_ctx *ctx, const char *name, float *host_out, int64_
 dart_status dart_debug_lm_head(dart_ctx *ctx, int rows, int multi_row, float *logits_out,
                                void *stream);
 
+/* Diagnostic (benchmark only): enqueue only the LM-head kernel of dart_draft_forward_topk (the
+ * projection that also selects each workgroup's k best candidates, Sec. 3.2 + Alg. 1) on the
+ * final-normed rows the last forward call left in the workspace; rows <= 8.  The per-workgroup
+ * candidate lists stay in the context's workspace and the row merge is not run.  logits_out:
+ * device [rows][vocab] fp32, or NULL to skip the store as dart_draft_forward_topk does without
+ * a logits buffer.  DART_ERR_STATE on contexts whose LM head does not select (fp32 storage,
+ * front end, d beyond one k-chunk). */
+dart_status dart_debug_lm_head_select(dart_ctx *ctx, int rows, int k, float *logits_out, void *stream);
+
 /* Diagnostic (benchmark only): the name and launch shape of the kernel that
- * dart_debug_lm_head(ctx, rows, multi_row != 0, ...) launches for the LM head, as text
+ * dart_debug_lm_head(ctx, rows, multi_row != 0, ...) -- or, with multi_row = 3,
+ * dart_debug_lm_head_select(ctx, rows, ...) -- launches for the LM head, as text
  * ("gemv_bf16_kernel<20,20,0,true,true> grid=184x512"), written to buf (at most len bytes
  * including the terminator).  Counter summaries under profiles/ are keyed by this string.
  * Returns the length written, or -1 on error. */

@@ -12,14 +12,15 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
+    "dart_draft_forward_topk",
     "dart_draft_forward_features", "dart_draft_forward_features_batched",
     "dart_draft_forward_batched", "dart_topk", "dart_topk_static", "dart_ngram_create", "dart_ngram_destroy",
     "dart_ngram_set_backoff",
     "dart_tree_prune", "dart_tree_verify_greedy",
 )
 # include/dart_debug.h: diagnostics for this repository's tests and benchmark, not product API
-DEBUG_SYMBOLS = ("dart_debug_read", "dart_debug_lm_head", "dart_debug_lm_head_key",
-                 "dart_debug_stream_read")
+DEBUG_SYMBOLS = ("dart_debug_read", "dart_debug_lm_head", "dart_debug_lm_head_select",
+                 "dart_debug_lm_head_key", "dart_debug_stream_read")
 
 DART_F32, DART_BF16 = 0, 1
 
@@ -86,6 +87,7 @@ def load_library() -> C.CDLL:
     lib.dart_destroy.restype = None
     lib.dart_reset.argtypes = [vp, i32]
     lib.dart_draft_forward.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
+    lib.dart_draft_forward_topk.argtypes = [vp, i32, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp]
     lib.dart_draft_forward_features.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
     lib.dart_draft_forward_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
                                                C.POINTER(C.c_int32), i32, vp, vp]
@@ -104,6 +106,7 @@ def load_library() -> C.CDLL:
     lib.dart_debug_read.argtypes = [vp, C.c_char_p, vp, i64]
     lib.dart_debug_read.restype = i64
     lib.dart_debug_lm_head.argtypes = [vp, i32, i32, vp, vp]
+    lib.dart_debug_lm_head_select.argtypes = [vp, i32, i32, vp, vp]
     lib.dart_debug_lm_head_key.argtypes = [vp, i32, i32, C.c_char_p, i32]
     lib.dart_debug_stream_read.argtypes = [vp, i64, i32, i32, vp, vp]
     if hasattr(lib, "dart_debug_set"):          # tuning builds (-DDART_TUNING) only
@@ -195,6 +198,21 @@ class DraftContext:
                "dart_draft_forward")
         return out
 
+    def draft_forward_topk(self, hidden, ctx_len: int, K: int, k: int, eps: float = 1e-9,
+                           n_cached: int = 0, seq: int = 0, logits_out=None, out=None, stream=None):
+        """dart_draft_forward_topk: the forward and the per-row top-k in one call; returns
+        (ids [K][k] int32, scores [K][k] fp32); logits are written only if logits_out is given."""
+        torch = _torch()
+        if out is None:
+            out = (torch.empty((K, k), dtype=torch.int32, device=hidden.device),
+                   torch.empty((K, k), dtype=torch.float32, device=hidden.device))
+        ids, scores = out
+        _check(self._lib.dart_draft_forward_topk(self._h, seq, hidden.data_ptr(), ctx_len, n_cached, K, k,
+                                                 eps, None if logits_out is None else logits_out.data_ptr(),
+                                                 ids.data_ptr(), scores.data_ptr(), _stream_ptr(stream)),
+               "dart_draft_forward_topk")
+        return ids, scores
+
     def draft_forward_features(self, features, next_tokens, ctx_len: int, K: int, n_cached: int = 0,
                                seq: int = 0, out=None, stream=None):
         """dart_draft_forward_features: features CUDA [>=ctx_len][feat_dim], next_tokens CUDA int32
@@ -256,6 +274,10 @@ class DraftContext:
         _check(self._lib.dart_debug_lm_head(self._h, rows, int(multi_row), out.data_ptr(),
                                             _stream_ptr(stream)), "dart_debug_lm_head")
         return out
+
+    def debug_lm_head_select(self, rows: int, k: int, out=None, stream=None):
+        _check(self._lib.dart_debug_lm_head_select(self._h, rows, k, out.data_ptr() if out is not None else None,
+                                                   _stream_ptr(stream)), "dart_debug_lm_head_select")
 
     def debug_lm_head_key(self, rows: int, multi_row: int = 0) -> str:
         buf = C.create_string_buffer(256)

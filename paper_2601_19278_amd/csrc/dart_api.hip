@@ -293,6 +293,10 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   }
   c->max_rows = g.max_batch * g.max_K;
   c->topk_chunks_max = topk_chunks(g.vocab);
+  if (g.dtype == DART_BF16 && !g.front_end)
+    c->lm_select_wgs = gemv_bf16_select_wgs(c->wlm, (g.vocab + 15) / 16, std::min(g.max_K, 8));
+  c->topk_chunks_max = std::max(c->topk_chunks_max, c->lm_select_wgs);
+  HIP_TRY(dev_alloc(&c->logits_tmp, (size_t)g.max_K * g.vocab));
   HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
   HIP_TRY(dev_alloc(&c->topk_ms, (size_t)c->max_rows * c->topk_chunks_max * 2));
   return hipSuccess;
@@ -337,10 +341,25 @@ hipError_t project(const dart_ctx *c, const DeviceMatrix &W, int row0, int nrows
 // LM head (Sec. 3.2) on the final-normed rows X (null on the multi-row path: operand tiles
 // already packed).  The skinny kernel writes the caller's logits directly when d fits one
 // k-chunk; a longer d goes through chunk partials and one more pass that adds them.
+// Candidate extraction fused into the LM head (dart_draft_forward_topk): k, eps and outputs.
+struct FusedCand {
+  int k;
+  float eps;
+  int32_t *ids;
+  float *scores;
+};
+
 hipError_t lm_head(const dart_ctx *c, const float *X, int rows, bool gemm, float *logits,
-                   hipStream_t st) {
+                   hipStream_t st, const FusedCand *fc = nullptr) {
   const int V = c->cfg.vocab;
   int chunks = 1;
+  if (fc) {
+    // the LM-head workgroups select their own candidates; the row merge finishes (Alg. 1, App. D)
+    const GemvTopk tk{c->topk_cand, c->topk_ms, fc->k};
+    HIP_TRY(launch_gemv_bf16(c->wlm, 0, (V + 15) / 16, X, rows, logits, V, 0, 1, &chunks, st, &tk));
+    return launch_topk_merge(c->topk_cand, c->topk_ms, rows, fc->k, c->lm_select_wgs, fc->eps, fc->ids,
+                             fc->scores, st);
+  }
   if (gemm || c->split_lm == 1 || c->cfg.dtype != DART_BF16)
     return project(c, c->wlm, 0, V, X, rows, logits, V, 0, 1, gemm ? 1 : 0, &chunks, st);
   const size_t cs = (size_t)DART_SKINNY_ROWS * c->lm_stride;
@@ -410,7 +429,7 @@ hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
 // weights).  The two kernels add a row's products in different orders, so a K/V slot filled
 // through one entry point is reused by the other only to rounding, not bit for bit.
 hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gemm, float *logits,
-                         hipStream_t st) {
+                         hipStream_t st, const FusedCand *fc = nullptr) {
   const dart_config &g = c->cfg;
   const int R = DART_SKINNY_ROWS;
   gemm = gemm && g.dtype == DART_BF16;
@@ -502,7 +521,7 @@ hipError_t forward_group(dart_ctx *c, int B, const SeqJob *jobs, int K, bool gem
   HIP_TRY(launch_resid_norm(g.dtype, c->y, c->proj, chunks, cs, g.d, c->g_final, QR, g.d, g.rms_eps,
                             gemm ? nullptr : c->u, gemm ? nullptr : c->yn, gemm ? c->xpack : nullptr,
                             gemm_bf16_terms(c->wlm), st));
-  return lm_head(c, yn_in, QR, gemm, logits, st);
+  return lm_head(c, yn_in, QR, gemm, logits, st, fc);
 }
 
 dart_status check_forward_args(const dart_ctx *c, int seq, const void *hidden, int n, int n_cached,
@@ -594,7 +613,7 @@ void dart_destroy(dart_ctx *c) {
                   c->g_post, c->g_final, c->g_q, c->g_k, c->mask_emb, c->rope_cos, c->rope_sin,
                   c->kbuf, c->vbuf, c->xn, c->resid, c->qkv, c->qrot, c->att_part, c->att_ml,
                   c->att_out, c->proj, c->y, c->yn, c->hmid, c->u, c->topk_cand, c->topk_ms,
-                  c->xn_kv, c->kv_part, c->lm_part, c->xpack, c->xpack2, c->wfc.data, c->embed, c->g_emb, c->feat32,
+                  c->xn_kv, c->kv_part, c->lm_part, c->logits_tmp, c->xpack, c->xpack2, c->wfc.data, c->embed, c->g_emb, c->feat32,
                   c->fc_part};
   for (void *p : bufs)
     if (p) (void)hipFree(p);
@@ -632,6 +651,34 @@ dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx
   const SeqJob job{seq, hidden, ctx_len, n_cached};
   c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
   hipError_t e = forward_group(c, 1, &job, K, false, logits_out, (hipStream_t)stream);
+  if (e != hipSuccess) return from_hip(e);
+  c->cached_rows[seq] = ctx_len;
+  return DART_OK;
+}
+
+dart_status dart_draft_forward_topk(dart_ctx *c, int seq, const void *hidden, int ctx_len, int n_cached,
+                                    int K, int k, float eps, float *logits_out, int32_t *ids_out,
+                                    float *scores_out, void *stream) {
+  float dummy = 0.f;
+  dart_status s = check_forward_args(c, seq, hidden, ctx_len, n_cached, K, &dummy);
+  if (s != DART_OK) return s;
+  if (!ids_out || !scores_out) return DART_ERR_ARG;
+  if (k < 1 || k > DART_MAX_TOPK || k > c->cfg.vocab) return DART_ERR_ARG;
+  if (c->cfg.front_end) return DART_ERR_STATE;
+  const SeqJob job{seq, hidden, ctx_len, n_cached};
+  c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
+  hipError_t e;
+  if (c->lm_select_wgs > 0 && K <= 8) {
+    const FusedCand fc{k, eps, ids_out, scores_out};
+    e = forward_group(c, 1, &job, K, false, logits_out, (hipStream_t)stream, &fc);
+  } else {
+    // shapes the fused selection does not serve (fp32 storage, more than 8 rows, a d longer than
+    // one k-chunk): the two steps one after the other, same results
+    float *logits = logits_out ? logits_out : c->logits_tmp;
+    e = forward_group(c, 1, &job, K, false, logits, (hipStream_t)stream);
+    if (e == hipSuccess)
+      e = launch_topk(c, logits, K, c->cfg.vocab, k, eps, ids_out, scores_out, (hipStream_t)stream);
+  }
   if (e != hipSuccess) return from_hip(e);
   c->cached_rows[seq] = ctx_len;
   return DART_OK;
@@ -909,10 +956,24 @@ dart_status dart_debug_lm_head(dart_ctx *c, int rows, int multi_row, float *logi
   return from_hip(lm_head(c, c->yn, rows, false, logits_out, (hipStream_t)stream));
 }
 
-// Diagnostic: which kernel, in which launch shape, dart_debug_lm_head runs.
+// Diagnostic: only the candidate-selecting LM-head kernel of dart_draft_forward_topk, on the rows
+// the last forward left behind; the per-workgroup lists stay in the workspace (no row merge).
+dart_status dart_debug_lm_head_select(dart_ctx *c, int rows, int k, float *logits_out, void *stream) {
+  if (!c || rows < 1 || rows > 8 || k < 1 || k > DART_MAX_TOPK || k > c->cfg.vocab) return DART_ERR_ARG;
+  if (c->lm_select_wgs <= 0) return DART_ERR_STATE;
+  const GemvTopk tk{c->topk_cand, c->topk_ms, k};
+  int chunks = 1;
+  return from_hip(launch_gemv_bf16(c->wlm, 0, (c->cfg.vocab + 15) / 16, c->yn, rows, logits_out,
+                                   c->cfg.vocab, 0, 1, &chunks, (hipStream_t)stream, &tk));
+}
+
+// Diagnostic: which kernel, in which launch shape, dart_debug_lm_head (multi_row 0, 1 or 2) or
+// dart_debug_lm_head_select (multi_row 3) runs.
 int dart_debug_lm_head_key(dart_ctx *c, int rows, int multi_row, char *buf, int len) {
   if (!c || !buf || len < 1 || rows < 1 || c->cfg.dtype != DART_BF16) return -1;
   const int nstrips = (c->cfg.vocab + 15) / 16;
+  if (multi_row == 3)
+    return c->lm_select_wgs > 0 ? gemv_bf16_describe(c->wlm, nstrips, rows, 1, buf, len, true) : -1;
   if (multi_row) return gemm_bf16_describe(c->wlm, nstrips, rows, 1, 0, buf, len);
   return gemv_bf16_describe(c->wlm, nstrips, rows, gemv_bf16_chunks(c->cfg.d), buf, len);
 }

@@ -175,6 +175,8 @@ struct dart_ctx {
   uint64_t *topk_cand = nullptr;  // [rows][chunks][DART_MAX_TOPK]
   float *topk_ms = nullptr;       // [rows][chunks][2]
   int topk_chunks_max;
+  int lm_select_wgs = 0;          // workgroups of the LM-head launch that selects its own candidates (0 = cannot)
+  float *logits_tmp = nullptr;    // [max_K][vocab]: dart_draft_forward_topk without a logits buffer, unfused
 };
 
 namespace dart {
@@ -233,11 +235,23 @@ hipError_t launch_resid_norm(int dtype, const float *resid, const float *part, i
 hipError_t launch_gemv_f32(const DeviceMatrix &W, int row0, int nrows, const float *X, int M,
                            float *out, int out_stride, hipStream_t st);
 
+// Candidate output of the skinny kernel when it selects its workgroups' top-k itself (the LM
+// head with at most 8 rows): per (row, workgroup) k ordering keys and (max, sum exp), in the
+// layout topk_merge_kernel reads with "chunks" = workgroups of the launch (gemv_bf16_select_wgs).
+struct GemvTopk {
+  uint64_t *cand;      // [row][workgroup][DART_MAX_TOPK] ordering keys, 0 = none
+  float *ms;           // [row][workgroup][2]
+  int k;
+};
+
 // bf16 skinny GEMM on packed weights; returns the number of k-chunks written through *chunks.
+// tk != null: also write the workgroups' candidates; out may then be null.
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int split, int *chunks,
-                            hipStream_t st);
-int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char *buf, int len);
+                            hipStream_t st, const GemvTopk *tk = nullptr);
+int gemv_bf16_select_wgs(const DeviceMatrix &W, int nstrips, int M);
+int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char *buf, int len,
+                       bool topk = false);
 int gemm_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nchunks, int epi, char *buf,
                        int len);
 int gemv_bf16_chunks(int Kd);                 // k-chunks forced by the register budget
@@ -280,6 +294,8 @@ hipError_t launch_qkv_post(const dart_ctx *c, const SeqBatch &sb, const float *q
 hipError_t launch_attention(const dart_ctx *c, const SeqBatch &sb, void *pack, int terms, hipStream_t st);
 
 int topk_chunks(int vocab);                   // vocabulary chunks of the top-k kernels
+hipError_t launch_topk_merge(const uint64_t *cand, const float *ms, int rows, int k, int nlists, float eps,
+                             int32_t *ids, float *scores, hipStream_t st);
 hipError_t launch_topk(const dart_ctx *c, const float *logits, int rows, int vocab, int k, float eps,
                        int32_t *ids, float *scores, hipStream_t st);
 

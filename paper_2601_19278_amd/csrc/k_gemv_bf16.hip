@@ -26,6 +26,7 @@
 
 #include "common.h"
 #include "dart_internal.h"
+#include "topk_select.h"
 
 namespace dart {
 
@@ -80,18 +81,27 @@ __device__ __forceinline__ void lds_barrier() {
 // the main loop is branch-free straight-line code -- the compiler can then keep D loads in
 // flight with exact wait counts.  EXACT = false handles ragged k ranges (unusual shapes) with
 // per-step guards and is not tuned.
-template <int KPW, int D, int MT, bool NT, bool EXACT>
+// TK = true (the LM head with at most 8 rows, one k-chunk): the workgroup also keeps the logits of
+// its strips in LDS and, after its last strip, selects per row the k best of them and their
+// (max, sum exp) -- the per-position candidate extraction of Alg. 1 done where the logits are
+// produced, so that no kernel has to read the vocabulary-wide rows again.  One wavefront per row;
+// the row merge (topk_merge_kernel) then combines the workgroups' lists exactly as it combines
+// the chunk lists of topk_kernel.  out may be null (logits not wanted).
+constexpr int GEMV_TK_STRIPS = 64;        // strips of one workgroup whose logits fit its LDS buffer
+template <int KPW, int D, int MT, bool NT, bool EXACT, bool TK = false>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
     const u32x4_t *__restrict__ Wp, // packed tiles, 64 x 16 bytes per tile
     const float *__restrict__ X,    // [M][Kd]
     int M, int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols,
-    float *__restrict__ out, int out_stride, size_t chunk_stride, int xcd_map) {
+    float *__restrict__ out, int out_stride, size_t chunk_stride, int xcd_map, GemvTopk tk) {
   static_assert(KPW % D == 0, "a register of the rolling buffer must serve the same slots in every strip");
   constexpr bool M8 = MT == 0;
   constexpr int NMT = M8 ? 1 : MT;                     // column tiles
   constexpr int NACC = M8 ? 1 : 2 * MT;                // accumulator tiles per strip
   constexpr int NBUF = NACC <= 2 ? 2 : 1;              // LDS double buffering while it fits
   __shared__ float part[NBUF][GEMV_WAVES][NACC * 256];
+  __shared__ float wl[TK ? GEMV_TK_STRIPS : 1][128];   // TK: logits of this workgroup's strips, [row][16]
+  static_assert(!TK || (MT == 0 && NBUF == 2), "candidate selection: at most 8 rows");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, gq = lane >> 4;
   const int chunk = blockIdx.x % nchunks;
@@ -168,6 +178,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
   }
 
   int buf = 0;
+  const int s_first = s;
+  int n_done = 0;                                      // strips this workgroup has finished
   for (; s < s_end; s += s_step) {
     const int sn = s + s_step;
     const u32x4_t *cur = Wp + ((size_t)(strip0 + s) * KT + ks0) * 64 + lane;
@@ -213,21 +225,83 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_bf16_kernel(
 #pragma unroll
       for (int w = 0; w < GEMV_WAVES; ++w) v_lo += part[buf][w][idx_lo];
       const int c = s * 16 + row, mm = 16 * mt + m;
-      if (mm < M && c < n_cols)
-        out[chunk * chunk_stride + (size_t)mm * out_stride + c] = v_hi + v_lo;
+      if constexpr (TK) {
+        const bool real = mm < M && c < n_cols;
+        wl[n_done][o] = real ? v_hi + v_lo : -3.0e38f;        // o = m * 16 + row
+        if (real && out) out[(size_t)mm * out_stride + c] = v_hi + v_lo;
+      } else {
+        if (mm < M && c < n_cols)
+          out[chunk * chunk_stride + (size_t)mm * out_stride + c] = v_hi + v_lo;
+      }
     }
     if (NBUF == 2) buf ^= 1;
+    ++n_done;
+  }
+  if constexpr (TK) {
+    // Candidates of this workgroup: wavefront m takes row m over the n_done * 16 logits in LDS.
+    __syncthreads();
+    const int m = wave;
+    if (m >= M) return;
+    constexpr int NE = GEMV_TK_STRIPS * 16 / 64;         // entries per lane
+    const int total = n_done * 16;
+    const int ne = lane < total ? min(NE, (total - lane + 63) >> 6) : 0;
+    float val[NE];
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      const int i = lane + 64 * e;
+      val[e] = e < ne ? wl[i >> 4][m * 16 + (i & 15)] : -3.0e38f;
+      mx = fmaxf(mx, val[e]);
+    }
+    mx = wave_max_dpp(mx);
+    float se = 0.f;
+    uint32_t v[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      // entries beyond the vocabulary (the padding outputs of the last strip) hold -3e38: they add
+      // exp(-inf) = 0 and sort below every real logit; their keys are dropped below
+      if (e < ne && val[e] > -1.0e38f) se += __expf(val[e] - mx);
+      v[e] = val[e] > -1.0e38f ? f32_sortable(val[e]) : 0u;
+    }
+    se = wave_sum_dpp(se);
+    const size_t slot = (size_t)m * gridDim.x + blockIdx.x;
+    if (lane == 0) {
+      tk.ms[slot * 2] = mx;
+      tk.ms[slot * 2 + 1] = se;
+    }
+    // vocabulary index of the lane's e-th entry: strip s_first + (i / 16) * s_step, output i % 16
+    uint64_t *sel = reinterpret_cast<uint64_t *>(&part[0][0][0]) + (size_t)wave * TOPK_CAP;
+    static_assert(sizeof(part) >= GEMV_WAVES * TOPK_CAP * sizeof(uint64_t), "selection buffers fit");
+    wave_select_indexed(
+        v, ne, [&](int e) { const int i = lane + 64 * e; return (strip0 + s_first + (i >> 4) * s_step) * 16 + (i & 15); },
+        tk.k, sel, [&](int r, uint64_t best) {
+          tk.cand[slot * DART_MAX_TOPK + r] = (best >> 32) ? best : 0;   // value word 0 = a padding entry
+        });
   }
 }
 
 template <int KPW, int D, bool EXACT>
-static void gemv_launch(bool nt, int mt, dim3 grid, hipStream_t st, const u32x4_t *wp, const float *X, int M,
-                        int KT, int kpw, int nchunks, int strip0, int nstrips, int n_cols, float *out,
-                        int out_stride, size_t chunk_stride) {
+static void gemv_launch(bool nt, int mt, const GemvTopk *tk, dim3 grid, hipStream_t st, const u32x4_t *wp,
+                        const float *X, int M, int KT, int kpw, int nchunks, int strip0, int nstrips,
+                        int n_cols, float *out, int out_stride, size_t chunk_stride) {
+  const GemvTopk none{nullptr, nullptr, 0};
+  if constexpr (EXACT) {                               // candidate selection: exact slices, <= 8 rows
+    if (tk) {
+      if (nt)
+        hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, 0, true, EXACT, true>), grid, dim3(GEMV_THREADS), 0, st,
+                           wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,
+                           chunk_stride, g_gemv_xcd, *tk);
+      else
+        hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, 0, false, EXACT, true>), grid, dim3(GEMV_THREADS), 0, st,
+                           wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,
+                           chunk_stride, g_gemv_xcd, *tk);
+      return;
+    }
+  }
 #define DART_GEMV_GO(MT_, NT_)                                                                    \
   hipLaunchKernelGGL((gemv_bf16_kernel<KPW, D, MT_, NT_, EXACT>), grid, dim3(GEMV_THREADS), 0, st, \
                      wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride,         \
-                     chunk_stride, g_gemv_xcd)
+                     chunk_stride, g_gemv_xcd, none)
   if constexpr (KPW <= 5) {                            // the row-block variants need short k-slices
     if (mt == 4) { if (nt) DART_GEMV_GO(4, true); else DART_GEMV_GO(4, false); return; }
     if (mt == 2) { if (nt) DART_GEMV_GO(2, true); else DART_GEMV_GO(2, false); return; }
@@ -319,13 +393,14 @@ static hipError_t gemv_plan(const DeviceMatrix &W, int nstrips, int M, int nch, 
   return hipSuccess;
 }
 
-// "gemv_bf16_kernel<KPW,D,MT,NT,EXACT> grid=<workgroups>x512" of the launch that
+// "gemv_bf16_kernel<KPW,D,MT,NT,EXACT[,true]> grid=<workgroups>x512" (",true": the candidate-
+// selecting variant) of the launch that
 // launch_gemv_bf16 makes for these arguments (diagnostics: keys the counter summaries).
-int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char *buf, int len) {
+int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char *buf, int len, bool topk) {
   GemvPlan p;
   if (gemv_plan(W, nstrips, M, nch, &p) != hipSuccess) return -1;
-  return snprintf(buf, len, "gemv_bf16_kernel<%d,%d,%d,%s,%s> grid=%dx%d", p.kpw_t, p.d_t, p.mt,
-                  p.nt ? "true" : "false", p.exact ? "true" : "false",
+  return snprintf(buf, len, "gemv_bf16_kernel<%d,%d,%d,%s,%s%s> grid=%dx%d", p.kpw_t, p.d_t, p.mt,
+                  p.nt ? "true" : "false", p.exact ? "true" : "false", topk ? ",true" : "",
                   p.wgs * p.nchunks * p.row_blocks, GEMV_THREADS);
 }
 
@@ -333,19 +408,36 @@ int gemv_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nch, char 
 // (columns beyond W.n_real - strip0*16 are not written).  nch: k-chunks (at least
 // gemv_bf16_chunks(Kd); 1 when the output must be complete in a single chunk).  M may exceed 16
 // only up to 16 * gemv_bf16_row_tiles(Kd, nch) * any number of row blocks (grid.y).
+// Workgroups of the launch that computes these strips for M <= 8 rows in one k-chunk, if that
+// launch can also select its workgroups' top-k candidates (GemvTopk); 0 if it cannot: the k
+// range must be one chunk of exact slices and a workgroup's strips must fit its LDS buffer.
+int gemv_bf16_select_wgs(const DeviceMatrix &W, int nstrips, int M) {
+  GemvPlan p;
+  if (M > 8 || gemv_bf16_chunks(W.Kd) != 1 || gemv_plan(W, nstrips, M, 1, &p) != hipSuccess || !p.exact)
+    return 0;
+  // strips per workgroup under the kernel's assignment (contiguous eighths of the strips per XCD
+  // class when the workgroup count divides by 8, else dealt round-robin)
+  const int per_wg = g_gemv_xcd == 2 && p.wgs % 8 == 0
+                         ? ((nstrips + 7) / 8 + p.wgs / 8 - 1) / (p.wgs / 8)
+                         : (nstrips + p.wgs - 1) / p.wgs;
+  return per_wg <= GEMV_TK_STRIPS ? p.wgs : 0;
+}
+
 hipError_t launch_gemv_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             float *out, int out_stride, size_t chunk_stride, int nch, int *chunks,
-                            hipStream_t st) {
+                            hipStream_t st, const GemvTopk *tk) {
   GemvPlan p;
   hipError_t e = gemv_plan(W, nstrips, M, nch, &p);
   if (e != hipSuccess) return e;
+  if (tk && (nch != 1 || gemv_bf16_select_wgs(W, nstrips, M) != p.wgs || !tk->cand || !tk->ms))
+    return hipErrorInvalidValue;
   const int KT = W.Kd / 32, nchunks = p.nchunks, kpw = p.kpw, mt = p.mt;
   if (chunks) *chunks = nchunks;
   const int n_cols = min(nstrips * 16, W.n_real - strip0 * 16);
   dim3 grid(p.wgs * nchunks, p.row_blocks);
   const u32x4_t *wp = (const u32x4_t *)W.data;
   const bool nt = p.nt;
-#define DART_GEMV_ARGS nt, mt, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
+#define DART_GEMV_ARGS nt, mt, tk, grid, st, wp, X, M, KT, kpw, nchunks, strip0, nstrips, n_cols, out, out_stride, chunk_stride
 #define DART_GEMV_CASE(KPW_, D_, EX_) \
   if (p.kpw_t == KPW_ && p.d_t == D_ && p.exact == EX_) gemv_launch<KPW_, D_, EX_>(DART_GEMV_ARGS); else
   DART_GEMV_CASE(20, 20, true) DART_GEMV_CASE(20, 10, true) DART_GEMV_CASE(20, 5, true)

@@ -79,6 +79,12 @@ int main() {
     int32_t i32 = 0;
     EXPECT(dart_topk(ctx, &dummy, 1, 64, 1, 1e-9f, &i32, &dummy, nullptr) == DART_ERR_SHAPE);
     EXPECT(dart_topk(ctx, &dummy, 1, 32, 33, 1e-9f, &i32, &dummy, nullptr) == DART_ERR_ARG);
+    // the combined call: the forward's checks, then the top-k's; the logits buffer is optional
+    EXPECT(dart_draft_forward_topk(ctx, 0, &dummy, 9, 0, 1, 1, 1e-9f, nullptr, &i32, &dummy, nullptr) == DART_ERR_SHAPE);
+    EXPECT(dart_draft_forward_topk(ctx, 0, &dummy, 4, 2, 1, 1, 1e-9f, nullptr, &i32, &dummy, nullptr) == DART_ERR_STATE);
+    EXPECT(dart_draft_forward_topk(ctx, 0, &dummy, 4, 0, 1, 0, 1e-9f, nullptr, &i32, &dummy, nullptr) == DART_ERR_ARG);
+    EXPECT(dart_draft_forward_topk(ctx, 0, &dummy, 4, 0, 1, DART_MAX_TOPK + 1, 1e-9f, nullptr, &i32, &dummy, nullptr) == DART_ERR_ARG);
+    EXPECT(dart_draft_forward_topk(ctx, 0, &dummy, 4, 0, 1, 1, 1e-9f, nullptr, nullptr, &dummy, nullptr) == DART_ERR_ARG);
     dart_destroy(ctx);
   } else {
     EXPECT(ctx == nullptr);
@@ -88,6 +94,7 @@ int main() {
   EXPECT(dart_draft_forward(nullptr, 0, nullptr, 1, 0, 1, nullptr, nullptr) == DART_ERR_ARG);
   EXPECT(dart_draft_forward_batched(nullptr, 1, nullptr, nullptr, nullptr, 1, nullptr, nullptr) == DART_ERR_ARG);
   EXPECT(dart_topk(nullptr, nullptr, 1, 1, 1, 1e-9f, nullptr, nullptr, nullptr) == DART_ERR_ARG);
+  EXPECT(dart_draft_forward_topk(nullptr, 0, nullptr, 1, 0, 1, 1, 1e-9f, nullptr, nullptr, nullptr, nullptr) == DART_ERR_ARG);
 
   // ---- dart_topk_static: range checks come before the device is touched
   {
