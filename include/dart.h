@@ -159,6 +159,21 @@ dart_status dart_draft_forward_topk(dart_ctx *ctx, int seq, const void *hidden, 
                                     int n_cached, int K, int k, float eps, float *logits_out,
                                     int32_t *ids_out, float *scores_out, void *stream);
 
+/* dart_draft_forward_batched followed by dart_topk on its batch*K rows (Sec. 3.2, then Alg. 1
+ * "Top-k_i tokens from l_i", App. D "s_logit"), as one call that needs no logits buffer from the
+ * caller: without one, the logits of each group of up to 16 sequences pass through a buffer of
+ * the context.  The two steps run one after the other (the multi-row LM head does not select
+ * candidates itself: measured no faster than the separate top-k).
+ *   hidden, ctx_len, n_cached, K   as dart_draft_forward_batched
+ *   logits_out  device [batch][K][vocab] fp32, or NULL when only the candidates are needed
+ *   ids_out     device [batch][K][k] int32, scores_out device [batch][K][k] fp32: exactly what
+ *               dart_topk returns for the logits this call computes (ids and order identical)
+ * Errors: as dart_draft_forward_batched and dart_topk; STATE on contexts with the front end. */
+dart_status dart_draft_forward_topk_batched(dart_ctx *ctx, int batch, const void *const *hidden,
+                                            const int32_t *ctx_len, const int32_t *n_cached, int K,
+                                            int k, float eps, float *logits_out, int32_t *ids_out,
+                                            float *scores_out, void *stream);
+
 /* Draft forward from the target model's raw outputs (contexts created with front_end = 1;
  * Sec. 3.2, Fig. 3): for every new prefix position, g = FC(features) and e = embedding of the
  * token that follows it (the shifted embeddings e_{2:n+1}); z = [g ; e] is the layer's 2d-wide

@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
-    "dart_draft_forward_topk",
+    "dart_draft_forward_topk", "dart_draft_forward_topk_batched",
     "dart_draft_forward_features", "dart_draft_forward_features_batched",
     "dart_draft_forward_batched", "dart_topk", "dart_topk_static", "dart_ngram_create", "dart_ngram_destroy",
     "dart_ngram_set_backoff",
@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.dart_draft_forward_features.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
     lib.dart_draft_forward_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
                                                C.POINTER(C.c_int32), i32, vp, vp]
+    lib.dart_draft_forward_topk_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
+                                                    C.POINTER(C.c_int32), i32, i32, f32, vp, vp, vp, vp]
     lib.dart_draft_forward_features_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp),
                                                         C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                                         i32, vp, vp]
@@ -237,6 +239,25 @@ class DraftContext:
         _check(self._lib.dart_draft_forward_batched(self._h, B, ptrs, lens, cached, K,
                                                     out.data_ptr(), _stream_ptr(stream)),
                "dart_draft_forward_batched")
+        return out
+
+    def draft_forward_topk_batched(self, hiddens, ctx_lens, n_cached, K: int, k: int, eps: float = 1e-9,
+                                   logits_out=None, out=None, stream=None):
+        """dart_draft_forward_topk_batched: the batched forward and the per-row top-k in one call;
+        returns (ids [B][K][k] int32, scores [B][K][k] fp32); logits are written only if
+        logits_out ([B][K][vocab] fp32) is given."""
+        torch = _torch()
+        B = len(hiddens)
+        if out is None:
+            out = (torch.empty((B, K, k), dtype=torch.int32, device=hiddens[0].device),
+                   torch.empty((B, K, k), dtype=torch.float32, device=hiddens[0].device))
+        ptrs = (C.c_void_p * B)(*[h.data_ptr() for h in hiddens])
+        lens = (C.c_int32 * B)(*[int(v) for v in ctx_lens])
+        cached = (C.c_int32 * B)(*[int(v) for v in n_cached])
+        _check(self._lib.dart_draft_forward_topk_batched(
+            self._h, B, ptrs, lens, cached, K, k, eps,
+            logits_out.data_ptr() if logits_out is not None else None, out[0].data_ptr(),
+            out[1].data_ptr(), _stream_ptr(stream)), "dart_draft_forward_topk_batched")
         return out
 
     def draft_forward_features_batched(self, features, next_tokens, ctx_lens, n_cached, K: int,

@@ -296,7 +296,9 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   if (g.dtype == DART_BF16 && !g.front_end)
     c->lm_select_wgs = gemv_bf16_select_wgs(c->wlm, (g.vocab + 15) / 16, std::min(g.max_K, 8));
   c->topk_chunks_max = std::max(c->topk_chunks_max, c->lm_select_wgs);
-  HIP_TRY(dev_alloc(&c->logits_tmp, (size_t)g.max_K * g.vocab));
+  // logits of one group of sequences, for the combined calls when the caller passes no buffer
+  const int tmp_rows = std::min(c->max_rows, DART_SEQ_GROUP * g.max_K);
+  HIP_TRY(dev_alloc(&c->logits_tmp, (size_t)tmp_rows * g.vocab));
   HIP_TRY(dev_alloc(&c->topk_cand, (size_t)c->max_rows * c->topk_chunks_max * DART_MAX_TOPK));
   HIP_TRY(dev_alloc(&c->topk_ms, (size_t)c->max_rows * c->topk_chunks_max * 2));
   return hipSuccess;
@@ -706,6 +708,44 @@ static dart_status forward_batched(dart_ctx *c, int batch, const void *const *ro
     }
     hipError_t e = forward_group(c, nb, jobs, K, true, logits_out + (size_t)b0 * K * c->cfg.vocab,
                                  (hipStream_t)stream);
+    if (e != hipSuccess) return from_hip(e);
+    for (int i = 0; i < nb; ++i) c->cached_rows[b0 + i] = ctx_len[b0 + i];
+  }
+  return DART_OK;
+}
+
+dart_status dart_draft_forward_topk_batched(dart_ctx *c, int batch, const void *const *hidden,
+                                            const int32_t *ctx_len, const int32_t *n_cached, int K,
+                                            int k, float eps, float *logits_out, int32_t *ids_out,
+                                            float *scores_out, void *stream) {
+  if (!c || !hidden || !ctx_len || !n_cached || !ids_out || !scores_out) return DART_ERR_ARG;
+  if (batch < 1 || batch > c->cfg.max_batch) return DART_ERR_ARG;
+  if (c->cfg.front_end) return DART_ERR_STATE;
+  float dummy = 0.f;
+  for (int b = 0; b < batch; ++b) {
+    dart_status s = check_forward_args(c, b, hidden[b], ctx_len[b], n_cached[b], K, &dummy);
+    if (s != DART_OK) return s;
+  }
+  if (k < 1 || k > DART_MAX_TOPK || k > c->cfg.vocab) return DART_ERR_ARG;
+  const int V = c->cfg.vocab;
+  hipStream_t st = (hipStream_t)stream;
+  for (int b0 = 0; b0 < batch; b0 += DART_SEQ_GROUP) {
+    const int nb = std::min(DART_SEQ_GROUP, batch - b0);
+    SeqJob jobs[DART_SEQ_GROUP];
+    for (int i = 0; i < nb; ++i) {
+      jobs[i] = SeqJob{b0 + i, hidden[b0 + i], ctx_len[b0 + i], n_cached[b0 + i]};
+      c->cached_rows[b0 + i] = 0;
+    }
+    float *lg = logits_out ? logits_out + (size_t)b0 * K * V : nullptr;
+    int32_t *ids = ids_out + (size_t)b0 * K * k;
+    float *sc = scores_out + (size_t)b0 * K * k;
+    // The multi-row LM head leaves the selection to the top-k kernels: a form of it whose
+    // workgroups select their rows' candidates in the epilogue was built and measured no faster
+    // (the selection is bound by instruction issue, about 25 instructions per logit in either
+    // place, and inside the LM head nothing overlaps it).
+    if (!lg) lg = c->logits_tmp;
+    hipError_t e = forward_group(c, nb, jobs, K, true, lg, st);
+    if (e == hipSuccess) e = launch_topk(c, lg, nb * K, V, k, eps, ids, sc, st);
     if (e != hipSuccess) return from_hip(e);
     for (int i = 0; i < nb; ++i) c->cached_rows[b0 + i] = ctx_len[b0 + i];
   }
