@@ -231,8 +231,11 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
       c->kv_rows = std::min(1024, round_up(g.max_ctx, 64));
     // the many-row kernel that keeps the skinny kernel's sums takes the whole cold prefix in
     // passes of up to 4096 rows (512 workgroup units: two per compute unit)
-    c->kv_ordered = !g.front_end && g.max_ctx > 32 && gemm_ordered_supported(c->wqkv, c->split_qkv);
-    if (c->kv_ordered) c->kv_rows = std::min(4096, round_up(g.max_ctx, 64));
+    // (with the front end the FC layer goes through the same kernel, in passes of 2048 rows: its
+    // fp32 feature rows and their operand tiles are 3d wide)
+    c->kv_ordered = g.max_ctx > 32 && gemm_ordered_supported(c->wqkv, c->split_qkv) &&
+                    (!g.front_end || gemm_ordered_supported(c->wfc, c->split_fc));
+    if (c->kv_ordered) c->kv_rows = std::min(g.front_end ? 2048 : 4096, round_up(g.max_ctx, 64));
     if (g.max_batch > 1) {     // the batched entry point runs on the multi-row kernel
       c->gch_qkv = gemm_bf16_chunks(in_dim, c->qkv_dim / 16);
       c->gch_o = gemm_bf16_chunks(c->q_dim, (d + 15) / 16);
@@ -409,6 +412,20 @@ hipError_t input_stage(dart_ctx *c, const SeqBatch &sb, float *xn, float *resid,
 hipError_t kv_pass(dart_ctx *c, const SeqBatch &sb, bool gemm, hipStream_t st) {
   const dart_config &g = c->cfg;
   const int M = sb.row_off[sb.B];
+  if (!gemm && c->kv_ordered && M > 32 && g.front_end) {
+    // single-sequence call with the front end, many rows: the FC layer and the K/V projection both
+    // run on the order-preserving many-row kernel (the skinny kernel's sums bit for bit, chunk
+    // partials already added), their fp32 inputs packed as two-term operand tiles in between
+    HIP_TRY(launch_feature_rows(g.dtype, sb, g.feat_dim, c->feat32, st));
+    HIP_TRY(launch_pack_rows(c->feat32, M, g.feat_dim, 2, c->xpack, st));
+    HIP_TRY(launch_gemm_ordered(c->wfc, 0, (g.d + 15) / 16, M, c->xpack, c->fc_part, g.d, c->split_fc, st));
+    HIP_TRY(launch_front_norm(g.dtype, sb, c->fc_part, 1, 0, c->embed, c->mask_emb, c->g_in, c->g_emb, g.d,
+                              g.rms_eps, c->xn_kv, nullptr, st));
+    HIP_TRY(launch_pack_rows(c->xn_kv, M, c->in_dim, 2, c->xpack, st));
+    HIP_TRY(launch_gemm_ordered(c->wqkv, c->q_dim / 16, 2 * c->kv_dim / 16, M, c->xpack, c->kv_part,
+                                2 * c->kv_dim, c->split_qkv, st));
+    return launch_qkv_post(c, sb, c->kv_part, 1, 0, 2 * c->kv_dim, c->q_dim, st);
+  }
   if (!gemm && c->kv_ordered && M > 32) {
     // single-sequence call, many rows: the input norm writes two-term operand tiles, the
     // order-preserving many-row kernel gives the skinny kernel's K/V sums bit for bit

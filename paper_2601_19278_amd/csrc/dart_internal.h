@@ -267,6 +267,7 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
                             int epi, hipStream_t st,
                             void *out_pack = nullptr);
 int gemm_bf16_chunks(int Kd, int nstrips);
+hipError_t launch_pack_rows(const float *X, int M, int Kd, int terms, void *pack, hipStream_t st);
 // Many rows with the skinny kernel's sums, bit for bit (the K/V build of a long prefix).
 bool gemm_ordered_supported(const DeviceMatrix &W, int nch);
 hipError_t launch_gemm_ordered(const DeviceMatrix &W, int strip0, int nstrips, int M, const void *pack,

@@ -623,6 +623,18 @@ int gemm_bf16_describe(const DeviceMatrix &W, int nstrips, int M, int nchunks, i
                   gemm_bf16_terms(W), a.units, GEMM_THREADS, per_range, passes);
 }
 
+// fp32 rows X[M][Kd] -> packed operand tiles (gemm_bf16_pack_shape(M, Kd) row tiles; terms 2: bf16
+// hi + lo with the skinny kernel's split, terms 1: fp16).
+hipError_t launch_pack_rows(const float *X, int M, int Kd, int terms, void *pack, hipStream_t st) {
+  if (!X || !pack || M < 1 || Kd < 32 || (terms != 1 && terms != 2)) return hipErrorInvalidValue;
+  int ntiles = 0, ksteps = 0;
+  gemm_bf16_pack_shape(M, Kd, &ntiles, &ksteps);
+  const int64_t items = (int64_t)ksteps * ntiles * 64;
+  hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X, M, Kd,
+                     ntiles, ksteps, terms, (u32x4_t *)pack);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, const float *X, int M,
                             void *pack, float *out, int out_stride, size_t chunk_stride, int nchunks,
                             int epi, hipStream_t st, void *out_pack) {
@@ -647,10 +659,7 @@ hipError_t launch_gemm_bf16(const DeviceMatrix &W, int strip0, int nstrips, cons
   a.out_ntiles = a.ntiles;                // the next projection carries the same rows
   const int ksteps = (a.KT + 1) / 2 * 2;
   if (X) {                                               // X == nullptr: pack already holds them
-    const int64_t items = (int64_t)ksteps * a.ntiles * 64;
-    hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, X,
-                       M, W.Kd, a.ntiles, ksteps, terms, (u32x4_t *)pack);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_pack_rows(X, M, W.Kd, terms, pack, st);
     if (e != hipSuccess) return e;
   }
   const dim3 grid(a.units), block(GEMM_THREADS);
