@@ -142,3 +142,54 @@ def test_c5_batched_full_size_chain_with_preset_table():
         np.testing.assert_array_equal(mask[b], ref.mask)
     ctx.close()
     table.close()
+
+
+def test_step_captured_in_a_hip_graph_replays_identically():
+    """The hot calls enqueue kernels only (no allocation, no synchronisation, no host-side copies), so a
+    whole step can be captured into a HIP graph; every replay, with eager steps and synchronisations
+    in between, must reproduce the eager result bit for bit."""
+    import torch
+    import paper_2601_19278_amd as dart
+    cfg = ds.scaled_config("C2", d=512, n_q_heads=8, n_kv_heads=2, head_dim=128, ffn=1536, vocab=40007,
+                           ctx=200, K=8)
+    ctx, W = make_context(cfg, 9700)
+    counts = ds.make_ngram_counts(cfg, 9701)
+    table = dart.NgramTable(cfg.n_gram, counts.keys, counts.succ_ids, counts.succ_counts, 1e-9)
+    h = hidden_to_device(cfg, ds.make_hidden(cfg, 9702))
+    n, K, k = cfg.ctx, cfg.K, cfg.topk
+    dev = h.device
+    tk = (torch.empty((K, k), dtype=torch.int32, device=dev), torch.empty((K, k), dtype=torch.float32, device=dev))
+    tree = (torch.empty((1, cfg.budget), dtype=torch.int32, device=dev),
+            torch.empty((1, cfg.budget), dtype=torch.int32, device=dev),
+            torch.empty((1, cfg.budget, cfg.budget), dtype=torch.uint8, device=dev),
+            torch.empty((1,), dtype=torch.int32, device=dev))
+    tail = torch.from_numpy(counts.keys[5].astype(np.int32)).cuda()[None]
+    params = dart.PruneParams(k=k, beam_w=cfg.beam_w, budget=cfg.budget)
+
+    def step():
+        ctx.draft_forward_topk(h, n, K, k, 1e-9, n_cached=n - 3, out=tk)
+        table.tree_prune(tk[0][None], tk[1][None], tail, params, out=tree)
+
+    ctx.draft_forward(h, n, K)                      # fills the K/V cache (and loads every kernel)
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (*tk, *tree)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for i in range(4):
+        for t in (*tk, *tree):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, (*tk, *tree)):
+            assert torch.equal(a, b), i
+        step()                                      # eager work between the replays
+        torch.cuda.synchronize()
+    ctx.close()
+    table.close()
