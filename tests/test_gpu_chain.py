@@ -95,6 +95,13 @@ def test_full_size_chain_with_preset_table(name):
     tail = counts.keys[123].astype(np.int32)       # a stored context: level 0 looks up a real row
     got = _chain(cfg, ctx, table, hidden, tail)
     _check_stages(cfg, W, model, hidden, tail, got, dict(atol=2e-2, rtol=1e-2))
+    # the combined forward + top-k call (warm) gives the same candidates as the two calls
+    import torch
+    h = hidden_to_device(cfg, hidden)
+    ids_f, scores_f = ctx.draft_forward_topk(h, hidden.shape[0], cfg.K, cfg.topk, 1e-9, n_cached=hidden.shape[0] - 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(ids_f.cpu().numpy(), got[1])
+    np.testing.assert_allclose(scores_f.cpu().numpy(), got[2], rtol=0, atol=2e-6)
     ctx.close()
     table.close()
 
