@@ -15,11 +15,11 @@
 // gives the next beam (first w) and the level's contenders for the global tree (first theta),
 // which are merged into the running best-theta list.  Since the best theta of a union is the
 // best theta of (best theta of one part) + (the other part), the running list equals Alg. 1's
-// "top-theta of T" after the last level.  Three ways of ranking a level: up to 256 expansions
-// with every N-gram score already in LDS (the presets: w*k = 200) -- one wavefront selects the
-// max(w, theta) expansions that matter by a threshold search and ranks only those, one barrier
-// per level (see the kernel); up to 1024 expansions -- ranking by counting over all threads;
-// beyond -- a bitonic sort.
+// "top-theta of T" after the last level.  Three ways of ranking a level: up to 512 expansions
+// (the presets: w*k = 200; the paper's defaults: 20 * 25 = 500) -- one wavefront selects the
+// max(w, theta) expansions that matter by a threshold search and ranks only those (see the
+// kernel); up to 1024 expansions -- ranking by counting over all threads; beyond -- a bitonic
+// sort.
 //
 // N-gram lookups.  The context a beam entry presents at level L is the last N-1 tokens of its
 // path: (candidate a of level L-2, candidate b of level L-1) for a trigram.  Which paths
@@ -28,9 +28,14 @@
 // small enough for LDS (k <= 13 at K = 8), the kernel resolves all of them before the first
 // level -- every hash probe and every successor-row read of the call in flight at once, two
 // memory round trips in total -- and the K levels then run without touching memory.
-// Otherwise each level looks up its own beam entries (at most w per level, as in App. C.2).
+// Otherwise, when at least the table rows of all possible contexts fit (k <= 45 at K = 8),
+// all hash probes still go out before the first level and a level only fetches the successor
+// rows of its own beam entries (at most w per level, as in App. C.2); beyond that each level
+// also probes for its beam entries' contexts.
 // A loaded successor is matched against its level's k candidates through a small bucketed
 // table of the candidate ids in LDS (one 16-byte read per successor instead of k compares).
+#include <type_traits>
+
 #include "common.h"
 #include "dart_internal.h"
 
@@ -40,10 +45,21 @@ constexpr int PRUNE_THREADS = 1024;    // one workgroup per sequence; many phase
 static_assert(DART_MAX_LEVEL_NODES <= 16384, "a level's pair scores share the ng array");
 constexpr int PRUNE_NG_CELLS = 16384;  // N-gram scores of all possible (context, candidate) pairs
 constexpr int PRUNE_NG_CTX = 1280;     // possible contexts of one call resolved up front
-constexpr int PRUNE_SMALL = 256;       // expansions per level the short-level loop handles (w * k)
+constexpr int PRUNE_SMALL = 512;       // expansions per level the short-level loop handles (w * k)
+
+// Short-level mode (at most PRUNE_SMALL expansions per level): the buffers of the wavefront that
+// ranks a level.  They share their memory with the expansion keys of the general mode.
+struct PruneSmall {
+  __align__(16) uint32_t sel_sc[PRUNE_SMALL];  // sortable scores of the level's expansions that matter
+  int32_t sel_e[PRUNE_SMALL];                  // ... and their (creation index << 16) | (beam entry << 8) | candidate
+  uint8_t pos[DART_MAX_K * PRUNE_SMALL];       // output index of the node (level, creation)
+};
 
 struct PruneShared {
-  uint64_t keys[DART_MAX_LEVEL_NODES];        // this level's expansions
+  union {
+    uint64_t keys[DART_MAX_LEVEL_NODES];      // general mode: this level's expansions (emission: the mask)
+    PruneSmall sm;
+  };
   int32_t cand_id[DART_MAX_K * DART_MAX_TOPK];
   float cand_sc[DART_MAX_K * DART_MAX_TOPK];
   // beam (double buffered)
@@ -78,12 +94,9 @@ struct PruneShared {
   // emission
   int32_t out_idx[DART_MAX_BUDGET];
   int32_t out_par[DART_MAX_BUDGET];
-  // short-level mode (at most PRUNE_SMALL expansions per level)
-  __align__(16) uint32_t sel_sc[PRUNE_SMALL];  // sortable scores of the level's expansions that matter
-  int32_t sel_e[PRUNE_SMALL];                  // ... and their (creation index << 16) | (beam entry << 8) | candidate
+  // short-level mode
   __align__(16) uint32_t lvl_sc[2][DART_MAX_BUDGET];   // scores of lvl_key[][], padded with 0 to a multiple of 4
   __align__(16) uint32_t best_sc[2][DART_MAX_BUDGET];  // scores of best_key[][], likewise
-  uint8_t pos[DART_MAX_K * PRUNE_SMALL];       // output index of the node (level, creation)
   int32_t lvl_cnt[2][DART_MAX_K];              // selected nodes per level, per wavefront
 };
 
@@ -100,7 +113,7 @@ __device__ __forceinline__ uint4 slot_load(const NgramTableDev &tab, uint64_t h)
 // Linear probing from slot h whose content `raw` has already been fetched: row of the packed
 // context, or -1.  A table is at most half full and the probe count is bounded by its size,
 // so the loop always ends.
-__device__ int32_t ngram_probe(const NgramSlot *slots, uint64_t mask, uint64_t packed, uint64_t h,
+__device__ __forceinline__ int32_t ngram_probe(const NgramSlot *slots, uint64_t mask, uint64_t packed, uint64_t h,
                                uint4 raw) {
   for (uint64_t probes = 0; probes <= mask; ++probes) {
     const uint64_t kk = ((uint64_t)raw.y << 32) | raw.x;
@@ -114,7 +127,7 @@ __device__ int32_t ngram_probe(const NgramSlot *slots, uint64_t mask, uint64_t p
 
 // Back-off (optional): the context without its oldest token, in the lower-order table.  Only a
 // trigram table can carry one, so the shorter context is the newest token alone.
-__device__ int32_t ngram_backoff_find(const NgramTableDev &tab, int tok) {
+__device__ __forceinline__ int32_t ngram_backoff_find(const NgramTableDev &tab, int tok) {
   if (!tab.bo_slots) return -1;
   const uint64_t packed = (uint64_t)(uint32_t)tok;
   const uint64_t h = mix64(packed) & tab.bo_slot_mask;
@@ -125,12 +138,12 @@ __device__ int32_t ngram_backoff_find(const NgramTableDev &tab, int tok) {
 
 // Finish a lookup of context (.., tok) whose first slot `raw` (at index h) has already been
 // fetched: its row, else its back-off row (flagged), else -1.
-__device__ int32_t ngram_resolve(const NgramTableDev &tab, uint64_t packed, uint64_t h, uint4 raw, int tok) {
+__device__ __forceinline__ int32_t ngram_resolve(const NgramTableDev &tab, uint64_t packed, uint64_t h, uint4 raw, int tok) {
   const int32_t row = ngram_probe(tab.slots, tab.slot_mask, packed, h, raw);
   return row >= 0 ? row : ngram_backoff_find(tab, tok);
 }
 
-__device__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed, int tok) {
+__device__ __forceinline__ int32_t ngram_find(const NgramTableDev &tab, uint64_t packed, int tok) {
   const uint64_t h = mix64(packed) & tab.slot_mask;
   return ngram_resolve(tab, packed, h, slot_load(tab, h), tok);
 }
@@ -160,7 +173,7 @@ __device__ __forceinline__ uint32_t cand_hash(int32_t id, int H) {
 }
 
 // Enter the K*k candidates (ids distinct within a level).  Ends with a barrier.
-__device__ void build_cand_table(PruneShared &sh, int K, int k, int t) {
+__device__ __forceinline__ void build_cand_table(PruneShared &sh, int K, int k, int t) {
   const int H = cand_buckets(k);
   for (int i = t; i < K * H * 4; i += PRUNE_THREADS) sh.ch_id[i] = -1;
   if (t < K) sh.ch_over[t] = 0;
@@ -270,7 +283,60 @@ __device__ __forceinline__ int count_above(const uint4 *s4, int n4, uint32_t min
   return r;
 }
 
-__device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, int K, int k,
+// The two newest tokens (prev, tok) of possible context g (numbering of ctx_offset).
+__device__ __forceinline__ void context_tokens(const PruneShared &sh, int g, int k, int ctx_len, int prev0,
+                                               int root, int &prev, int &tok) {
+  int L, idx;
+  if (g == 0) {
+    L = 0, idx = 0;
+  } else if (ctx_len < 2) {
+    L = 1 + (g - 1) / k, idx = (g - 1) % k;
+  } else if (g < 1 + k) {
+    L = 1, idx = g - 1;
+  } else {
+    L = 2 + (g - 1 - k) / (k * k), idx = (g - 1 - k) % (k * k);
+  }
+  if (L == 0) {
+    prev = prev0, tok = root;
+  } else if (ctx_len < 2 || L == 1) {
+    prev = root, tok = sh.cand_id[(L - 1) * k + idx];
+  } else {
+    prev = sh.cand_id[(L - 2) * k + idx / k], tok = sh.cand_id[(L - 1) * k + idx % k];
+  }
+}
+
+// Table rows of all NC possible contexts into rows[] (-1 = unseen), when the pair scores of all
+// of them do not fit LDS but their rows do: the hash probes of the whole call are in flight
+// together (four per thread at a time) instead of one dependent probe per level, and a level
+// only fetches its beam entries' successor rows.
+__device__ __forceinline__ void resolve_context_rows(const PruneShared &sh, const NgramTableDev &tab, int NC, int k,
+                                     int ctx_len, int prev0, int root, int t, int32_t *rows) {
+  constexpr int Q = 4;
+  for (int g0 = 0; g0 < NC; g0 += Q * PRUNE_THREADS) {
+    uint64_t packed[Q], hslot[Q];
+    uint4 raw[Q];
+    int newest[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      const int g = g0 + q * PRUNE_THREADS + t;
+      if (g < NC) {
+        int prev, tok;
+        context_tokens(sh, g, k, ctx_len, prev0, root, prev, tok);
+        packed[q] = pack_context(ctx_len, prev, tok);
+        newest[q] = tok;
+        hslot[q] = mix64(packed[q]) & tab.slot_mask;
+        raw[q] = slot_load(tab, hslot[q]);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      const int g = g0 + q * PRUNE_THREADS + t;
+      if (g < NC) rows[g] = ngram_resolve(tab, packed[q], hslot[q], raw[q], newest[q]);
+    }
+  }
+}
+
+__device__ __forceinline__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, int K, int k,
                                      int ctx_len, int prev0, int root, int t) {
   const int NC = ctx_offset(K, k, ctx_len);
   for (int e = t; e < NC * k; e += PRUNE_THREADS) sh.ng[e] = tab.logp_miss;
@@ -285,24 +351,8 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
   for (int q = 0; q < Q; ++q) {
     const int g = t + q * PRUNE_THREADS;
     if (g < NC) {
-      int L, idx;
-      if (g == 0) {
-        L = 0, idx = 0;
-      } else if (ctx_len < 2) {
-        L = 1 + (g - 1) / k, idx = (g - 1) % k;
-      } else if (g < 1 + k) {
-        L = 1, idx = g - 1;
-      } else {
-        L = 2 + (g - 1 - k) / (k * k), idx = (g - 1 - k) % (k * k);
-      }
       int prev, tok;
-      if (L == 0) {
-        prev = prev0, tok = root;
-      } else if (ctx_len < 2 || L == 1) {
-        prev = root, tok = sh.cand_id[(L - 1) * k + idx];
-      } else {
-        prev = sh.cand_id[(L - 2) * k + idx / k], tok = sh.cand_id[(L - 1) * k + idx % k];
-      }
+      context_tokens(sh, g, k, ctx_len, prev0, root, prev, tok);
       packed[q] = pack_context(ctx_len, prev, tok);
       newest[q] = tok;
       hslot[q] = mix64(packed[q]) & tab.slot_mask;
@@ -404,6 +454,206 @@ __device__ void resolve_all_contexts(PruneShared &sh, const NgramTableDev &tab, 
   }
 }
 
+// The level loop of the short-level mode (see the kernel).  NS: scores per lane of the ranking
+// wavefront (4 up to 256 expansions per level, 8 up to 512).  PRE: every N-gram score is in LDS
+// already (up-front mode); otherwise the scores of a level's pairs are fetched between levels.  nb, n_best, cur, bcur: beam size,
+// best-list length and the live halves of the double buffers, carried on to the emission.
+template <int NS, bool PRE>
+__device__ __forceinline__ void short_levels(PruneShared &sh, const NgramTableDev &tab,
+                                             const PruneLevelWeights &lw, int K, int k, int beam_w,
+                                             int theta, int ctx_len, float w_ng, bool pre_rows,
+                                             const int32_t *rows_all, int t, int &nb, int &n_best,
+                                             int &cur, int &bcur) {
+  const int lane = t & 63, wav = t >> 6;
+  int n_lvl_prev = 0;
+  // Both lists are sorted and the level list's entries all have a higher level than the best
+  // list's, so between the lists the score decides and a tie goes to the best list's entry.
+  // Done by threads 64 .. 64 + n_best + n_lvl_prev (at most 2 * 127 of them).
+  auto merge_prev = [&](int lb) {
+    const int bnx = bcur ^ 1;
+    const int n_out = min(theta, n_best + n_lvl_prev);
+    const int tt = t - 64;
+    if (tt >= 0 && tt < n_best + n_lvl_prev) {
+      uint64_t key;
+      uint32_t sc;
+      int tok, par, rank;
+      if (tt < n_best) {
+        key = sh.best_key[bcur][tt];
+        sc = sh.best_sc[bcur][tt];
+        tok = sh.best_tok[bcur][tt];
+        par = sh.best_par[bcur][tt];
+        rank = tt + count_above(reinterpret_cast<const uint4 *>(sh.lvl_sc[lb]),
+                                (n_lvl_prev + 3) >> 2, sc, 0);
+      } else {
+        const int j0 = tt - n_best;
+        key = sh.lvl_key[lb][j0];
+        sc = sh.lvl_sc[lb][j0];
+        tok = sh.lvl_tok[lb][j0];
+        par = sh.lvl_par[lb][j0];
+        const int b4 = (n_best + 3) >> 2;
+        rank = j0 + (n_best ? count_above(reinterpret_cast<const uint4 *>(sh.best_sc[bcur]), b4, sc, b4) : 0);
+        if (sc == 0) rank = theta;                       // an entry the level did not keep
+      }
+      if (rank < theta) {
+        sh.best_key[bnx][rank] = key;
+        sh.best_sc[bnx][rank] = sc;
+        sh.best_tok[bnx][rank] = tok;
+        sh.best_par[bnx][rank] = par;
+      }
+    } else if (t >= 512 && t - 512 + n_out < ((n_out + 3) & ~3)) {
+      sh.best_sc[bnx][t - 512 + n_out] = 0;              // padding of the merged list
+    }
+    n_best = n_out;
+    bcur = bnx;
+  };
+  for (int L = 0; L < K; ++L) {
+    const int n_new = nb * k;
+    const int nb_next = min(beam_w, n_new);
+    const int n_lvl = min(theta, n_new);
+    const int nxt = cur ^ 1, lb = L & 1;
+    const bool last = L + 1 == K;
+    if (wav == 0) {
+      const float wl = lw.w_logit[L], wv = lw.w_level[L];
+      // scores of expansions lane, lane + 64, ... (0 = none).  Indices are clamped instead of
+      // branched on, so that the dependent LDS chains overlap; e / k by a reciprocal (exact for
+      // e < 512, k <= 64: e * k < 2^16).
+      uint32_t sc[NS];
+      int bc[NS];                             // (beam entry << 8) | candidate
+      const uint32_t inv_k = (65536u + k - 1) / k;
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        const int e = min(lane + 64 * i, n_new - 1);
+        const int bb = (int)(((uint32_t)e * inv_k) >> 16), c = e - bb * k;
+        const int p_ci = sh.beam_ci[cur][bb];
+        const int gctx = ctx_offset(L, k, ctx_len) +
+                         (L < 2 || ctx_len < 2 ? p_ci : sh.beam_pi[cur][bb] * k + p_ci);
+        const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
+        const float g = __fmul_rn(w_ng, sh.ng[PRE ? gctx * k + c : e]);
+        const float inc = __fmul_rn(__fadd_rn(a, g), wv);
+        const uint32_t v = f32_sortable(__fadd_rn(sh.beam_score[cur][bb], inc));
+        sc[i] = lane + 64 * i < n_new ? v : 0;
+        bc[i] = (bb << 8) | c;
+      }
+      // Once the best list is full, its last score is a floor: an expansion at or below it
+      // can never enter the tree (a tie goes to the lower level), so the level list needs
+      // only the expansions above the floor.  The list as merged two levels ago is the one
+      // this wavefront may read; its floor is lower than the current one, which is safe.
+      int n_keep = n_lvl;
+      if (theta > 0 && n_best == theta) {
+        const uint32_t floor_sc = sh.best_sc[bcur][theta - 1];
+        int above_floor = 0;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) above_floor += (int)__popcll(__ballot(sc[i] > floor_sc));
+        n_keep = min(n_lvl, above_floor);
+      }
+      const int need = max(nb_next, n_keep);   // expansions of this level that matter (<= n_new)
+      // A threshold T with at least `need` scores >= T, found bit by bit from the top (every
+      // accepted bit keeps that property).  The search stops as soon as few more than `need`
+      // scores are left above T: any such T selects a superset of the expansions that matter.
+      // The bits that all scores of the level share (sign, exponent and often the first
+      // mantissa bits) are taken over at once: T starts as that common prefix, which is <= every
+      // score, and the search begins at the highest bit in which two scores differ.
+      uint32_t hi = 0, lo = ~0u;
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        hi = max(hi, sc[i]);
+        lo = min(lo, sc[i] ? sc[i] : ~0u);
+      }
+      const uint32_t top = wave_max_u32(hi);
+      const uint32_t bot = ~wave_max_u32(~lo);
+      const int first = 31 - __clz((int)(top ^ bot));           // -1: all scores are equal
+      uint32_t T = first < 0 ? top : top & ~((2u << first) - 1u);
+      int above = n_new;
+      const int enough = need <= 64 ? 64 : need + 8;   // up to 64 are ranked in one pass
+      for (int bit = first; bit >= 0 && above > enough; --bit) {
+        const uint32_t trial = T | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) cnt += (int)__popcll(__ballot(sc[i] >= trial));
+        if (cnt >= need) {
+          T = trial;
+          above = cnt;
+        }
+      }
+      // the expansions with score >= T (real scores are > 0, T >= the smallest of them), in
+      // creation order
+      int m = 0;
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        const bool in = sc[i] >= T && sc[i] != 0;
+        const uint64_t mask = __ballot(in);
+        if (in) {
+          const int at = m + __popcll(mask & (((uint64_t)1 << lane) - 1));
+          sh.sm.sel_sc[at] = sc[i];
+          sh.sm.sel_e[at] = ((lane + 64 * i) << 16) | bc[i];
+        }
+        m += __popcll(mask);
+      }
+      if (lane < ((m + 3) & ~3) - m) sh.sm.sel_sc[m + lane] = 0;      // pad the last group of four
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // rank among the selected = rank among all: scores above mine + equal scores created
+      // before me (= earlier in the list)
+      const uint4 *s4 = reinterpret_cast<const uint4 *>(sh.sm.sel_sc);
+      for (int p0 = lane; p0 < m; p0 += 64) {
+        const uint32_t mine = sh.sm.sel_sc[p0];
+        const int ebc = sh.sm.sel_e[p0];
+        const int e = ebc >> 16, bb = (ebc >> 8) & 0xFF, c = ebc & 0xFF;
+        const int jt = p0 >> 2;
+        int r = count_above(s4, (m + 3) >> 2, mine, jt);
+        {
+          const uint4 v = s4[jt];                        // my own group: ties before me
+          const int i = p0 & 3;
+          r += (i > 0 && v.x == mine) + (i > 1 && v.y == mine) + (i > 2 && v.z == mine);
+        }
+        if (r < need) {
+          const int tok = sh.cand_id[L * k + c];
+          if (r < nb_next) {
+            sh.beam_score[nxt][r] = f32_unsortable(mine);
+            sh.beam_tok[nxt][r] = tok;
+            sh.beam_prev[nxt][r] = sh.beam_tok[cur][bb];
+            sh.beam_cre[nxt][r] = e;
+            sh.beam_ci[nxt][r] = c;
+            sh.beam_pi[nxt][r] = sh.beam_ci[cur][bb];
+            if (!PRE && !last) {                         // table row of the context it will present
+              const int gnext = ctx_offset(L + 1, k, ctx_len) +
+                                (L + 1 < 2 || ctx_len < 2 ? c : sh.beam_ci[cur][bb] * k + c);
+              sh.beam_row[r] = pre_rows ? rows_all[gnext]
+                                        : ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][bb], tok), tok);
+            }
+          }
+          if (r < n_keep) {
+            sh.lvl_key[lb][r] = ((uint64_t)mine << 32) | ((uint64_t)(15 - L) << 28) |
+                                (uint64_t)(0x0FFFFFFF - e);
+            sh.lvl_sc[lb][r] = mine;
+            sh.lvl_tok[lb][r] = tok;
+            sh.lvl_par[lb][r] = sh.beam_cre[cur][bb];
+          }
+        }
+      }
+      // the entries not kept and the padding of the last group of four: score 0, which the
+      // merge ranks below every real entry
+      for (int j = n_keep + lane; j < ((n_lvl + 3) & ~3); j += 64) sh.lvl_sc[lb][j] = 0;
+      // the next level's scores read what this level placed
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    if (L > 0) merge_prev(lb ^ 1);
+    __syncthreads();
+    if (!PRE && !last) {                  // N-gram scores of the next level's (beam entry, candidate) pairs
+      score_rows(sh, tab, nb_next, k, L + 1, t);
+      __syncthreads();
+    }
+    n_lvl_prev = n_lvl;
+    cur = nxt;
+    nb = nb_next;
+  }
+  merge_prev((K - 1) & 1);
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     const int32_t *__restrict__ ids, const float *__restrict__ scores, int K,
     const int32_t *__restrict__ ctx_tail, NgramTableDev tab, int k, int beam_w, int budget,
@@ -429,8 +679,12 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   const int root = ctx_tail[ctx_len - 1];
   const int prev0 = ctx_len >= 2 ? ctx_tail[ctx_len - 2] : 0;
   // all possible contexts up front when they fit (uniform for the workgroup)
-  const bool pre = ctx_offset(K, k, ctx_len) <= PRUNE_NG_CTX &&
-                   ctx_offset(K, k, ctx_len) * k <= PRUNE_NG_CELLS;
+  const int NC = ctx_offset(K, k, ctx_len);
+  const bool pre = NC <= PRUNE_NG_CTX && NC * k <= PRUNE_NG_CELLS;
+  // otherwise at least the rows of all possible contexts, when they fit behind the pair scores
+  // of one level (at most DART_MAX_LEVEL_NODES cells of ng are used level by level)
+  const bool pre_rows = !pre && NC <= PRUNE_NG_CELLS - DART_MAX_LEVEL_NODES;
+  int32_t *const rows_all = reinterpret_cast<int32_t *>(sh.ng + DART_MAX_LEVEL_NODES);
   if (t == 0) {
     sh.beam_score[0][0] = 0.f;
     sh.beam_tok[0][0] = root;
@@ -438,198 +692,49 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     sh.beam_cre[0][0] = -1;                    // the root
     sh.beam_ci[0][0] = 0;
     sh.beam_pi[0][0] = 0;
-    if (!pre) sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev0, root), root);
+    if (!pre && !pre_rows) sh.beam_row[0] = ngram_find(tab, pack_context(ctx_len, prev0, root), root);
   }
   int nb = 1, n_best = 0, cur = 0, bcur = 0;
   __syncthreads();
   build_cand_table(sh, K, k, t);
-  if (pre)
+  if (pre) {
     resolve_all_contexts(sh, tab, K, k, ctx_len, prev0, root, t);
-  else
+  } else {
+    if (pre_rows) {
+      resolve_context_rows(sh, tab, NC, k, ctx_len, prev0, root, t, rows_all);
+      __syncthreads();
+      if (t == 0) sh.beam_row[0] = rows_all[0];
+      __syncthreads();
+    }
     score_rows(sh, tab, 1, k, 0, t);
+  }
   __syncthreads();
 
-  // Short-level mode: every level has at most PRUNE_SMALL expansions and every N-gram score is
-  // already in LDS.  Ranking all w*k expansions of a level by counting costs (w*k)^2 compares,
-  // but only the best max(w, theta) of them are ever used.  So one wavefront holds the level's
-  // scores in registers (four per lane), finds a score T at or just below that of the last
-  // expansion that matters by a bitwise search with ballots, compacts the expansions with
+  // Short-level mode: every level has at most PRUNE_SMALL expansions.  Ranking all w*k expansions
+  // of a level by counting costs (w*k)^2 compares (and as many LDS reads), but only the best
+  // max(w, theta) of them are ever used.  So one wavefront holds the level's scores in registers
+  // (four per lane up to 256 expansions, eight beyond), finds a score T at or just below that of
+  // the last expansion that matters by a bitwise search with ballots, compacts the expansions with
   // score >= T into LDS in creation order and ranks only those among themselves (32-bit
   // sortable scores, read four at a time; among equal scores the earlier creation wins, as in
-  // the 64-bit key).  That wavefront runs the whole beam recursion without waiting for anyone;
-  // two other wavefronts merge the previous level's list into the best list meanwhile (the
-  // level lists are double buffered), and a level costs one barrier.
-  const bool small = pre && beam_w * k <= PRUNE_SMALL;
+  // the 64-bit key).  Two other wavefronts merge the previous level's list into the best list
+  // meanwhile (the level lists are double buffered).  With every N-gram score already in LDS
+  // (up-front mode) that wavefront runs the whole beam recursion and a level costs one barrier;
+  // otherwise it also notes the table rows of the next beam, and all threads fetch those rows'
+  // successors between two levels (score_rows).
+  const bool small = beam_w * k <= PRUNE_SMALL;
   if (small) {
-    const int lane = t & 63, wav = t >> 6;
-    int n_lvl_prev = 0;
-    // Both lists are sorted and the level list's entries all have a higher level than the best
-    // list's, so between the lists the score decides and a tie goes to the best list's entry.
-    // Done by threads 64 .. 64 + n_best + n_lvl_prev (at most 2 * 127 of them).
-    auto merge_prev = [&](int lb) {
-      const int bnx = bcur ^ 1;
-      const int n_out = min(theta, n_best + n_lvl_prev);
-      const int tt = t - 64;
-      if (tt >= 0 && tt < n_best + n_lvl_prev) {
-        uint64_t key;
-        uint32_t sc;
-        int tok, par, rank;
-        if (tt < n_best) {
-          key = sh.best_key[bcur][tt];
-          sc = sh.best_sc[bcur][tt];
-          tok = sh.best_tok[bcur][tt];
-          par = sh.best_par[bcur][tt];
-          rank = tt + count_above(reinterpret_cast<const uint4 *>(sh.lvl_sc[lb]),
-                                  (n_lvl_prev + 3) >> 2, sc, 0);
-        } else {
-          const int j0 = tt - n_best;
-          key = sh.lvl_key[lb][j0];
-          sc = sh.lvl_sc[lb][j0];
-          tok = sh.lvl_tok[lb][j0];
-          par = sh.lvl_par[lb][j0];
-          const int b4 = (n_best + 3) >> 2;
-          rank = j0 + (n_best ? count_above(reinterpret_cast<const uint4 *>(sh.best_sc[bcur]), b4, sc, b4) : 0);
-          if (sc == 0) rank = theta;                       // an entry the level did not keep
-        }
-        if (rank < theta) {
-          sh.best_key[bnx][rank] = key;
-          sh.best_sc[bnx][rank] = sc;
-          sh.best_tok[bnx][rank] = tok;
-          sh.best_par[bnx][rank] = par;
-        }
-      } else if (t >= 512 && t - 512 + n_out < ((n_out + 3) & ~3)) {
-        sh.best_sc[bnx][t - 512 + n_out] = 0;              // padding of the merged list
-      }
-      n_best = n_out;
-      bcur = bnx;
-    };
-    for (int L = 0; L < K; ++L) {
-      const int n_new = nb * k;
-      const int nb_next = min(beam_w, n_new);
-      const int n_lvl = min(theta, n_new);
-      const int nxt = cur ^ 1, lb = L & 1;
-      if (wav == 0) {
-        const float wl = lw.w_logit[L], wv = lw.w_level[L];
-        // scores of expansions lane, lane + 64, lane + 128, lane + 192 (0 = none).  Indices are
-        // clamped instead of branched on, so that the four dependent LDS chains overlap;
-        // e / k by a reciprocal (exact for e < 256, k <= 64: e * k < 2^16).
-        uint32_t sc[4];
-        int bc[4];                              // (beam entry << 8) | candidate
-        const uint32_t inv_k = (65536u + k - 1) / k;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int e = min(lane + 64 * i, n_new - 1);
-          const int bb = (int)(((uint32_t)e * inv_k) >> 16), c = e - bb * k;
-          const int p_ci = sh.beam_ci[cur][bb];
-          const int gctx = ctx_offset(L, k, ctx_len) +
-                           (L < 2 || ctx_len < 2 ? p_ci : sh.beam_pi[cur][bb] * k + p_ci);
-          const float a = __fmul_rn(wl, sh.cand_sc[L * k + c]);
-          const float g = __fmul_rn(w_ng, sh.ng[gctx * k + c]);
-          const float inc = __fmul_rn(__fadd_rn(a, g), wv);
-          const uint32_t v = f32_sortable(__fadd_rn(sh.beam_score[cur][bb], inc));
-          sc[i] = lane + 64 * i < n_new ? v : 0;
-          bc[i] = (bb << 8) | c;
-        }
-        // Once the best list is full, its last score is a floor: an expansion at or below it
-        // can never enter the tree (a tie goes to the lower level), so the level list needs
-        // only the expansions above the floor.  The list as merged two levels ago is the one
-        // this wavefront may read; its floor is lower than the current one, which is safe.
-        int n_keep = n_lvl;
-        if (theta > 0 && n_best == theta) {
-          const uint32_t floor_sc = sh.best_sc[bcur][theta - 1];
-          n_keep = min(n_lvl, (int)(__popcll(__ballot(sc[0] > floor_sc)) + __popcll(__ballot(sc[1] > floor_sc)) +
-                                    __popcll(__ballot(sc[2] > floor_sc)) + __popcll(__ballot(sc[3] > floor_sc))));
-        }
-        const int need = max(nb_next, n_keep);   // expansions of this level that matter (<= n_new)
-        // A threshold T with at least `need` scores >= T, found bit by bit from the top (every
-        // accepted bit keeps that property).  The search stops as soon as few more than `need`
-        // scores are left above T: any such T selects a superset of the expansions that matter.
-        // The bits that all scores of the level share (sign, exponent and often the first
-        // mantissa bits) are taken over at once: T starts as that common prefix, which is <= every
-        // score, and the search begins at the highest bit in which two scores differ.
-        const uint32_t top = wave_max_u32(max(max(sc[0], sc[1]), max(sc[2], sc[3])));
-        const uint32_t bot = ~wave_max_u32(~min(min(sc[0] ? sc[0] : ~0u, sc[1] ? sc[1] : ~0u),
-                                                min(sc[2] ? sc[2] : ~0u, sc[3] ? sc[3] : ~0u)));
-        const int first = 31 - __clz((int)(top ^ bot));           // -1: all scores are equal
-        uint32_t T = first < 0 ? top : top & ~((2u << first) - 1u);
-        int above = n_new;
-        const int enough = need <= 64 ? 64 : need + 8;   // up to 64 are ranked in one pass
-        for (int bit = first; bit >= 0 && above > enough; --bit) {
-          const uint32_t trial = T | (1u << bit);
-          const int cnt = __popcll(__ballot(sc[0] >= trial)) + __popcll(__ballot(sc[1] >= trial)) +
-                          __popcll(__ballot(sc[2] >= trial)) + __popcll(__ballot(sc[3] >= trial));
-          if (cnt >= need) {
-            T = trial;
-            above = cnt;
-          }
-        }
-        // the expansions with score >= T (real scores are > 0, T >= the smallest of them), in
-        // creation order
-        int m = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bool in = sc[i] >= T && sc[i] != 0;
-          const uint64_t mask = __ballot(in);
-          if (in) {
-            const int at = m + __popcll(mask & (((uint64_t)1 << lane) - 1));
-            sh.sel_sc[at] = sc[i];
-            sh.sel_e[at] = ((lane + 64 * i) << 16) | bc[i];
-          }
-          m += __popcll(mask);
-        }
-        if (lane < ((m + 3) & ~3) - m) sh.sel_sc[m + lane] = 0;      // pad the last group of four
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        // rank among the selected = rank among all: scores above mine + equal scores created
-        // before me (= earlier in the list)
-        const uint4 *s4 = reinterpret_cast<const uint4 *>(sh.sel_sc);
-        for (int p0 = lane; p0 < m; p0 += 64) {
-          const uint32_t mine = sh.sel_sc[p0];
-          const int ebc = sh.sel_e[p0];
-          const int e = ebc >> 16, bb = (ebc >> 8) & 0xFF, c = ebc & 0xFF;
-          const int jt = p0 >> 2;
-          int r = count_above(s4, (m + 3) >> 2, mine, jt);
-          {
-            const uint4 v = s4[jt];                        // my own group: ties before me
-            const int i = p0 & 3;
-            r += (i > 0 && v.x == mine) + (i > 1 && v.y == mine) + (i > 2 && v.z == mine);
-          }
-          if (r < need) {
-            const int tok = sh.cand_id[L * k + c];
-            if (r < nb_next) {
-              sh.beam_score[nxt][r] = f32_unsortable(mine);
-              sh.beam_tok[nxt][r] = tok;
-              sh.beam_prev[nxt][r] = sh.beam_tok[cur][bb];
-              sh.beam_cre[nxt][r] = e;
-              sh.beam_ci[nxt][r] = c;
-              sh.beam_pi[nxt][r] = sh.beam_ci[cur][bb];
-            }
-            if (r < n_keep) {
-              sh.lvl_key[lb][r] = ((uint64_t)mine << 32) | ((uint64_t)(15 - L) << 28) |
-                                  (uint64_t)(0x0FFFFFFF - e);
-              sh.lvl_sc[lb][r] = mine;
-              sh.lvl_tok[lb][r] = tok;
-              sh.lvl_par[lb][r] = sh.beam_cre[cur][bb];
-            }
-          }
-        }
-        // the entries not kept and the padding of the last group of four: score 0, which the
-        // merge ranks below every real entry
-        for (int j = n_keep + lane; j < ((n_lvl + 3) & ~3); j += 64) sh.lvl_sc[lb][j] = 0;
-        // the next level's scores read what this level placed
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      }
-      if (L > 0) merge_prev(lb ^ 1);
-      __syncthreads();
-      n_lvl_prev = n_lvl;
-      cur = nxt;
-      nb = nb_next;
+#define DART_SHORT_LEVELS(NS_, PRE_)                                                                  \
+  short_levels<NS_, PRE_>(sh, tab, lw, K, k, beam_w, theta, ctx_len, w_ng, pre_rows, rows_all, t, nb, \
+                          n_best, cur, bcur)
+    if (beam_w * k <= 256) {
+      if (pre) DART_SHORT_LEVELS(4, true);
+      else DART_SHORT_LEVELS(4, false);
+    } else {
+      if (pre) DART_SHORT_LEVELS(8, true);
+      else DART_SHORT_LEVELS(8, false);
     }
-    merge_prev((K - 1) & 1);
-    __syncthreads();
+#undef DART_SHORT_LEVELS
   }
 
   for (int L = 0; !small && L < K; ++L) {
@@ -659,6 +764,12 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
              (uint64_t)(0x0FFFFFFF - e);
     };
 
+    // possible-context number that candidate c of this level, expanded from beam entry b, presents
+    // at the next level: (its parent's candidate, its own candidate)
+    auto next_context = [&](int c, int b) {
+      return ctx_offset(L + 1, k, ctx_len) + (L + 1 < 2 || ctx_len < 2 ? c : sh.beam_ci[cur][b] * k + c);
+    };
+
     if (n_new <= PRUNE_THREADS) {
       // Register-resident path: thread e (< n_new) owns expansion e.  Keys are ranked by
       // counting the keys that beat them (keys are unique); with few expansions the count of
@@ -678,7 +789,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
         key = expansion_key(e, tok, bb);
         sh.keys[e] = key;
         sh.rank[e] = 0;
-        if (!last && !pre) {
+        if (!last && !pre && !pre_rows) {
           packed = pack_context(ctx_len, sh.beam_tok[cur][bb], tok);
           hslot = mix64(packed) & tab.slot_mask;
           raw = slot_load(tab, hslot);
@@ -715,7 +826,8 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
       }
       // beam_row of this level was last read before the barriers above: safe to overwrite
       if (owner && !last && !pre && r < nb_next)
-        sh.beam_row[r] = ngram_resolve(tab, packed, hslot, raw, tok);
+        sh.beam_row[r] = pre_rows ? rows_all[next_context(e - bb * k, bb)]
+                                  : ngram_resolve(tab, packed, hslot, raw, tok);
     } else {
       // General path (up to 4096 expansions): bitonic sort of the keys in LDS.
       int P = 2, logP = 1;
@@ -756,7 +868,9 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
           sh.beam_cre[nxt][t] = e;
           sh.beam_ci[nxt][t] = c;
           sh.beam_pi[nxt][t] = sh.beam_ci[cur][b];
-          if (!last && !pre) row = ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk), tk);
+          if (!last && !pre)
+            row = pre_rows ? rows_all[next_context(c, b)]
+                           : ngram_find(tab, pack_context(ctx_len, sh.beam_tok[cur][b], tk), tk);
         }
         if (t < n_lvl) {
           sh.lvl_key[0][t] = kk;
@@ -827,19 +941,19 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
       }
     }
     for (int i = t; i < K * PRUNE_SMALL / 16; i += PRUNE_THREADS)
-      reinterpret_cast<uint4 *>(sh.pos)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
+      reinterpret_cast<uint4 *>(sh.sm.pos)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
     __syncthreads();
     if (t < n_best) {
       int idx = 1 + within + (wav == 1 ? sh.lvl_cnt[0][lev] : 0);
       for (int l = 0; l < lev; ++l) idx += sh.lvl_cnt[0][l] + sh.lvl_cnt[1][l];
       sh.out_idx[t] = idx;
-      sh.pos[lev * PRUNE_SMALL + key_creation(key)] = (uint8_t)idx;
+      sh.sm.pos[lev * PRUNE_SMALL + key_creation(key)] = (uint8_t)idx;
     }
     __syncthreads();
     if (t < n_best) {
       int parent = 0;
       if (lev > 0) {
-        const int v = sh.pos[(lev - 1) * PRUNE_SMALL + sh.best_par[bcur][t]];
+        const int v = sh.sm.pos[(lev - 1) * PRUNE_SMALL + sh.best_par[bcur][t]];
         parent = v == 0xFF ? -2 : v;                   // -2 only if the set were not ancestor-closed
       }
       const int idx = sh.out_idx[t];
@@ -891,6 +1005,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   // ancestor mask: built in LDS (the expansion keys are no longer needed), written out once
   uint8_t *mk = reinterpret_cast<uint8_t *>(sh.keys);
   const int cells = budget * budget;
+  __syncthreads();                     // short-level mode: pos[] lives in the same memory and was just read
   for (int i = t; i < (cells + 3) / 4; i += PRUNE_THREADS) reinterpret_cast<uint32_t *>(mk)[i] = 0;
   __syncthreads();
   if (t < n_nodes) {

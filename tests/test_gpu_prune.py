@@ -48,9 +48,13 @@ def _compare(case, model, params, tokens, parents, mask, n_nodes):
     (3, 8, 13, 20, 60, 64),      # largest k whose possible contexts are all resolved up front
     (3, 8, 14, 20, 60, 64),      # smallest k that looks up level by level
     (2, 16, 12, 12, 100, 32),    # bigram model, deepest draft
-    (3, 8, 8, 32, 60, 64),       # 256 expansions per level: the most the single-wavefront level loop takes
+    (3, 8, 8, 32, 60, 64),       # 256 expansions per level: the most with four scores per lane
     (3, 8, 8, 32, 128, 64),      # ... with more than 64 of them kept per level (two ranking passes)
-    (3, 8, 9, 29, 60, 64),       # 261 expansions: just beyond it
+    (3, 8, 9, 29, 60, 64),       # 261 expansions: eight scores per lane in the single-wavefront loop
+    (3, 8, 12, 40, 100, 64),     # 480 expansions, every context resolved up front
+    (3, 8, 16, 32, 60, 64),      # 512 expansions (the most that loop takes), rows up front, scores level by level
+    (3, 8, 19, 27, 60, 64),      # 513 expansions: ranking by counting over all threads
+    (3, 16, 30, 17, 60, 16),     # more possible contexts than rows fit: one probe per beam entry and level
 ])
 def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
     params = otp.PruneParams(k=k, beam_w=w, budget=budget)
