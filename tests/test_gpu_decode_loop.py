@@ -63,8 +63,13 @@ def test_single_sequence_decode_loop(name, tol):
     cached, taus = 0, []
     while n + cfg.K + 1 <= cfg.ctx:
         tail = np.asarray(seq[-(cfg.n_gram - 1):], dtype=np.int32)
-        logits = ctx.draft_forward(h_dev, n, cfg.K, n_cached=cached)
-        ids, scores = ctx.topk(logits, cfg.topk, 1e-9)
+        if name == "C1":
+            logits = ctx.draft_forward(h_dev, n, cfg.K, n_cached=cached)
+            ids, scores = ctx.topk(logits, cfg.topk, 1e-9)
+        else:       # bf16: forward and top-k as one call (the LM head selects its candidates itself)
+            logits = torch.empty((cfg.K, cfg.vocab), dtype=torch.float32, device="cuda")
+            ids, scores = ctx.draft_forward_topk(h_dev, n, cfg.K, cfg.topk, 1e-9, n_cached=cached,
+                                                 logits_out=logits)
         tree_dev = table.tree_prune(ids, scores, torch.from_numpy(tail).cuda(), gp)
         tree = [t.cpu().numpy() for t in tree_dev]
         ref_tree = _step_checks(cfg, model, op, logits.cpu().numpy(),
@@ -119,9 +124,14 @@ def test_batched_decode_loop_with_diverging_lengths():
         if max(lens) + cfg.K + 1 > cfg.ctx:
             break
         tails = np.stack([np.asarray(s[-(cfg.n_gram - 1):], dtype=np.int32) for s in seqs])
-        logits = ctx.draft_forward_batched(devs, lens, cached, cfg.K)          # [B][K][vocab]
-        ids, scores = ctx.topk(logits.reshape(B * cfg.K, -1), cfg.topk, 1e-9)
-        ids, scores = ids.reshape(B, cfg.K, -1), scores.reshape(B, cfg.K, -1)
+        logits = torch.empty((B, cfg.K, cfg.vocab), dtype=torch.float32, device="cuda")
+        if it % 2 == 0:
+            ctx.draft_forward_batched(devs, lens, cached, cfg.K, out=logits)
+            ids, scores = ctx.topk(logits.reshape(B * cfg.K, -1), cfg.topk, 1e-9)
+            ids, scores = ids.reshape(B, cfg.K, -1), scores.reshape(B, cfg.K, -1)
+        else:       # every other iteration through the combined call
+            ids, scores = ctx.draft_forward_topk_batched(devs, lens, cached, cfg.K, cfg.topk, 1e-9,
+                                                         logits_out=logits)
         tk, pr, mk, nn = table.tree_prune(ids, scores, torch.from_numpy(tails).cuda(), gp)
         refs, targets = [], []
         for b in range(B):
