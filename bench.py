@@ -354,12 +354,15 @@ def main() -> int:
     def prune():
         table.tree_prune(tk[0][None], tk[1][None], tail, params, out=tree)
 
-    # bf16 contexts without the front end: the LM head selects the candidates itself and the
-    # logits never travel through HBM (dart_draft_forward_topk); otherwise the two calls
-    fused = cfg.dtype == "bf16" and not fe
+    # bf16 contexts: the LM head selects the candidates itself and the logits never travel through
+    # HBM (dart_draft_forward_topk, dart_draft_forward_features_topk); fp32: the two calls
+    fused = cfg.dtype == "bf16"
 
     def forward_topk():
-        ctx.draft_forward_topk(h_dev, n, K, k, 1e-9, n_cached=n - args.n_new, out=tk)
+        if fe:
+            ctx.draft_forward_features_topk(h_dev, tok_dev, n, K, k, 1e-9, n_cached=n - args.n_new, out=tk)
+        else:
+            ctx.draft_forward_topk(h_dev, n, K, k, 1e-9, n_cached=n - args.n_new, out=tk)
 
     def step_two_call():
         forward(n - args.n_new)

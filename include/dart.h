@@ -189,6 +189,15 @@ dart_status dart_draft_forward_features(dart_ctx *ctx, int seq, const void *feat
                                         const int32_t *next_tokens, int ctx_len, int n_cached,
                                         int K, float *logits_out, void *stream);
 
+/* dart_draft_forward_features followed by dart_topk on its K rows, as one call: what
+ * dart_draft_forward_topk is to dart_draft_forward (same selection inside the LM head on bf16
+ * contexts with K <= 8, same outputs; Sec. 3.2 + Alg. 1 "Top-k_i tokens from l_i").
+ * Errors: as dart_draft_forward_features and dart_topk (ARG also for NULL ids_out / scores_out). */
+dart_status dart_draft_forward_features_topk(dart_ctx *ctx, int seq, const void *features,
+                                             const int32_t *next_tokens, int ctx_len, int n_cached,
+                                             int K, int k, float eps, float *logits_out,
+                                             int32_t *ids_out, float *scores_out, void *stream);
+
 /* Same for `batch` sequences in slots 0..batch-1 (ragged lengths).
  *   hidden      HOST array of `batch` device pointers, each [ctx_len[b]][d]
  *   ctx_len, n_cached   HOST arrays [batch]

@@ -12,7 +12,7 @@ _LIB = None
 
 EXPORTED_SYMBOLS = (
     "dart_status_str", "dart_create", "dart_destroy", "dart_reset", "dart_draft_forward",
-    "dart_draft_forward_topk", "dart_draft_forward_topk_batched",
+    "dart_draft_forward_topk", "dart_draft_forward_topk_batched", "dart_draft_forward_features_topk",
     "dart_draft_forward_features", "dart_draft_forward_features_batched",
     "dart_draft_forward_batched", "dart_topk", "dart_topk_static", "dart_ngram_create", "dart_ngram_destroy",
     "dart_ngram_set_backoff",
@@ -89,6 +89,7 @@ def load_library() -> C.CDLL:
     lib.dart_draft_forward.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
     lib.dart_draft_forward_topk.argtypes = [vp, i32, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp]
     lib.dart_draft_forward_features.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp]
+    lib.dart_draft_forward_features_topk.argtypes = [vp, i32, vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp]
     lib.dart_draft_forward_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
                                                C.POINTER(C.c_int32), i32, vp, vp]
     lib.dart_draft_forward_topk_batched.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(C.c_int32),
@@ -226,6 +227,21 @@ class DraftContext:
                                                      next_tokens.data_ptr(), ctx_len, n_cached, K,
                                                      out.data_ptr(), _stream_ptr(stream)),
                "dart_draft_forward_features")
+        return out
+
+    def draft_forward_features_topk(self, features, next_tokens, ctx_len: int, K: int, k: int,
+                                    eps: float = 1e-9, n_cached: int = 0, seq: int = 0, logits_out=None,
+                                    out=None, stream=None):
+        """dart_draft_forward_features_topk: the front-end forward and the per-row top-k in one call;
+        returns (ids [K][k] int32, scores [K][k] fp32); logits are written only if logits_out is given."""
+        torch = _torch()
+        if out is None:
+            out = (torch.empty((K, k), dtype=torch.int32, device=features.device),
+                   torch.empty((K, k), dtype=torch.float32, device=features.device))
+        _check(self._lib.dart_draft_forward_features_topk(
+            self._h, seq, features.data_ptr(), next_tokens.data_ptr(), ctx_len, n_cached, K, k, eps,
+            logits_out.data_ptr() if logits_out is not None else None, out[0].data_ptr(), out[1].data_ptr(),
+            _stream_ptr(stream)), "dart_draft_forward_features_topk")
         return out
 
     def draft_forward_batched(self, hiddens, ctx_lens, n_cached, K: int, out=None, stream=None):

@@ -296,7 +296,7 @@ hipError_t build(dart_ctx *c, const dart_weights *w) {
   }
   c->max_rows = g.max_batch * g.max_K;
   c->topk_chunks_max = topk_chunks(g.vocab);
-  if (g.dtype == DART_BF16 && !g.front_end)
+  if (g.dtype == DART_BF16)
     c->lm_select_wgs = gemv_bf16_select_wgs(c->wlm, (g.vocab + 15) / 16, std::min(g.max_K, 8));
   c->topk_chunks_max = std::max(c->topk_chunks_max, c->lm_select_wgs);
   // logits of one group of sequences, for the combined calls when the caller passes no buffer
@@ -675,17 +675,12 @@ dart_status dart_draft_forward(dart_ctx *c, int seq, const void *hidden, int ctx
   return DART_OK;
 }
 
-dart_status dart_draft_forward_topk(dart_ctx *c, int seq, const void *hidden, int ctx_len, int n_cached,
-                                    int K, int k, float eps, float *logits_out, int32_t *ids_out,
-                                    float *scores_out, void *stream) {
-  float dummy = 0.f;
-  dart_status s = check_forward_args(c, seq, hidden, ctx_len, n_cached, K, &dummy);
-  if (s != DART_OK) return s;
+// Shared body of the two single-sequence combined calls (the job carries tokens with the front end).
+static dart_status forward_topk_one(dart_ctx *c, const SeqJob &job, int K, int k, float eps,
+                                    float *logits_out, int32_t *ids_out, float *scores_out, void *stream) {
   if (!ids_out || !scores_out) return DART_ERR_ARG;
   if (k < 1 || k > DART_MAX_TOPK || k > c->cfg.vocab) return DART_ERR_ARG;
-  if (c->cfg.front_end) return DART_ERR_STATE;
-  const SeqJob job{seq, hidden, ctx_len, n_cached};
-  c->cached_rows[seq] = 0;           // a failed launch sequence leaves the slot undefined
+  c->cached_rows[job.slot] = 0;      // a failed launch sequence leaves the slot undefined
   hipError_t e;
   if (c->lm_select_wgs > 0 && K <= 8) {
     const FusedCand fc{k, eps, ids_out, scores_out};
@@ -699,8 +694,33 @@ dart_status dart_draft_forward_topk(dart_ctx *c, int seq, const void *hidden, in
       e = launch_topk(c, logits, K, c->cfg.vocab, k, eps, ids_out, scores_out, (hipStream_t)stream);
   }
   if (e != hipSuccess) return from_hip(e);
-  c->cached_rows[seq] = ctx_len;
+  c->cached_rows[job.slot] = job.n;
   return DART_OK;
+}
+
+dart_status dart_draft_forward_topk(dart_ctx *c, int seq, const void *hidden, int ctx_len, int n_cached,
+                                    int K, int k, float eps, float *logits_out, int32_t *ids_out,
+                                    float *scores_out, void *stream) {
+  float dummy = 0.f;
+  dart_status s = check_forward_args(c, seq, hidden, ctx_len, n_cached, K, &dummy);
+  if (s != DART_OK) return s;
+  if (c->cfg.front_end) return DART_ERR_STATE;
+  const SeqJob job{seq, hidden, ctx_len, n_cached};
+  return forward_topk_one(c, job, K, k, eps, logits_out, ids_out, scores_out, stream);
+}
+
+dart_status dart_draft_forward_features_topk(dart_ctx *c, int seq, const void *features,
+                                             const int32_t *next_tokens, int ctx_len, int n_cached,
+                                             int K, int k, float eps, float *logits_out,
+                                             int32_t *ids_out, float *scores_out, void *stream) {
+  float dummy = 0.f;
+  dart_status s = check_forward_args(c, seq, features, ctx_len, n_cached, K, &dummy);
+  if (s != DART_OK) return s;
+  if (!next_tokens) return DART_ERR_ARG;
+  if (!c->cfg.front_end) return DART_ERR_STATE;
+  SeqJob job{seq, features, ctx_len, n_cached};
+  job.tokens = next_tokens;
+  return forward_topk_one(c, job, K, k, eps, logits_out, ids_out, scores_out, stream);
 }
 
 // Shared body of the two batched entry points (tokens = null without the front end).

@@ -95,6 +95,8 @@ int main() {
   EXPECT(dart_draft_forward_batched(nullptr, 1, nullptr, nullptr, nullptr, 1, nullptr, nullptr) == DART_ERR_ARG);
   EXPECT(dart_topk(nullptr, nullptr, 1, 1, 1, 1e-9f, nullptr, nullptr, nullptr) == DART_ERR_ARG);
   EXPECT(dart_draft_forward_topk(nullptr, 0, nullptr, 1, 0, 1, 1, 1e-9f, nullptr, nullptr, nullptr, nullptr) == DART_ERR_ARG);
+  EXPECT(dart_draft_forward_features_topk(nullptr, 0, nullptr, nullptr, 1, 0, 1, 1, 1e-9f, nullptr, nullptr, nullptr,
+                                          nullptr) == DART_ERR_ARG);
   EXPECT(dart_draft_forward_topk_batched(nullptr, 1, nullptr, nullptr, nullptr, 1, 1, 1e-9f, nullptr, nullptr, nullptr,
                                          nullptr) == DART_ERR_ARG);
 

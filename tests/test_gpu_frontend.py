@@ -77,10 +77,16 @@ def test_front_end_growing_prefix_and_entry_point_guards():
     with pytest.raises(dart.DartError) as ei:
         ctx.draft_forward(f_dev, 10, 2)                      # fused-input call on a front-end context
     assert ei.value.status == 5
+    with pytest.raises(dart.DartError) as ei:
+        ctx.draft_forward_topk(f_dev, 10, 2, 3)
+    assert ei.value.status == 5
     ctx.close()
     plain = dart.DraftContext(cfg, ds.make_weights(cfg, 6100))
     with pytest.raises(dart.DartError) as ei:
         plain.draft_forward_features(f_dev, t_dev, 10, 2)
+    assert ei.value.status == 5
+    with pytest.raises(dart.DartError) as ei:
+        plain.draft_forward_features_topk(f_dev, t_dev, 10, 2, 3)
     assert ei.value.status == 5
     plain.close()
 
@@ -100,6 +106,18 @@ def test_front_end_full_size_1p7b_shapes():
     assert ok, msg
     warm = ctx.draft_forward_features(f_dev, t_dev, cfg.ctx, cfg.K, n_cached=cfg.ctx - 4).cpu().numpy()
     np.testing.assert_array_equal(warm, cold)
+    # forward + top-k as one call: the same logits, candidates bit-exact against the full sort
+    from oracle import topk as otk
+    lg = torch.empty((cfg.K, cfg.vocab), dtype=torch.float32, device="cuda")
+    ids, scores = ctx.draft_forward_features_topk(f_dev, t_dev, cfg.ctx, cfg.K, cfg.topk, 1e-9,
+                                                  n_cached=cfg.ctx - 4, logits_out=lg)
+    np.testing.assert_array_equal(lg.cpu().numpy(), cold)
+    ref_ids, ref_scores = otk.topk_rows(cold, cfg.topk, 1e-9)
+    np.testing.assert_array_equal(ids.cpu().numpy(), ref_ids)
+    np.testing.assert_allclose(scores.cpu().numpy(), ref_scores, rtol=0, atol=1e-5)
+    ids2, scores2 = ctx.draft_forward_features_topk(f_dev, t_dev, cfg.ctx, cfg.K, cfg.topk, 1e-9,
+                                                    n_cached=cfg.ctx - 1)
+    assert torch.equal(ids2, ids) and torch.equal(scores2, scores)
     ctx.close()
 
 
