@@ -58,7 +58,8 @@ def _compare(case, model, params, tokens, parents, mask, n_nodes):
 ])
 def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
     params = otp.PruneParams(k=k, beam_w=w, budget=budget)
-    n_cases = 6 if k * w > 1000 else 24
+    # 256 independent planted cases at the headline presets' shape, 64 at the other presets', fewer elsewhere
+    n_cases = 256 if (K, k, w, budget) == (8, 10, 20, 60) else (64 if (k, w) in ((4, 4), (8, 20)) else (6 if k * w > 1000 else 24))
     for seed in range(n_cases):
         case = ds.make_prune_case(7000 + seed, vocab=151936, K=K, k=k, n_gram=n_gram, S=S)
         model = NgramModel(n_gram, case.table.keys, case.table.succ_ids, case.table.succ_counts, 1e-9)
