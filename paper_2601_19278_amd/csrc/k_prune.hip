@@ -34,8 +34,6 @@
 // also probes for its beam entries' contexts.
 // A loaded successor is matched against its level's k candidates through a small bucketed
 // table of the candidate ids in LDS (one 16-byte read per successor instead of k compares).
-#include <type_traits>
-
 #include "common.h"
 #include "dart_internal.h"
 
