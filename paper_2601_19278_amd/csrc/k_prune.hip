@@ -15,11 +15,11 @@
 // gives the next beam (first w) and the level's contenders for the global tree (first theta),
 // which are merged into the running best-theta list.  Since the best theta of a union is the
 // best theta of (best theta of one part) + (the other part), the running list equals Alg. 1's
-// "top-theta of T" after the last level.  Three ways of ranking a level: up to 512 expansions
-// (the presets: w*k = 200; the paper's defaults: 20 * 25 = 500) -- one wavefront selects the
-// max(w, theta) expansions that matter by a threshold search and ranks only those (see the
-// kernel); up to 1024 expansions -- ranking by counting over all threads; beyond -- a bitonic
-// sort.
+// "top-theta of T" after the last level.  Ways of ranking a level: when a call's levels have at
+// most 1024 expansions (the presets: w*k = 200; the paper's defaults: 20 * 25 = 500) -- one
+// wavefront selects the max(w, theta) expansions that matter by a threshold search and ranks
+// only those (see the kernel); otherwise -- ranking by counting over all threads for the levels
+// of up to 1024 expansions (the first ones), a bitonic sort beyond.
 //
 // N-gram lookups.  The context a beam entry presents at level L is the last N-1 tokens of its
 // path: (candidate a of level L-2, candidate b of level L-1) for a trigram.  Which paths
@@ -43,7 +43,7 @@ constexpr int PRUNE_THREADS = 1024;    // one workgroup per sequence; many phase
 static_assert(DART_MAX_LEVEL_NODES <= 16384, "a level's pair scores share the ng array");
 constexpr int PRUNE_NG_CELLS = 16384;  // N-gram scores of all possible (context, candidate) pairs
 constexpr int PRUNE_NG_CTX = 1280;     // possible contexts of one call resolved up front
-constexpr int PRUNE_SMALL = 512;       // expansions per level the short-level loop handles (w * k)
+constexpr int PRUNE_SMALL = 1024;      // expansions per level the short-level loop handles (w * k)
 
 // Short-level mode (at most PRUNE_SMALL expansions per level): the buffers of the wavefront that
 // ranks a level.  They share their memory with the expansion keys of the general mode.
@@ -453,7 +453,7 @@ __device__ __forceinline__ void resolve_all_contexts(PruneShared &sh, const Ngra
 }
 
 // The level loop of the short-level mode (see the kernel).  NS: scores per lane of the ranking
-// wavefront (4 up to 256 expansions per level, 8 up to 512).  PRE: every N-gram score is in LDS
+// wavefront (4 up to 256 expansions per level, 8 up to 512, 16 up to 1024).  PRE: every N-gram score is in LDS
 // already (up-front mode); otherwise the scores of a level's pairs are fetched between levels.  nb, n_best, cur, bcur: beam size,
 // best-list length and the live halves of the double buffers, carried on to the emission.
 template <int NS, bool PRE>
@@ -514,7 +514,7 @@ __device__ __forceinline__ void short_levels(PruneShared &sh, const NgramTableDe
       const float wl = lw.w_logit[L], wv = lw.w_level[L];
       // scores of expansions lane, lane + 64, ... (0 = none).  Indices are clamped instead of
       // branched on, so that the dependent LDS chains overlap; e / k by a reciprocal (exact for
-      // e < 512, k <= 64: e * k < 2^16).
+      // e < 1024, k <= 64: checked exhaustively).
       uint32_t sc[NS];
       int bc[NS];                             // (beam entry << 8) | candidate
       const uint32_t inv_k = (65536u + k - 1) / k;
@@ -711,7 +711,7 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
   // Short-level mode: every level has at most PRUNE_SMALL expansions.  Ranking all w*k expansions
   // of a level by counting costs (w*k)^2 compares (and as many LDS reads), but only the best
   // max(w, theta) of them are ever used.  So one wavefront holds the level's scores in registers
-  // (four per lane up to 256 expansions, eight beyond), finds a score T at or just below that of
+  // (4, 8 or 16 per lane), finds a score T at or just below that of
   // the last expansion that matters by a bitwise search with ballots, compacts the expansions with
   // score >= T into LDS in creation order and ranks only those among themselves (32-bit
   // sortable scores, read four at a time; among equal scores the earlier creation wins, as in
@@ -728,9 +728,12 @@ __global__ __launch_bounds__(PRUNE_THREADS) void prune_kernel(
     if (beam_w * k <= 256) {
       if (pre) DART_SHORT_LEVELS(4, true);
       else DART_SHORT_LEVELS(4, false);
-    } else {
+    } else if (beam_w * k <= 512) {
       if (pre) DART_SHORT_LEVELS(8, true);
       else DART_SHORT_LEVELS(8, false);
+    } else {
+      if (pre) DART_SHORT_LEVELS(16, true);
+      else DART_SHORT_LEVELS(16, false);
     }
 #undef DART_SHORT_LEVELS
   }

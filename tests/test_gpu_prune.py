@@ -53,7 +53,9 @@ def _compare(case, model, params, tokens, parents, mask, n_nodes):
     (3, 8, 9, 29, 60, 64),       # 261 expansions: eight scores per lane in the single-wavefront loop
     (3, 8, 12, 40, 100, 64),     # 480 expansions, every context resolved up front
     (3, 8, 16, 32, 60, 64),      # 512 expansions (the most that loop takes), rows up front, scores level by level
-    (3, 8, 19, 27, 60, 64),      # 513 expansions: ranking by counting over all threads
+    (3, 8, 19, 27, 60, 64),      # 513 expansions: sixteen scores per lane
+    (3, 6, 32, 32, 128, 64),     # 1024 expansions: the most the single-wavefront loop takes
+    (3, 6, 41, 25, 60, 16),      # 1025 expansions: counting over all threads (first levels), then the sorted path
     (3, 16, 30, 17, 60, 16),     # more possible contexts than rows fit: one probe per beam entry and level
 ])
 def test_planted_cases_match_oracle(n_gram, K, k, w, budget, S):
